@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle of one transformer block (CPU only).
+
+Each test fixes the oracle to something other than itself: finite
+differences, algebraic invariants of the block definition, special cases that
+reduce to library routines (torch CPU float64 autograd), or brute-force
+scalar loops on tiny inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as Fn
+
+from oracle import block_oracle as bo
+from paper_2605_25451_amd import synth
+
+TINY = dict(hidden=16, n_q_heads=4, n_kv_heads=4, head_dim=4, mlp_hidden=24, dtype=synth.DTYPE_FP32)
+
+
+def tiny_cases():
+    vit = synth.scaled(synth.vit_tiny(), **TINY)
+    dec = synth.scaled(synth.decoder_7b(), **TINY)
+    gqa = synth.scaled(synth.decoder_8b_gqa(), **{**TINY, "n_kv_heads": 2})
+    dit = synth.scaled(synth.dit_block(), **TINY)
+    vit_causal = synth.scaled(vit, mask=synth.MASK_CAUSAL)
+    return {
+        "vit": synth.make_case(vit, [3, 5], 10, weight_std=0.3),
+        "vit_causal": synth.make_case(vit_causal, [4, 3], 11, weight_std=0.3),
+        "decoder": synth.make_case(dec, [5, 2, 4], 12, weight_std=0.3),
+        "gqa": synth.make_case(gqa, [6, 3], 13, weight_std=0.3),
+        "dit": synth.make_case(dit, [4, 4, 3], 14, weight_std=0.3),
+    }
+
+
+CASES = tiny_cases()
+
+
+def run(case, x=None, params=None, cond=None, cu=None):
+    return bo.block_forward(case.cfg, case.params if params is None else params,
+                            case.x if x is None else x,
+                            case.cu_seqlens if cu is None else cu,
+                            case.cond if cond is None else cond)
+
+
+# ------------------------------------------------------------------ P1 finite differences
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_backward_matches_central_differences(name):
+    """Loss <y, G>; every input and every parameter entry is perturbed."""
+    case = CASES[name]
+    G = case.dy.astype(np.float64)
+    y, cache = run(case)
+    dx, grads, dcond = bo.block_backward(case.cfg, case.params, cache, G)
+    eps = 1e-6
+
+    def loss(x=None, params=None, cond=None):
+        return float((run(case, x=x, params=params, cond=cond)[0] * G).sum())
+
+    def fd(arr, setter):
+        out = np.zeros(arr.shape)
+        flat = arr.astype(np.float64).ravel()
+        for i in range(flat.size):
+            for sgn in (+1, -1):
+                pert = flat.copy(); pert[i] += sgn * eps
+                out.ravel()[i] += sgn * setter(pert.reshape(arr.shape))
+        return out / (2 * eps)
+
+    def check(analytic, numeric, what):
+        scale = max(np.abs(numeric).max(), 1e-30)
+        assert np.abs(analytic - numeric).max() / scale < 2e-6, what
+
+    check(dx, fd(case.x, lambda a: loss(x=a)), "dx")
+    for k, v in case.params.items():
+        check(grads[k], fd(v, lambda a, k=k: loss(params={**case.params, k: a})), k)
+    assert set(grads) == set(case.params)
+    if case.cond is not None:
+        check(dcond, fd(case.cond, lambda a: loss(cond=a)), "dcond")
+    else:
+        assert dcond is None
+
+
+# ------------------------------------------------------------------ P2 softmax
+
+def test_softmax_rows_sum_to_one_and_mask_is_exact_zero():
+    rng = np.random.default_rng(0)
+    q, k = rng.standard_normal((9, 8)) * 3, rng.standard_normal((9, 8)) * 3
+    for causal in (False, True):
+        p = bo.attention_probs(q, k, causal)
+        assert np.abs(p.sum(-1) - 1).max() < 1e-12
+        assert (p >= 0).all()
+        if causal:
+            assert (p[np.triu_indices(9, 1)] == 0).all()
+            assert (np.diag(p) > 0).all()
+            assert p[0, 0] == 1.0
+        else:
+            assert (p > 0).all()
+
+
+def test_attention_matches_scalar_loops():
+    """Brute force with python floats on a tiny GQA case."""
+    rng = np.random.default_rng(1)
+    T, Hq, Hkv, dh = 7, 4, 2, 3
+    q = rng.standard_normal((T, Hq, dh)); k = rng.standard_normal((T, Hkv, dh))
+    v = rng.standard_normal((T, Hkv, dh)); cu = [0, 3, 7]
+    for causal in (False, True):
+        o = bo.attention_fwd(q, k, v, np.array(cu), causal)
+        for s in range(2):
+            for a in range(Hq):
+                b = a // 2
+                for i in range(cu[s], cu[s + 1]):
+                    js = [j for j in range(cu[s], cu[s + 1]) if (not causal or j <= i)]
+                    sc = [sum(q[i, a, e] * k[j, b, e] for e in range(dh)) / math.sqrt(dh) for j in js]
+                    mx = max(sc); w = [math.exp(t - mx) for t in sc]; z = sum(w)
+                    for e in range(dh):
+                        ref = sum(w[n] * v[j, b, e] for n, j in enumerate(js)) / z
+                        assert abs(o[i, a, e] - ref) < 1e-12
+
+
+# ------------------------------------------------------------------ P3 causal direction
+
+def test_causal_outputs_ignore_future_tokens():
+    case = CASES["decoder"]
+    y0, _ = run(case)
+    x2 = case.x.astype(np.float64).copy()
+    cu = case.cu_seqlens
+    t = int(cu[0]) + 2                       # perturb everything after token t of doc 0
+    x2[t + 1:cu[1], ::2] += 1.0
+    y1, _ = run(case, x=x2)
+    assert np.array_equal(y0[:t + 1], y1[:t + 1])
+    assert not np.allclose(y0[t + 1:cu[1]], y1[t + 1:cu[1]])
+    assert np.array_equal(y0[cu[1]:], y1[cu[1]:])
+
+
+def test_bidirectional_outputs_see_future_tokens():
+    case = CASES["vit"]
+    y0, _ = run(case)
+    x2 = case.x.astype(np.float64).copy()
+    x2[2, ::2] += 1.0                        # (a constant over d would be removed by LN)
+    y1, _ = run(case, x=x2)
+    assert np.abs(y0[0] - y1[0]).max() > 1e-6          # earlier token changed
+    assert np.array_equal(y0[3:], y1[3:])              # the other sequence did not
+
+
+# ------------------------------------------------------------------ P4 packing
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_packed_equals_each_sequence_alone(name):
+    case = CASES[name]
+    y, cache = run(case)
+    dx, grads, dcond = bo.block_backward(case.cfg, case.params, cache, case.dy)
+    gsum = {k: np.zeros_like(v, dtype=np.float64) for k, v in case.params.items()}
+    for s in range(case.S):
+        sub = synth.sub_case(case, [s])
+        ys, dxs, gs, dcs = bo.block_fwd_bwd(sub.cfg, sub.params, sub.x, sub.cu_seqlens, sub.dy, sub.cond)
+        lo, hi = case.cu_seqlens[s], case.cu_seqlens[s + 1]
+        # (BLAS may round differently for different row counts: not bit-equal)
+        assert np.allclose(ys, y[lo:hi], rtol=1e-12, atol=1e-13)
+        assert np.allclose(dxs, dx[lo:hi], rtol=1e-11, atol=1e-12)
+        if dcond is not None:
+            assert np.allclose(dcs[0], dcond[s], rtol=1e-12, atol=1e-14)
+        for k in gsum:
+            gsum[k] += gs[k]
+    for k in gsum:
+        assert np.allclose(gsum[k], grads[k], rtol=1e-10, atol=1e-12), k
+
+
+def test_permuting_documents_permutes_outputs():
+    case = CASES["decoder"]
+    y, _ = run(case)
+    perm = [2, 0, 1]
+    sub = synth.sub_case(case, perm)
+    yp, _ = bo.block_forward(sub.cfg, sub.params, sub.x, sub.cu_seqlens)
+    cu = case.cu_seqlens
+    ref = np.concatenate([y[cu[s]:cu[s + 1]] for s in perm])
+    assert np.allclose(ref, yp, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ P5 torch float64 autograd
+
+def _torch_block(case, S1=True):
+    """Plain composition of torch CPU float64 library routines (one sequence,
+    no RoPE, Hkv == Hq), differentiated by autograd."""
+    cfg = case.cfg
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    x = t(case.x); P = {k: t(v) for k, v in case.params.items()}
+    T, d = x.shape; H, dh, F = cfg.n_q_heads, cfg.head_dim, cfg.mlp_hidden
+
+    def norm(z, g, b):
+        if cfg.norm == synth.NORM_LAYERNORM:
+            return Fn.layer_norm(z, (d,), P[g], P[b], cfg.norm_eps)
+        return z * torch.rsqrt(z.pow(2).mean(-1, keepdim=True) + cfg.norm_eps) * P[g]
+
+    h = norm(x, "norm1_g", "norm1_b")
+    qkv = Fn.linear(h, P["w_qkv"], P.get("b_qkv"))
+    q, k, v = [z.reshape(T, H, dh).transpose(0, 1) for z in qkv.split(H * dh, dim=1)]
+    o = Fn.scaled_dot_product_attention(q, k, v, is_causal=bool(cfg.mask))
+    o = o.transpose(0, 1).reshape(T, H * dh)
+    x1 = x + Fn.linear(o, P["w_o"], P.get("b_o"))
+    h2 = norm(x1, "norm2_g", "norm2_b")
+    up = Fn.linear(h2, P["w_up"], P.get("b_up"))
+    a = Fn.gelu(up) if cfg.act == synth.ACT_GELU else Fn.silu(up[:, :F]) * up[:, F:]
+    y = x1 + Fn.linear(a, P["w_down"], P.get("b_down"))
+    (y * torch.tensor(case.dy, dtype=torch.float64)).sum().backward()
+    return y.detach().numpy(), x.grad.numpy(), {k: v.grad.numpy() for k, v in P.items()}
+
+
+@pytest.mark.parametrize("kind", ["vit", "vit_causal", "decoder_norope"])
+def test_single_sequence_matches_torch_autograd(kind):
+    if kind == "decoder_norope":
+        cfg = synth.scaled(synth.decoder_7b(), **TINY, rope=0)
+    else:
+        cfg = CASES[kind].cfg
+    case = synth.make_case(cfg, [11], 21, weight_std=0.3)
+    y, dx, grads, _ = bo.block_fwd_bwd(cfg, case.params, case.x, case.cu_seqlens, case.dy)
+    ty, tdx, tg = _torch_block(case)
+    assert np.allclose(y, ty, rtol=1e-11, atol=1e-12)
+    assert np.allclose(dx, tdx, rtol=1e-10, atol=1e-11)
+    for k in grads:
+        assert np.allclose(grads[k], tg[k], rtol=1e-10, atol=1e-11), k
+
+
+# ------------------------------------------------------------------ P6 GQA
+
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    case = CASES["gqa"]
+    cfg = case.cfg
+    Hq, Hkv, dh, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+    grp = Hq // Hkv
+    w = case.params["w_qkv"]
+    wq, wk, wv = w[:Hq * dh], w[Hq * dh:(Hq + Hkv) * dh], w[(Hq + Hkv) * dh:]
+    rep = lambda m: np.repeat(m.reshape(Hkv, dh, d), grp, axis=0).reshape(Hq * dh, d)
+    mha_cfg = synth.scaled(cfg, n_kv_heads=Hq)
+    mha_params = {**case.params, "w_qkv": np.concatenate([wq, rep(wk), rep(wv)])}
+    y, dx, g, _ = bo.block_fwd_bwd(cfg, case.params, case.x, case.cu_seqlens, case.dy)
+    y2, dx2, g2, _ = bo.block_fwd_bwd(mha_cfg, mha_params, case.x, case.cu_seqlens, case.dy)
+    assert np.allclose(y, y2, rtol=1e-12, atol=1e-13)
+    assert np.allclose(dx, dx2, rtol=1e-11, atol=1e-12)
+    fold = lambda m: m.reshape(Hkv, grp, dh, d).sum(axis=1).reshape(Hkv * dh, d)
+    gw = g2["w_qkv"]
+    folded = np.concatenate([gw[:Hq * dh], fold(gw[Hq * dh:2 * Hq * dh]), fold(gw[2 * Hq * dh:])])
+    assert np.allclose(g["w_qkv"], folded, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ P7 RoPE
+
+def test_rope_preserves_pair_norms_and_identity_at_position_zero():
+    rng = np.random.default_rng(3)
+    t = rng.standard_normal((6, 2, 8))
+    theta = bo.rope_angles(np.arange(6), 8, 10000.0)
+    r = bo.rope_apply(t, theta)
+    n0 = t[..., :4] ** 2 + t[..., 4:] ** 2
+    n1 = r[..., :4] ** 2 + r[..., 4:] ** 2
+    assert np.allclose(n0, n1, rtol=1e-13)
+    assert np.array_equal(r[0], t[0])                       # position 0 = identity
+    back = bo.rope_apply(r, theta, sign=-1.0)
+    assert np.allclose(back, t, rtol=1e-13, atol=1e-14)
+    # the angle table: theta[p,i] = p * base^(-2i/dh), written out
+    for pos in (1, 5):
+        for i in range(4):
+            assert abs(theta[pos, i] - pos * 10000.0 ** (-2 * i / 8)) < 1e-15
+    # first pair of token 1 rotates by exactly 1 radian
+    assert abs(r[1, 0, 0] - (t[1, 0, 0] * math.cos(1) - t[1, 0, 4] * math.sin(1))) < 1e-14
+    assert abs(r[1, 0, 4] - (t[1, 0, 4] * math.cos(1) + t[1, 0, 0] * math.sin(1))) < 1e-14
+
+
+def test_rope_scores_depend_only_on_relative_position():
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((5, 1, 8)); k = rng.standard_normal((5, 1, 8))
+    s = []
+    for shift in (0, 7):
+        th = bo.rope_angles(np.arange(5) + shift, 8, 10000.0)
+        s.append(bo.rope_apply(q, th)[:, 0] @ bo.rope_apply(k, th)[:, 0].T)
+    assert np.allclose(s[0], s[1], rtol=1e-11, atol=1e-12)
+
+
+def test_positions_restart_at_every_sequence():
+    assert bo.positions_in_sequence(np.array([0, 3, 5, 9])).tolist() == [0, 1, 2, 0, 1, 0, 1, 2, 3]
+
+
+# ------------------------------------------------------------------ P8 norms
+
+def test_norm_invariances():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((4, 12)); g = rng.standard_normal(12); b = rng.standard_normal(12)
+    h, _ = bo.layernorm_fwd(x, g, b, 1e-5)
+    h2, _ = bo.layernorm_fwd(x + 3.7, g, b, 1e-5)
+    assert np.allclose(h, h2, rtol=1e-10, atol=1e-12)
+    ref = Fn.layer_norm(torch.tensor(x), (12,), torch.tensor(g), torch.tensor(b), 1e-5).numpy()
+    assert np.allclose(h, ref, rtol=1e-12, atol=1e-13)
+    r, _ = bo.rmsnorm_fwd(x, g, 0.0)
+    r2, _ = bo.rmsnorm_fwd(5.0 * x, g, 0.0)
+    assert np.allclose(r, r2, rtol=1e-12)
+    assert np.allclose((r / g) ** 2, x ** 2 / (x ** 2).mean(-1, keepdims=True), rtol=1e-12)
+
+
+def test_first_token_of_causal_document_outputs_its_value():
+    rng = np.random.default_rng(6)
+    q = rng.standard_normal((6, 2, 4)); k = rng.standard_normal((6, 2, 4)); v = rng.standard_normal((6, 2, 4))
+    o = bo.attention_fwd(q, k, v, np.array([0, 2, 6]), True)
+    assert np.array_equal(o[0], v[0]) and np.array_equal(o[2], v[2])
+
+
+def test_activation_closed_forms():
+    z = np.array([-3.0, -1.0, 0.0, 0.5, 2.0])
+    for zi, gi in zip(z, bo.gelu(z)):
+        assert abs(gi - 0.5 * zi * (1 + math.erf(zi / math.sqrt(2)))) < 1e-15
+    assert bo.gelu(np.array([0.0]))[0] == 0.0
+    assert abs(bo.gelu_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+    assert abs(bo.silu(np.array([1.0]))[0] - 1 / (1 + math.exp(-1))) < 1e-15
+    assert abs(bo.silu_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+    e = 1e-6
+    assert np.allclose(bo.gelu_grad(z), (bo.gelu(z + e) - bo.gelu(z - e)) / (2 * e), atol=1e-9)
+    assert np.allclose(bo.silu_grad(z), (bo.silu(z + e) - bo.silu(z - e)) / (2 * e), atol=1e-9)
+
+
+# ------------------------------------------------------------------ P9 adaLN
+
+def test_adaln_zero_is_the_identity():
+    case = CASES["dit"]
+    params = {**case.params, "w_ada": np.zeros_like(case.params["w_ada"]),
+              "b_ada": np.zeros_like(case.params["b_ada"])}
+    y, cache = run(case, params=params)
+    assert np.array_equal(y, case.x.astype(np.float64))
+    dx, _, _ = bo.block_backward(case.cfg, params, cache, case.dy)
+    assert np.array_equal(dx, case.dy.astype(np.float64))
+
+
+def test_adaln_unit_gate_equals_plain_prenorm_block():
+    case = CASES["dit"]
+    d = case.cfg.hidden
+    b = np.zeros(6 * d); b[2 * d:3 * d] = 1.0; b[5 * d:] = 1.0      # gates 1, shifts/scales 0
+    params = {**case.params, "w_ada": np.zeros_like(case.params["w_ada"]), "b_ada": b}
+    y, _ = run(case, params=params)
+    plain_cfg = synth.scaled(case.cfg, norm=synth.NORM_LAYERNORM)
+    plain = {k: v for k, v in case.params.items() if k not in ("w_ada", "b_ada")}
+    plain.update(norm1_g=np.ones(d), norm1_b=np.zeros(d), norm2_g=np.ones(d), norm2_b=np.zeros(d))
+    y2, _ = bo.block_forward(plain_cfg, plain, case.x, case.cu_seqlens)
+    assert np.allclose(y, y2, rtol=1e-13, atol=1e-14)
