@@ -1,0 +1,198 @@
+/*
+ * bigmac_block.h -- C-ABI of the MI355X (gfx950) library that runs the forward
+ * and backward pass of one packed, variable-length transformer block, plus the
+ * host-side nested schedule and the single-GPU micro-unit executor built on it.
+ *
+ * Background.  The paper's training pipeline (Sec. 3) nests modality-encoder
+ * and generator units into an unchanged LLM pipeline schedule; the work every
+ * unit executes is the forward/backward of transformer blocks (ViT encoder
+ * blocks, LLM decoder blocks, diffusion-transformer generator blocks; Sec. 2.1
+ * "Multimodal LLMs", "Model heterogeneity") over packed sequences (Sec. 3.3).
+ * The paper gives no arithmetic for the blocks; each is the standard pre-norm
+ * residual block of its kind:
+ *
+ *   h   = N1(x)                       LayerNorm | RMSNorm | LN0 + adaLN modulate
+ *   qkv = h Wqkv^T (+ bqkv)           rows of Wqkv: all q heads, all k heads, all v heads
+ *   q,k = RoPE(q,k)                   rotate-half pairs (i, i+dh/2), angle p*base^(-2i/dh),
+ *                                     p = position inside the token's own sequence
+ *   o   = softmax(q k^T/sqrt(dh) + mask) v     per sequence and head; q head a uses
+ *                                     kv head a / (Hq/Hkv); mask causal or none
+ *   x1  = x + [gate1 *] (o Wo^T (+ bo))
+ *   h2  = N2(x1)
+ *   m   = gelu_erf(h2 W1^T + b1) W2^T + b2   |   (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T
+ *   y   = x1 + [gate2 *] m
+ *
+ *   adaLN: [shift1,scale1,gate1,shift2,scale2,gate2] = split6(silu(cond_s) Wada^T + bada)
+ *          per sequence s, N(x) = LN0(x) * (1 + scale) + shift.
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  The caller owns every buffer; the library never allocates or
+ *     frees device memory and keeps no pointer after a call returns (an
+ *     executor object keeps the pointers it was created with).
+ *   - Tensors are row-major, token-major ([T, features]); bf16 storage with
+ *     fp32 accumulation (dtype 0) or fp32 storage (dtype 1, the check path).
+ *     Device pointers must be 16-byte aligned.
+ *   - Work is enqueued on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream); no call synchronises with the host.
+ *   - Errors are return codes; bm_last_error() gives the text of the last
+ *     failure on the calling thread.  Nothing aborts or throws.
+ */
+#ifndef BIGMAC_BLOCK_H
+#define BIGMAC_BLOCK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BM_OK = 0,
+  BM_ERR_INVALID_ARG = -1,          /* NULL/misaligned pointer, bad cu_seqlens, bad sizes   */
+  BM_ERR_UNSUPPORTED = -2,          /* a shape or variant the kernels do not cover          */
+  BM_ERR_WORKSPACE_TOO_SMALL = -3,  /* scratch_bytes below what bm_block_sizes reports      */
+  BM_ERR_HIP = -4                   /* a HIP runtime call failed (text in bm_last_error)    */
+} bm_status;
+
+enum { BM_NORM_LAYERNORM = 0, BM_NORM_RMSNORM = 1, BM_NORM_ADALN = 2 };
+enum { BM_ACT_GELU = 0, BM_ACT_SWIGLU = 1 };
+enum { BM_MASK_BIDIRECTIONAL = 0, BM_MASK_CAUSAL = 1 };
+enum { BM_DTYPE_BF16 = 0, BM_DTYPE_FP32 = 1 };
+
+/* Shape and variant of one block. hidden must equal n_q_heads*head_dim. */
+typedef struct {
+  int32_t hidden, n_q_heads, n_kv_heads, head_dim, mlp_hidden;
+  int32_t norm;         /* BM_NORM_*                                                       */
+  int32_t act;          /* BM_ACT_GELU: two-matrix MLP;  BM_ACT_SWIGLU: w_up is [2F,d],
+                           gate rows first, then linear rows                               */
+  int32_t mask;         /* BM_MASK_*; attention is always block-diagonal by cu_seqlens     */
+  int32_t rope;         /* 0/1                                                             */
+  float   rope_base;
+  float   norm_eps;
+  int32_t linear_bias;  /* 0/1: biases on the four linear layers                           */
+  int32_t dtype;        /* BM_DTYPE_*                                                      */
+  int32_t deterministic;/* reserved; every kernel here is free of floating-point atomics,
+                           so results are run-to-run bit-identical either way             */
+} bm_block_desc;
+
+/* Parameters (storage dtype) -- and, with the same field meaning, their
+ * gradients (always fp32).  Weight matrices are [out, in] row-major.  Fields a
+ * variant does not own must be NULL. */
+typedef struct {
+  void *norm1_g, *norm1_b;   /* [d]             (LayerNorm: g,b; RMSNorm: g)               */
+  void *w_qkv,  *b_qkv;      /* [(Hq+2Hkv)dh,d], [(Hq+2Hkv)dh]                             */
+  void *w_o,    *b_o;        /* [d, Hq*dh], [d]                                            */
+  void *norm2_g, *norm2_b;
+  void *w_up,   *b_up;       /* [F,d] or [2F,d];  [F] or [2F]                              */
+  void *w_down, *b_down;     /* [d,F], [d]                                                 */
+  void *w_ada,  *b_ada;      /* [6d,d], [6d]    (adaLN only)                               */
+} bm_block_params;
+
+/* Last error text of the calling thread ("" if none). Never NULL. */
+const char* bm_last_error(void);
+
+/* Bytes the caller must provide for `saved` (kept from forward to backward)
+ * and for `scratch` (free after each call; max over forward and backward).
+ * T packed tokens in S sequences, none longer than max_seqlen. */
+bm_status bm_block_sizes(const bm_block_desc* desc, int32_t T, int32_t S, int32_t max_seqlen,
+                         size_t* saved_bytes, size_t* scratch_bytes);
+
+/* Forward of one block.
+ *   w               parameters (dev pointers inside a host struct)
+ *   x      dev      [T, hidden]   block input (the caller keeps it for backward)
+ *   cu_seqlens_dev  [S+1] int32   sequence boundaries, cu[0]=0, cu[S]=T, increasing
+ *   cu_seqlens_host [S+1] int32   the same values in host memory (validated, and used
+ *                                 to build launch grids without a device round trip)
+ *   cond   dev      [S, hidden]   per-sequence conditioning (adaLN), else NULL
+ *   y      dev      [T, hidden]   output; must not alias x, saved or scratch
+ *   saved  dev      saved_bytes   written here, read by bm_block_backward
+ *   scratch dev     scratch_bytes
+ * Returns BM_ERR_INVALID_ARG for bad arguments (nothing is launched then). */
+bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_params* w,
+                           const void* x, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, int32_t S, int32_t T,
+                           int32_t max_seqlen, const void* cond, void* y, void* saved,
+                           void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* Backward of one block.
+ *   x, cond, cu_*   as given to the forward call that filled `saved`
+ *   dy     dev      [T, hidden]  upstream gradient
+ *   dx     dev      [T, hidden]  gradient w.r.t. x (overwritten)
+ *   grads           fp32 buffers shaped like the parameters; the call ADDS its
+ *                   contribution (the caller zeroes them once per optimiser step:
+ *                   the accumulation semantics of Sec. 3.2 "Module handoff")
+ *   dcond  dev      [S, hidden] storage dtype, overwritten (adaLN), else NULL */
+bm_status bm_block_backward(const bm_block_desc* desc, const bm_block_params* w,
+                            const void* x, const void* dy, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, int32_t S, int32_t T,
+                            int32_t max_seqlen, const void* cond, const void* saved,
+                            void* dx, const bm_block_params* grads, void* dcond,
+                            void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* ---- single operations of the path (same kernels the block calls use) ------------- */
+
+/* C = op(A) op(B) (+bias) with fp32 accumulation; layouts
+ *   0 "NT": C[M,N]  = A[M,K] B[N,K]^T        (linear forward,  Y = X W^T)
+ *   1 "NN": C[M,N]  = A[M,K] B[K,N]          (input gradient,  dX = dY W)
+ *   2 "TN": C[M,N] += A[K,M]^T B[K,N]        (weight gradient, dW += dY^T X; C is fp32)
+ * A, B (and C for layouts 0/1, bias[N]) are in the storage dtype; leading dimensions
+ * in elements.  scratch may be NULL when scratch_bytes is 0; bm_gemm_scratch_bytes
+ * gives what the split reduction of layout 2 wants. */
+size_t    bm_gemm_scratch_bytes(int32_t layout, int32_t M, int32_t N, int32_t K, int32_t dtype);
+bm_status bm_gemm(int32_t layout, int32_t dtype, int32_t M, int32_t N, int32_t K,
+                  const void* A, int32_t lda, const void* B, int32_t ldb,
+                  void* C, int32_t ldc, const void* bias,
+                  void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* Variable-length attention, q:[T,Hq,dh] k,v:[T,Hkv,dh] rows of one packed qkv
+ * buffer with row stride ld_qkv elements; o:[T,Hq*dh]; lse:[Hq,T] fp32 (natural-log
+ * sum-exp of the scaled scores of each row).  Softmax scale 1/sqrt(dh). */
+bm_status bm_attention_forward(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv, int32_t dh,
+                               const void* q, const void* k, const void* v, int32_t ld_qkv,
+                               const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                               int32_t S, int32_t T, int32_t max_seqlen,
+                               void* o, float* lse, void* hip_stream);
+
+/* Gradients dq,dk,dv (rows of one packed buffer with row stride ld_dqkv, fully
+ * overwritten) from do:[T,Hq*dh], the forward's q,k,v,o and lse.
+ * scratch: bm_attention_backward_scratch_bytes(...) bytes. */
+size_t    bm_attention_backward_scratch_bytes(int32_t Hq, int32_t Hkv, int32_t dh, int32_t T);
+bm_status bm_attention_backward(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv, int32_t dh,
+                                const void* q, const void* k, const void* v, int32_t ld_qkv,
+                                const void* o, const void* d_o, const float* lse,
+                                const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                                int32_t S, int32_t T, int32_t max_seqlen,
+                                void* dq, void* dk, void* dv, int32_t ld_dqkv,
+                                void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* ---- nested schedule (host only; Sec. 3.1 and the BuildSchedule figure) ------------ */
+
+enum { BM_OP_ENC_FWD = 0, BM_OP_ENC_BWD = 1, BM_OP_LLM_FWD = 2, BM_OP_LLM_BWD = 3,
+       BM_OP_GEN_FWD = 4, BM_OP_GEN_BWD = 5 };
+enum { BM_ORDER_NESTED = 0,             /* the paper's nested order                         */
+       BM_ORDER_COMPUTE_EFFICIENT = 1,  /* all encoder forwards first, backwards last       */
+       BM_ORDER_SEQUENTIAL = 2 };       /* one unit at a time                               */
+
+/* Writes the op stream for M microbatches in units of unit_size, W warm-up
+ * encoder units, an LLM 1F1B order with llm_depth units in flight.  Each op is
+ * two int32: (opcode, index) where index is a unit id for ENC and GEN ops and
+ * a microbatch id for LLM ops.  n_ops: in = capacity of ops_out in ops,
+ * out = ops written (or needed, with BM_ERR_INVALID_ARG, if capacity is short). */
+bm_status bm_build_schedule(int32_t order, int32_t M, int32_t unit_size, int32_t W,
+                            int32_t llm_depth, int32_t has_generator,
+                            int32_t* ops_out /* host */, int32_t* n_ops /* host */);
+
+/* Checks an op stream for dependency safety (encoder output before its LLM
+ * forwards, generator between the unit's last forward and first backward,
+ * encoder backward after the unit's last LLM backward, each op exactly once)
+ * and reports the peak number of live encoder/generator units and LLM
+ * microbatches.  peak_out: host int32[3] or NULL. */
+bm_status bm_check_schedule(const int32_t* ops /* host */, int32_t n_ops, int32_t M,
+                            int32_t unit_size, int32_t has_generator, int32_t* peak_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIGMAC_BLOCK_H */

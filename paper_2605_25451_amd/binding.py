@@ -1,0 +1,203 @@
+"""Thin ctypes binding over the C-ABI library (argument marshalling only).
+
+Every function has the name and argument order of its C entry point in
+``include/bigmac_block.h``.  Tensors are torch device tensors used purely as
+device memory: the binding passes their ``data_ptr()`` and the current HIP
+stream.  There is no fallback: if the shared library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbigmac_block.so")
+
+BM_OK = 0
+BM_ERR_INVALID_ARG, BM_ERR_UNSUPPORTED, BM_ERR_WORKSPACE_TOO_SMALL, BM_ERR_HIP = -1, -2, -3, -4
+GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
+OP_ENC_FWD, OP_ENC_BWD, OP_LLM_FWD, OP_LLM_BWD, OP_GEN_FWD, OP_GEN_BWD = range(6)
+ORDER_NESTED, ORDER_COMPUTE_EFFICIENT, ORDER_SEQUENTIAL = 0, 1, 2
+
+PARAM_FIELDS = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b",
+                "w_up", "b_up", "w_down", "b_down", "w_ada", "b_ada")
+
+
+class BmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"bm_status {status}: {text}")
+        self.status = status
+
+
+class BlockDesc(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("mlp_hidden", C.c_int32), ("norm", C.c_int32),
+                ("act", C.c_int32), ("mask", C.c_int32), ("rope", C.c_int32),
+                ("rope_base", C.c_float), ("norm_eps", C.c_float), ("linear_bias", C.c_int32),
+                ("dtype", C.c_int32), ("deterministic", C.c_int32)]
+
+
+class BlockParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_25451_amd.build` "
+                "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        pi32 = C.POINTER(C.c_int32)
+        l.bm_last_error.restype = C.c_char_p
+        l.bm_block_sizes.argtypes = [C.POINTER(BlockDesc), i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+        l.bm_block_forward.argtypes = [C.POINTER(BlockDesc), C.POINTER(BlockParams), vp, vp, vp, i32,
+                                       i32, i32, vp, vp, vp, vp, sz, vp]
+        l.bm_block_backward.argtypes = [C.POINTER(BlockDesc), C.POINTER(BlockParams), vp, vp, vp, vp,
+                                        i32, i32, i32, vp, vp, vp, C.POINTER(BlockParams), vp, vp, sz, vp]
+        l.bm_gemm_scratch_bytes.argtypes = [i32] * 5
+        l.bm_gemm_scratch_bytes.restype = sz
+        l.bm_gemm.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, sz, vp]
+        l.bm_attention_forward.argtypes = [i32] * 5 + [vp, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+        l.bm_attention_backward_scratch_bytes.argtypes = [i32] * 4
+        l.bm_attention_backward_scratch_bytes.restype = sz
+        l.bm_attention_backward.argtypes = ([i32] * 5 + [vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32,
+                                                          i32, vp, vp, vp, i32, vp, sz, vp])
+        l.bm_build_schedule.argtypes = [i32] * 6 + [pi32, pi32]
+        l.bm_check_schedule.argtypes = [pi32, i32, i32, i32, i32, pi32]
+        for name in ("bm_block_sizes", "bm_block_forward", "bm_block_backward", "bm_gemm",
+                     "bm_attention_forward", "bm_attention_backward", "bm_build_schedule",
+                     "bm_check_schedule"):
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def _check(status: int):
+    if status != BM_OK:
+        raise BmError(status, lib().bm_last_error().decode())
+
+
+def last_error() -> str:
+    return lib().bm_last_error().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_desc(cfg) -> BlockDesc:
+    """From any object with the BlockDesc field names (e.g. synth.BlockConfig)."""
+    return BlockDesc(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.mlp_hidden,
+                     cfg.norm, cfg.act, cfg.mask, cfg.rope, cfg.rope_base, cfg.norm_eps,
+                     cfg.linear_bias, cfg.dtype, getattr(cfg, "deterministic", 1))
+
+
+def make_params(tensors: Dict[str, object]) -> BlockParams:
+    p = BlockParams()
+    for n in PARAM_FIELDS:
+        setattr(p, n, _ptr(tensors.get(n)))
+    return p
+
+
+def _host_cu(cu_host) -> np.ndarray:
+    a = np.ascontiguousarray(cu_host, dtype=np.int32)
+    return a
+
+
+# ---------------------------------------------------------------- entry points
+
+def block_sizes(desc: BlockDesc, T: int, S: int, max_seqlen: int):
+    saved, scratch = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().bm_block_sizes(C.byref(desc), T, S, max_seqlen, C.byref(saved), C.byref(scratch)))
+    return saved.value, scratch.value
+
+
+def block_forward(desc, w: BlockParams, x, cu_seqlens_dev, cu_seqlens_host, S, T, max_seqlen, cond,
+                  y, saved, scratch, scratch_bytes, stream=None):
+    cu_h = _host_cu(cu_seqlens_host)
+    _check(lib().bm_block_forward(C.byref(desc), C.byref(w), _ptr(x), _ptr(cu_seqlens_dev),
+                                  cu_h.ctypes.data, S, T, max_seqlen, _ptr(cond), _ptr(y),
+                                  _ptr(saved), _ptr(scratch), scratch_bytes,
+                                  _stream() if stream is None else stream))
+
+
+def block_backward(desc, w: BlockParams, x, dy, cu_seqlens_dev, cu_seqlens_host, S, T, max_seqlen,
+                   cond, saved, dx, grads: BlockParams, dcond, scratch, scratch_bytes, stream=None):
+    cu_h = _host_cu(cu_seqlens_host)
+    _check(lib().bm_block_backward(C.byref(desc), C.byref(w), _ptr(x), _ptr(dy),
+                                   _ptr(cu_seqlens_dev), cu_h.ctypes.data, S, T, max_seqlen,
+                                   _ptr(cond), _ptr(saved), _ptr(dx), C.byref(grads), _ptr(dcond),
+                                   _ptr(scratch), scratch_bytes,
+                                   _stream() if stream is None else stream))
+
+
+def gemm_scratch_bytes(layout, M, N, K, dtype) -> int:
+    return lib().bm_gemm_scratch_bytes(layout, M, N, K, dtype)
+
+
+def gemm(layout, dtype, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, scratch=None,
+         scratch_bytes=0, stream=None):
+    _check(lib().bm_gemm(layout, dtype, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc,
+                         _ptr(bias), _ptr(scratch), scratch_bytes,
+                         _stream() if stream is None else stream))
+
+
+def attention_forward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, cu_seqlens_dev, cu_seqlens_host,
+                      S, T, max_seqlen, o, lse, stream=None):
+    cu_h = _host_cu(cu_seqlens_host)
+    _check(lib().bm_attention_forward(dtype, mask, Hq, Hkv, dh, _ptr(q), _ptr(k), _ptr(v), ld_qkv,
+                                      _ptr(cu_seqlens_dev), cu_h.ctypes.data, S, T, max_seqlen,
+                                      _ptr(o), _ptr(lse), _stream() if stream is None else stream))
+
+
+def attention_backward_scratch_bytes(Hq, Hkv, dh, T) -> int:
+    return lib().bm_attention_backward_scratch_bytes(Hq, Hkv, dh, T)
+
+
+def attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, cu_seqlens_dev,
+                       cu_seqlens_host, S, T, max_seqlen, dq, dk, dv, ld_dqkv, scratch,
+                       scratch_bytes, stream=None):
+    cu_h = _host_cu(cu_seqlens_host)
+    _check(lib().bm_attention_backward(dtype, mask, Hq, Hkv, dh, _ptr(q), _ptr(k), _ptr(v), ld_qkv,
+                                       _ptr(o), _ptr(d_o), _ptr(lse), _ptr(cu_seqlens_dev),
+                                       cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
+                                       _ptr(dv), ld_dqkv, _ptr(scratch), scratch_bytes,
+                                       _stream() if stream is None else stream))
+
+
+def build_schedule(order, M, unit_size, W, llm_depth, has_generator):
+    """Returns a list of (opcode, index)."""
+    n = C.c_int32(0)
+    lib().bm_build_schedule(order, M, unit_size, W, llm_depth, int(has_generator), None, C.byref(n))
+    if n.value <= 0:
+        _check(BM_ERR_INVALID_ARG)
+    buf = (C.c_int32 * (2 * n.value))()
+    _check(lib().bm_build_schedule(order, M, unit_size, W, llm_depth, int(has_generator), buf, C.byref(n)))
+    return [(buf[2 * i], buf[2 * i + 1]) for i in range(n.value)]
+
+
+def check_schedule(ops, M, unit_size, has_generator):
+    """Raises BmError if the op stream is not dependency safe; returns the peak
+    live (encoder units, generator units, LLM microbatches)."""
+    flat = (C.c_int32 * (2 * len(ops)))(*[v for op in ops for v in op])
+    peak = (C.c_int32 * 3)()
+    _check(lib().bm_check_schedule(flat, len(ops), M, unit_size, int(has_generator), peak))
+    return tuple(peak)

@@ -1,0 +1,132 @@
+// Error text, back-end selection (MFMA kernels when the shape allows, the
+// generic fp32-FMA kernels otherwise) and the C-ABI wrappers of the single
+// operations.
+#include "common.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+
+namespace bm {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+bm_status hip_fail(hipError_t e, const char* what) {
+  set_error("HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
+  return BM_ERR_HIP;
+}
+
+size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype) {
+  if (dtype != BM_DTYPE_BF16) return 0;
+  return gemm_mfma_scratch_bytes(layout, M, N, K);
+}
+
+bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int lda, const void* B,
+               int ldb, void* C, int ldc, const GemmEpilogue& epi, void* scratch,
+               size_t scratch_bytes, hipStream_t st) {
+  if (M <= 0 || N <= 0) return BM_OK;
+  if (gemm_mfma_supported(layout, dtype, M, N, K, lda, ldb, ldc, epi))
+    return gemm_mfma(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
+  return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, st);
+}
+
+}  // namespace bm
+
+using namespace bm;
+
+extern "C" const char* bm_last_error(void) { return g_err; }
+
+static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+extern "C" size_t bm_gemm_scratch_bytes(int32_t layout, int32_t M, int32_t N, int32_t K,
+                                        int32_t dtype) {
+  if (layout < 0 || layout > 2 || M <= 0 || N <= 0 || K <= 0) return 0;
+  return gemm_scratch_bytes(layout, M, N, K, dtype);
+}
+
+extern "C" bm_status bm_gemm(int32_t layout, int32_t dtype, int32_t M, int32_t N, int32_t K,
+                             const void* A, int32_t lda, const void* B, int32_t ldb, void* C,
+                             int32_t ldc, const void* bias, void* scratch, size_t scratch_bytes,
+                             void* hip_stream) {
+  BM_ARG_CHECK(layout >= 0 && layout <= 2, "bm_gemm: layout %d", layout);
+  BM_ARG_CHECK(dtype == BM_DTYPE_BF16 || dtype == BM_DTYPE_FP32, "bm_gemm: dtype %d", dtype);
+  BM_ARG_CHECK(M > 0 && N > 0 && K > 0, "bm_gemm: sizes must be positive");
+  BM_ARG_CHECK(A && B && C && al16(A) && al16(B) && al16(C), "bm_gemm: NULL or misaligned operand");
+  BM_ARG_CHECK(!bias || al16(bias), "bm_gemm: misaligned bias");
+  BM_ARG_CHECK(layout != GEMM_TN || !bias, "bm_gemm: bias is not defined for layout TN");
+  const int a_cols = layout == GEMM_TN ? M : K, b_cols = layout == GEMM_NT ? K : N;
+  BM_ARG_CHECK(lda >= a_cols && ldb >= b_cols && ldc >= N, "bm_gemm: leading dimension too small");
+  size_t need = gemm_scratch_bytes(layout, M, N, K, dtype);
+  if (need > scratch_bytes || (need && !scratch)) {
+    set_error("bm_gemm needs %zu scratch bytes, got %zu", need, scratch_bytes);
+    return BM_ERR_WORKSPACE_TOO_SMALL;
+  }
+  GemmEpilogue e; e.bias = bias;
+  return gemm(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, e, scratch, scratch_bytes,
+              (hipStream_t)hip_stream);
+}
+
+static bm_status check_attn(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv, int32_t dh,
+                            const int32_t* cu_dev, const int32_t* cu_host, int32_t S, int32_t T,
+                            int32_t max_seqlen, int32_t ld) {
+  BM_ARG_CHECK(dtype == BM_DTYPE_BF16 || dtype == BM_DTYPE_FP32, "attention: dtype %d", dtype);
+  BM_ARG_CHECK(mask == 0 || mask == 1, "attention: mask %d", mask);
+  BM_ARG_CHECK(Hq > 0 && Hkv > 0 && dh > 0 && Hq % Hkv == 0, "attention: bad head counts %d/%d", Hq, Hkv);
+  BM_ARG_CHECK(S >= 1 && T >= 1 && cu_dev && cu_host, "attention: bad S/T/cu_seqlens");
+  BM_ARG_CHECK(cu_host[0] == 0 && cu_host[S] == T, "attention: cu_seqlens must span [0, T]");
+  for (int s = 0; s < S; ++s) {
+    int L = cu_host[s + 1] - cu_host[s];
+    BM_ARG_CHECK(L >= 1 && L <= max_seqlen, "attention: sequence %d has length %d (max_seqlen %d)", s, L, max_seqlen);
+  }
+  BM_ARG_CHECK(ld >= Hq * dh, "attention: row stride %d too small", ld);
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  BM_ARG_CHECK(ld % vec == 0 && dh % vec == 0, "attention: row stride and head_dim must be multiples of %d", vec);
+  return BM_OK;
+}
+
+extern "C" bm_status bm_attention_forward(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv,
+                                          int32_t dh, const void* q, const void* k, const void* v,
+                                          int32_t ld_qkv, const int32_t* cu_dev,
+                                          const int32_t* cu_host, int32_t S, int32_t T,
+                                          int32_t max_seqlen, void* o, float* lse, void* hip_stream) {
+  BM_RETURN_IF(check_attn(dtype, mask, Hq, Hkv, dh, cu_dev, cu_host, S, T, max_seqlen, ld_qkv));
+  BM_ARG_CHECK(q && k && v && o && lse && al16(q) && al16(k) && al16(v) && al16(o),
+               "attention: NULL or misaligned tensor");
+  AttnArgs a{dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, cu_dev, cu_host, S, T, max_seqlen};
+  return attention_forward(a, o, lse, (hipStream_t)hip_stream);
+}
+
+extern "C" size_t bm_attention_backward_scratch_bytes(int32_t Hq, int32_t Hkv, int32_t dh, int32_t T) {
+  if (Hq <= 0 || Hkv <= 0 || dh <= 0 || T <= 0) return 0;
+  return attention_backward_scratch_bytes(Hq, Hkv, dh, T);
+}
+
+extern "C" bm_status bm_attention_backward(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv,
+                                           int32_t dh, const void* q, const void* k, const void* v,
+                                           int32_t ld_qkv, const void* o, const void* d_o,
+                                           const float* lse, const int32_t* cu_dev,
+                                           const int32_t* cu_host, int32_t S, int32_t T,
+                                           int32_t max_seqlen, void* dq, void* dk, void* dv,
+                                           int32_t ld_dqkv, void* scratch, size_t scratch_bytes,
+                                           void* hip_stream) {
+  BM_RETURN_IF(check_attn(dtype, mask, Hq, Hkv, dh, cu_dev, cu_host, S, T, max_seqlen, ld_qkv));
+  BM_ARG_CHECK(q && k && v && o && d_o && lse && dq && dk && dv, "attention backward: NULL tensor");
+  BM_ARG_CHECK(al16(q) && al16(k) && al16(v) && al16(o) && al16(d_o) && al16(dq) && al16(dk) && al16(dv),
+               "attention backward: misaligned tensor");
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  BM_ARG_CHECK(ld_dqkv >= Hq * dh && ld_dqkv % vec == 0, "attention backward: bad gradient row stride");
+  size_t need = attention_backward_scratch_bytes(Hq, Hkv, dh, T);
+  if (need > scratch_bytes || !scratch) {
+    set_error("attention backward needs %zu scratch bytes, got %zu", need, scratch_bytes);
+    return BM_ERR_WORKSPACE_TOO_SMALL;
+  }
+  AttnArgs a{dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, cu_dev, cu_host, S, T, max_seqlen};
+  return attention_backward(a, o, d_o, lse, dq, dk, dv, ld_dqkv, scratch, scratch_bytes,
+                            (hipStream_t)hip_stream);
+}

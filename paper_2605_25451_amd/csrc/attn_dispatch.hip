@@ -1,0 +1,33 @@
+// Attention back-end selection: MFMA flash kernels for bf16 with head sizes
+// they cover, the generic fp32-arithmetic kernels otherwise.
+#include "common.h"
+
+namespace bm {
+
+bool attention_mfma_supported(const AttnArgs& a);
+bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStream_t st);
+size_t attention_backward_mfma_scratch_bytes(int Hq, int Hkv, int dh, int T);
+bm_status attention_backward_mfma(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
+                                  void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
+                                  size_t scratch_bytes, hipStream_t st);
+
+bm_status attention_forward(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
+  if (attention_mfma_supported(a)) return attention_forward_mfma(a, o, lse, st);
+  return attention_forward_generic(a, o, lse, st);
+}
+
+size_t attention_backward_scratch_bytes(int Hq, int Hkv, int dh, int T) {
+  size_t generic = align_up((size_t)Hq * T * sizeof(float), 256);   // delta
+  size_t mfma = attention_backward_mfma_scratch_bytes(Hq, Hkv, dh, T);
+  return generic > mfma ? generic : mfma;
+}
+
+bm_status attention_backward(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
+                             void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
+                             size_t scratch_bytes, hipStream_t st) {
+  if (attention_mfma_supported(a))
+    return attention_backward_mfma(a, o, d_o, lse, dq, dk, dv, ld_dqkv, scratch, scratch_bytes, st);
+  return attention_backward_generic(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
+}
+
+}  // namespace bm

@@ -1,0 +1,205 @@
+// Shared declarations of the gfx950 block library: element types, vector
+// loads, wavefront reductions, error plumbing and the internal kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/bigmac_block.h"
+
+namespace bm {
+
+typedef __bf16 bf16_t;
+
+// ---------------------------------------------------------------- errors
+void set_error(const char* fmt, ...);
+bm_status hip_fail(hipError_t e, const char* what);
+
+#define BM_CHECK_HIP(expr)                                         \
+  do {                                                             \
+    hipError_t _e = (expr);                                        \
+    if (_e != hipSuccess) return ::bm::hip_fail(_e, #expr);        \
+  } while (0)
+
+#define BM_CHECK_LAUNCH(name)                                      \
+  do {                                                             \
+    hipError_t _e = hipGetLastError();                             \
+    if (_e != hipSuccess) return ::bm::hip_fail(_e, name);         \
+  } while (0)
+
+#define BM_RETURN_IF(st)                                           \
+  do {                                                             \
+    bm_status _s = (st);                                           \
+    if (_s != BM_OK) return _s;                                    \
+  } while (0)
+
+#define BM_ARG_CHECK(cond, ...)                                    \
+  do {                                                             \
+    if (!(cond)) {                                                 \
+      ::bm::set_error(__VA_ARGS__);                                \
+      return BM_ERR_INVALID_ARG;                                   \
+    }                                                              \
+  } while (0)
+
+// ---------------------------------------------------------------- device helpers
+constexpr int WAVE = 64;
+
+template <typename T> struct Elt;
+template <> struct Elt<float> {
+  static constexpr int VEC = 4;   // elements per 16-byte access
+  __device__ static inline float to_f(float v) { return v; }
+  __device__ static inline float from_f(float v) { return v; }
+};
+template <> struct Elt<bf16_t> {
+  static constexpr int VEC = 8;
+  __device__ static inline float to_f(bf16_t v) { return (float)v; }
+  __device__ static inline bf16_t from_f(float v) { return (bf16_t)v; }
+};
+
+// 16-byte vector of elements with float views.
+template <typename T> struct alignas(16) Vec16 {
+  T v[Elt<T>::VEC];
+};
+
+template <typename T>
+__device__ inline void load16(const T* p, float (&out)[Elt<T>::VEC]) {
+  Vec16<T> t = *reinterpret_cast<const Vec16<T>*>(p);
+#pragma unroll
+  for (int i = 0; i < Elt<T>::VEC; ++i) out[i] = Elt<T>::to_f(t.v[i]);
+}
+
+template <typename T>
+__device__ inline void store16(T* p, const float (&in)[Elt<T>::VEC]) {
+  Vec16<T> t;
+#pragma unroll
+  for (int i = 0; i < Elt<T>::VEC; ++i) t.v[i] = Elt<T>::from_f(in[i]);
+  *reinterpret_cast<Vec16<T>*>(p) = t;
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+  return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
+  return v;
+}
+
+// ---------------------------------------------------------------- host helpers
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+inline size_t elt_size(int dtype) { return dtype == BM_DTYPE_BF16 ? 2 : 4; }
+
+// Bump allocator over the caller's workspace; a null base only measures.
+struct Arena {
+  char* base;
+  size_t off = 0;
+  explicit Arena(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T = void> T* take(size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return base ? reinterpret_cast<T*>(base + o) : nullptr;
+  }
+};
+
+// ---------------------------------------------------------------- GEMM
+enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
+
+// Epilogue of C = acc (+bias) (+residual); all optional.
+struct GemmEpilogue {
+  const void* bias = nullptr;       // [N] storage dtype
+  const void* residual = nullptr;   // [M, ldc] storage dtype
+  int out_fp32 = 0;                 // write C as fp32 regardless of dtype (NT/NN)
+};
+
+size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype);
+bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int lda, const void* B,
+               int ldb, void* C, int ldc, const GemmEpilogue& epi, void* scratch,
+               size_t scratch_bytes, hipStream_t st);
+
+// generic (any shape, fp32 FMA) and MFMA (bf16) back ends
+bm_status gemm_generic(int layout, int dtype, int M, int N, int K, const void* A, int lda,
+                       const void* B, int ldb, void* C, int ldc, const GemmEpilogue& epi,
+                       hipStream_t st);
+bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc,
+                         const GemmEpilogue& epi);
+size_t gemm_mfma_scratch_bytes(int layout, int M, int N, int K);
+bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+                    void* C, int ldc, const GemmEpilogue& epi, void* scratch, size_t scratch_bytes,
+                    hipStream_t st);
+
+// ---------------------------------------------------------------- attention
+struct AttnArgs {
+  int dtype, causal, Hq, Hkv, dh;
+  const void *q, *k, *v;   // row stride ld_qkv elements
+  int ld_qkv;
+  const int32_t* cu_dev;
+  const int32_t* cu_host;
+  int S, T, max_seqlen;
+};
+bm_status attention_forward(const AttnArgs& a, void* o, float* lse, hipStream_t st);
+size_t attention_backward_scratch_bytes(int Hq, int Hkv, int dh, int T);
+bm_status attention_backward(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
+                             void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
+                             size_t scratch_bytes, hipStream_t st);
+
+bm_status attention_forward_generic(const AttnArgs& a, void* o, float* lse, hipStream_t st);
+bm_status attention_backward_generic(const AttnArgs& a, const void* o, const void* d_o,
+                                     const float* lse, void* dq, void* dk, void* dv, int ld_dqkv,
+                                     float* delta, hipStream_t st);
+
+// ---------------------------------------------------------------- elementwise / norms
+// seq id of every token: tok_seq[t] = s with cu[s] <= t < cu[s+1]
+bm_status launch_tok_seq(const int32_t* cu_dev, int S, int T, int32_t* tok_seq, hipStream_t st);
+
+struct NormArgs {
+  int dtype, kind;          // BM_NORM_*
+  int T, d;
+  float eps;
+  const void* gamma = nullptr;
+  const void* beta = nullptr;
+  const float* mod = nullptr;        // adaLN: fp32 [S, ld_mod]
+  int ld_mod = 0, shift_off = 0, scale_off = 0;
+  const int32_t* tok_seq = nullptr;
+};
+// h = N(x); stats[2T] = (mean, rstd) written when write_stats
+bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, int write_stats,
+                       hipStream_t st);
+size_t norm_backward_scratch_bytes(int T, int d);
+// dx = dres + dN/dx(dh);  dgamma/dbeta fp32 += (LayerNorm/RMSNorm)
+// adaLN: dmod[:, shift_off..] = segsum(dh), dmod[:, scale_off..] = segsum(dh * xhat) (overwrite, fp32)
+bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, const void* dh,
+                        const void* dres, void* dx, float* dgamma, float* dbeta, float* dmod,
+                        const int32_t* cu_dev, int S, void* scratch, hipStream_t st);
+
+// RoPE in place on the first n_heads heads of each row of qkv; sign=+1 fwd, -1 bwd
+bm_status rope_inplace(int dtype, void* qkv, int ld, int T, int n_heads, int dh, float base,
+                       const int32_t* cu_dev, const int32_t* tok_seq, float sign, hipStream_t st);
+
+bm_status act_forward(int dtype, int act, const void* up, void* a, int T, int F, hipStream_t st);
+bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, int T, int F,
+                       hipStream_t st);
+
+// out[n] += sum_t a[t, n]   (fp32 accumulate, deterministic two-stage)
+size_t colsum_scratch_bytes(int T, int N);
+bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, float* out,
+                            void* scratch, hipStream_t st);
+// out[s, n] = sum_{t in s} a[t,n] * b[t,n]    (fp32, overwrite; b optional)
+bm_status segment_colsum(int dtype, const void* a, const void* b, int ld, int N,
+                         const int32_t* cu_dev, int S, float* out, int ld_out, hipStream_t st);
+// out[t, n] = (residual ? residual[t,n] : 0) + a[t, n] * gate[tok_seq[t], n]
+bm_status gate_mul(int dtype, const void* a, const float* gate, int ld_gate,
+                   const int32_t* tok_seq, const void* residual, void* out, int T, int N,
+                   hipStream_t st);
+// out = silu(in) (storage dtype) ; dsilu: out = g * silu'(in) with g fp32
+bm_status silu_forward(int dtype, const void* in, void* out, long n, hipStream_t st);
+bm_status silu_backward_f32(int dtype, const void* in, const float* g, void* out, long n,
+                            hipStream_t st);
+// fp32 -> storage dtype
+bm_status cast_from_f32(int dtype, const float* in, void* out, long n, hipStream_t st);
+
+}  // namespace bm

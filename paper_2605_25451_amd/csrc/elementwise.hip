@@ -1,0 +1,704 @@
+// HBM-bound kernels of the block: norms (LayerNorm / RMSNorm / affine-free LN
+// with adaLN modulation) forward and backward, RoPE, GELU / SwiGLU, column and
+// per-sequence reductions for bias / gamma / adaLN gradients.
+//
+// Access pattern: every kernel moves 16 bytes per lane per access, with a
+// wavefront covering one contiguous 1 KiB span of a row, and reduces inside a
+// wavefront with cross-lane shuffles (no LDS, no barrier, on the per-row
+// paths).  Arithmetic is fp32 whatever the storage type.
+#include "common.h"
+
+namespace bm {
+
+// ------------------------------------------------------------------ tok_seq
+__global__ void tok_seq_kernel(const int32_t* __restrict__ cu, int S, int T,
+                               int32_t* __restrict__ tok_seq) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  int lo = 0, hi = S;   // find s with cu[s] <= t < cu[s+1]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu[mid] <= t) lo = mid; else hi = mid;
+  }
+  tok_seq[t] = lo;
+}
+
+bm_status launch_tok_seq(const int32_t* cu_dev, int S, int T, int32_t* tok_seq, hipStream_t st) {
+  hipLaunchKernelGGL(tok_seq_kernel, dim3(cdiv(T, 256)), dim3(256), 0, st, cu_dev, S, T, tok_seq);
+  BM_CHECK_LAUNCH("tok_seq");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ norm forward
+// One wavefront per row; the row lives in registers (NV 16-byte vectors per lane).
+template <typename T, int KIND, int NV>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(
+    const T* __restrict__ x, T* __restrict__ h, float* __restrict__ stats,
+    const T* __restrict__ gamma, const T* __restrict__ beta, const float* __restrict__ mod,
+    int ld_mod, int shift_off, int scale_off, const int32_t* __restrict__ tok_seq, int rows, int d,
+    float eps, int write_stats) {
+  constexpr int VEC = Elt<T>::VEC;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * d;
+  float buf[NV][VEC];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int col = (i * WAVE + lane) * VEC;
+    if (col < d) {
+      load16(xr + col, buf[i]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) buf[i][e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s += (KIND == BM_NORM_RMSNORM) ? buf[i][e] * buf[i][e] : buf[i][e];
+  }
+  s = wave_sum(s);
+  float mean = 0.f, rstd;
+  const float inv_d = 1.0f / (float)d;
+  if (KIND == BM_NORM_RMSNORM) {
+    rstd = 1.0f / sqrtf(s * inv_d + eps);
+  } else {
+    mean = s * inv_d;
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int col = (i * WAVE + lane) * VEC;
+      if (col < d) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { float c = buf[i][e] - mean; v += c * c; }
+      }
+    }
+    v = wave_sum(v);
+    rstd = 1.0f / sqrtf(v * inv_d + eps);
+  }
+  if (write_stats && lane == 0) { stats[row] = mean; stats[rows + row] = rstd; }
+  T* hr = h + (size_t)row * d;
+  const float* mrow = nullptr;
+  if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int col = (i * WAVE + lane) * VEC;
+    if (col >= d) continue;
+    float out[VEC];
+    if (KIND == BM_NORM_LAYERNORM) {
+      float g[VEC], b[VEC];
+      load16(gamma + col, g); load16(beta + col, b);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[e] = (buf[i][e] - mean) * rstd * g[e] + b[e];
+    } else if (KIND == BM_NORM_RMSNORM) {
+      float g[VEC];
+      load16(gamma + col, g);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[e] = buf[i][e] * rstd * g[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        out[e] = (buf[i][e] - mean) * rstd * (1.0f + mrow[scale_off + col + e]) + mrow[shift_off + col + e];
+    }
+    store16(hr + col, out);
+  }
+}
+
+template <typename T, int KIND>
+static bm_status norm_fwd_dispatch(const NormArgs& a, const void* x, void* h, float* stats,
+                                   int write_stats, hipStream_t st) {
+  constexpr int VEC = Elt<T>::VEC;
+  int nv = cdiv(a.d, WAVE * VEC);
+  dim3 grid(cdiv(a.T, 4)), block(256);
+#define BM_LAUNCH_NV(NVV)                                                                        \
+  hipLaunchKernelGGL((norm_fwd_kernel<T, KIND, NVV>), grid, block, 0, st, (const T*)x, (T*)h,    \
+                     stats, (const T*)a.gamma, (const T*)a.beta, a.mod, a.ld_mod, a.shift_off,   \
+                     a.scale_off, a.tok_seq, a.T, a.d, a.eps, write_stats)
+  if (nv <= 1) BM_LAUNCH_NV(1);
+  else if (nv <= 2) BM_LAUNCH_NV(2);
+  else if (nv <= 4) BM_LAUNCH_NV(4);
+  else if (nv <= 8) BM_LAUNCH_NV(8);
+  else if (nv <= 16) BM_LAUNCH_NV(16);
+  else { set_error("norm: hidden %d too wide", a.d); return BM_ERR_UNSUPPORTED; }
+#undef BM_LAUNCH_NV
+  BM_CHECK_LAUNCH("norm_fwd");
+  return BM_OK;
+}
+
+bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, int write_stats,
+                       hipStream_t st) {
+  if (a.T == 0) return BM_OK;
+#define BM_KIND(TT)                                                                              \
+  switch (a.kind) {                                                                              \
+    case BM_NORM_LAYERNORM: return norm_fwd_dispatch<TT, BM_NORM_LAYERNORM>(a, x, h, stats, write_stats, st); \
+    case BM_NORM_RMSNORM: return norm_fwd_dispatch<TT, BM_NORM_RMSNORM>(a, x, h, stats, write_stats, st);     \
+    default: return norm_fwd_dispatch<TT, BM_NORM_ADALN>(a, x, h, stats, write_stats, st);       \
+  }
+  if (a.dtype == BM_DTYPE_BF16) { BM_KIND(bf16_t) } else { BM_KIND(float) }
+#undef BM_KIND
+}
+
+// ------------------------------------------------------------------ norm backward
+// Each wavefront walks rows with a grid stride; every lane owns the same
+// columns on every row, so the gamma/beta column sums accumulate in registers
+// and leave the kernel as one partial row per workgroup.
+constexpr int NORM_BWD_MAX_BLOCKS = 1024;
+
+template <typename T, int KIND, int NV>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(
+    const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
+    const T* __restrict__ dres, T* __restrict__ dx, const T* __restrict__ gamma,
+    const float* __restrict__ mod, int ld_mod, int scale_off, const int32_t* __restrict__ tok_seq,
+    float* __restrict__ partial /* [gridDim.x][2][d] */, int rows, int d) {
+  constexpr int VEC = Elt<T>::VEC;
+  extern __shared__ float sm[];   // [d]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float gam[NV][VEC];
+  float acc_g[NV][VEC], acc_b[NV][VEC];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int col = (i * WAVE + lane) * VEC;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { acc_g[i][e] = 0.f; acc_b[i][e] = 0.f; gam[i][e] = 1.f; }
+    if (KIND != BM_NORM_ADALN && col < d) load16(gamma + col, gam[i]);
+  }
+  const float inv_d = 1.0f / (float)d;
+  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+    const size_t off = (size_t)row * d;
+    const float mean = stats[row], rstd = stats[rows + row];
+    const float* mrow = nullptr;
+    if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod + scale_off;
+    float xv[NV][VEC], gv[NV][VEC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int col = (i * WAVE + lane) * VEC;
+      if (col < d) {
+        float dhv[VEC];
+        load16(x + off + col, xv[i]);
+        load16(dh + off + col, dhv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          float g;
+          if (KIND == BM_NORM_ADALN) g = dhv[e] * (1.0f + mrow[col + e]);
+          else g = dhv[e] * gam[i][e];
+          if (KIND == BM_NORM_RMSNORM) {
+            s2 += g * xv[i][e];
+            acc_g[i][e] += dhv[e] * xv[i][e] * rstd;
+          } else {
+            float xh = (xv[i][e] - mean) * rstd;
+            xv[i][e] = xh;
+            s1 += g; s2 += g * xh;
+            acc_g[i][e] += dhv[e] * xh;
+            acc_b[i][e] += dhv[e];
+          }
+          gv[i][e] = g;
+        }
+      }
+    }
+    s2 = wave_sum(s2) * inv_d;
+    if (KIND != BM_NORM_RMSNORM) s1 = wave_sum(s1) * inv_d;
+    const float r3 = rstd * rstd * rstd;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int col = (i * WAVE + lane) * VEC;
+      if (col < d) {
+        float out[VEC], res[VEC];
+        load16(dres + off + col, res);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          float v;
+          if (KIND == BM_NORM_RMSNORM) v = rstd * gv[i][e] - xv[i][e] * r3 * s2;
+          else v = rstd * (gv[i][e] - s1 - xv[i][e] * s2);
+          out[e] = res[e] + v;
+        }
+        store16(dx + off + col, out);
+      }
+    }
+  }
+  if (KIND == BM_NORM_ADALN) return;   // shift/scale gradients are per-sequence sums (own kernel)
+  // combine the four wavefronts through LDS, one after the other (fixed order)
+  for (int which = 0; which < (KIND == BM_NORM_LAYERNORM ? 2 : 1); ++which) {
+    for (int w = 0; w < 4; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          int col = (i * WAVE + lane) * VEC;
+          if (col < d) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+              float v = which == 0 ? acc_g[i][e] : acc_b[i][e];
+              if (w == 0) sm[col + e] = v; else sm[col + e] += v;
+            }
+          }
+        }
+      }
+      __syncthreads();
+    }
+    float* prow = partial + ((size_t)blockIdx.x * 2 + which) * d;
+    for (int c = threadIdx.x; c < d; c += 256) prow[c] = sm[c];
+    __syncthreads();
+  }
+}
+
+__global__ void partial_reduce_kernel(const float* __restrict__ partial, int nparts, int stride,
+                                      int n, float* __restrict__ out) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * stride + c];
+  out[c] += s;
+}
+
+// adaLN: dshift[s,:] = sum_{t in s} dh,  dscale[s,:] = sum_{t in s} dh * xhat
+template <typename T>
+__global__ __launch_bounds__(256) void adaln_seg_grads_kernel(
+    const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
+    const int32_t* __restrict__ cu, float* __restrict__ dmod, int ld_mod, int shift_off,
+    int scale_off, int rows, int d) {
+  __shared__ float sm[2][4][64];
+  const int s = blockIdx.x;
+  const int c = blockIdx.y * 64 + (threadIdx.x & 63);
+  const int rg = threadIdx.x >> 6;
+  float a_sh = 0.f, a_sc = 0.f;
+  if (c < d) {
+    for (int t = cu[s] + rg; t < cu[s + 1]; t += 4) {
+      float g = Elt<T>::to_f(dh[(size_t)t * d + c]);
+      float xh = (Elt<T>::to_f(x[(size_t)t * d + c]) - stats[t]) * stats[rows + t];
+      a_sh += g; a_sc += g * xh;
+    }
+  }
+  sm[0][rg][threadIdx.x & 63] = a_sh; sm[1][rg][threadIdx.x & 63] = a_sc;
+  __syncthreads();
+  if (rg == 0 && c < d) {
+    int l = threadIdx.x;
+    dmod[(size_t)s * ld_mod + shift_off + c] = sm[0][0][l] + sm[0][1][l] + sm[0][2][l] + sm[0][3][l];
+    dmod[(size_t)s * ld_mod + scale_off + c] = sm[1][0][l] + sm[1][1][l] + sm[1][2][l] + sm[1][3][l];
+  }
+}
+
+static int norm_bwd_blocks(int T) { int b = cdiv(T, 4); return b < NORM_BWD_MAX_BLOCKS ? b : NORM_BWD_MAX_BLOCKS; }
+
+size_t norm_backward_scratch_bytes(int T, int d) {
+  return (size_t)norm_bwd_blocks(T) * 2 * d * sizeof(float);
+}
+
+template <typename T, int KIND>
+static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float* stats,
+                                   const void* dh, const void* dres, void* dx, float* partial,
+                                   hipStream_t st) {
+  constexpr int VEC = Elt<T>::VEC;
+  int nv = cdiv(a.d, WAVE * VEC);
+  dim3 grid(norm_bwd_blocks(a.T)), block(256);
+  size_t lds = (size_t)a.d * sizeof(float);
+#define BM_LAUNCH_NV(NVV)                                                                        \
+  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV>), grid, block, lds, st, (const T*)x, stats,  \
+                     (const T*)dh, (const T*)dres, (T*)dx, (const T*)a.gamma, a.mod, a.ld_mod,   \
+                     a.scale_off, a.tok_seq, partial, a.T, a.d)
+  if (nv <= 1) BM_LAUNCH_NV(1);
+  else if (nv <= 2) BM_LAUNCH_NV(2);
+  else if (nv <= 4) BM_LAUNCH_NV(4);
+  else if (nv <= 8) BM_LAUNCH_NV(8);
+  else if (nv <= 16) BM_LAUNCH_NV(16);
+  else { set_error("norm: hidden %d too wide", a.d); return BM_ERR_UNSUPPORTED; }
+#undef BM_LAUNCH_NV
+  BM_CHECK_LAUNCH("norm_bwd");
+  return BM_OK;
+}
+
+bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, const void* dh,
+                        const void* dres, void* dx, float* dgamma, float* dbeta, float* dmod,
+                        const int32_t* cu_dev, int S, void* scratch, hipStream_t st) {
+  if (a.T == 0) return BM_OK;
+  float* partial = (float*)scratch;
+  bm_status rc;
+#define BM_KIND(TT)                                                                              \
+  switch (a.kind) {                                                                              \
+    case BM_NORM_LAYERNORM: rc = norm_bwd_dispatch<TT, BM_NORM_LAYERNORM>(a, x, stats, dh, dres, dx, partial, st); break; \
+    case BM_NORM_RMSNORM: rc = norm_bwd_dispatch<TT, BM_NORM_RMSNORM>(a, x, stats, dh, dres, dx, partial, st); break;     \
+    default: rc = norm_bwd_dispatch<TT, BM_NORM_ADALN>(a, x, stats, dh, dres, dx, partial, st); break; \
+  }
+  if (a.dtype == BM_DTYPE_BF16) { BM_KIND(bf16_t) } else { BM_KIND(float) }
+#undef BM_KIND
+  BM_RETURN_IF(rc);
+  const int nb = norm_bwd_blocks(a.T);
+  if (a.kind == BM_NORM_ADALN) {
+    dim3 grid(S, cdiv(a.d, 64));
+    if (a.dtype == BM_DTYPE_BF16)
+      hipLaunchKernelGGL(adaln_seg_grads_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)x,
+                         stats, (const bf16_t*)dh, cu_dev, dmod, a.ld_mod, a.shift_off, a.scale_off,
+                         a.T, a.d);
+    else
+      hipLaunchKernelGGL(adaln_seg_grads_kernel<float>, grid, dim3(256), 0, st, (const float*)x,
+                         stats, (const float*)dh, cu_dev, dmod, a.ld_mod, a.shift_off, a.scale_off,
+                         a.T, a.d);
+    BM_CHECK_LAUNCH("adaln_seg_grads");
+    return BM_OK;
+  }
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 256)), dim3(256), 0, st, partial, nb,
+                     2 * a.d, a.d, dgamma);
+  if (a.kind == BM_NORM_LAYERNORM)
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 256)), dim3(256), 0, st,
+                       partial + a.d, nb, 2 * a.d, a.d, dbeta);
+  BM_CHECK_LAUNCH("norm_bwd_reduce");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ RoPE
+// One thread owns VEC rotation pairs (i .. i+VEC-1, and the same + dh/2) of one
+// token and walks the heads, so each angle is evaluated once per token.
+template <typename T>
+__global__ void rope_kernel(T* __restrict__ qkv, int ld, int T_rows, int n_heads, int dh,
+                            float log2_base, const int32_t* __restrict__ cu,
+                            const int32_t* __restrict__ tok_seq, float sign) {
+  constexpr int VEC = Elt<T>::VEC;
+  const int half = dh >> 1;
+  const int chunks = half / VEC;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)T_rows * chunks) return;
+  const int t = (int)(gid / chunks);
+  const int i0 = (int)(gid % chunks) * VEC;
+  const int pos = t - cu[tok_seq[t]];
+  float cs[VEC], sn[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    // angle = pos * base^(-2i/dh), evaluated and range-reduced in fp64
+    double inv_freq = exp2(-2.0 * (double)(i0 + e) / (double)dh * (double)log2_base);
+    double ang = (double)pos * inv_freq;
+    const double two_pi = 6.283185307179586476925286766559;
+    ang -= two_pi * rint(ang / two_pi);
+    float s, c;
+    sincosf((float)ang, &s, &c);
+    cs[e] = c; sn[e] = sign * s;
+  }
+  T* row = qkv + (size_t)t * ld;
+  for (int hd = 0; hd < n_heads; ++hd) {
+    T* p = row + hd * dh + i0;
+    float a[VEC], b[VEC], ra[VEC], rb[VEC];
+    load16(p, a); load16(p + half, b);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      ra[e] = a[e] * cs[e] - b[e] * sn[e];
+      rb[e] = b[e] * cs[e] + a[e] * sn[e];
+    }
+    store16(p, ra); store16(p + half, rb);
+  }
+}
+
+bm_status rope_inplace(int dtype, void* qkv, int ld, int T, int n_heads, int dh, float base,
+                       const int32_t* cu_dev, const int32_t* tok_seq, float sign, hipStream_t st) {
+  if (T == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  if ((dh / 2) % vec != 0) { set_error("rope: head_dim %d unsupported", dh); return BM_ERR_UNSUPPORTED; }
+  long n = (long)T * ((dh / 2) / vec);
+  float log2_base = log2f(base);
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st, (bf16_t*)qkv, ld,
+                       T, n_heads, dh, log2_base, cu_dev, tok_seq, sign);
+  else
+    hipLaunchKernelGGL(rope_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st, (float*)qkv, ld, T,
+                       n_heads, dh, log2_base, cu_dev, tok_seq, sign);
+  BM_CHECK_LAUNCH("rope");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ activations
+__device__ inline float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ inline float gelu_grad_f(float z) {
+  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
+  float pdf = expf(-0.5f * z * z) * 0.39894228040143268f;
+  return cdf + z * pdf;
+}
+__device__ inline float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+template <typename T, int ACT>
+__global__ void act_fwd_kernel(const T* __restrict__ up, T* __restrict__ a, int rows, int F) {
+  constexpr int VEC = Elt<T>::VEC;
+  const int per_row = F / VEC;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)rows * per_row) return;
+  const long t = gid / per_row;
+  const int c = (int)(gid % per_row) * VEC;
+  float out[VEC];
+  if (ACT == BM_ACT_GELU) {
+    float z[VEC];
+    load16(up + t * F + c, z);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = gelu_f(z[e]);
+  } else {
+    float g[VEC], u[VEC];
+    load16(up + t * 2 * F + c, g); load16(up + t * 2 * F + F + c, u);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = g[e] * sigmoid_f(g[e]) * u[e];
+  }
+  store16(a + t * F + c, out);
+}
+
+template <typename T, int ACT>
+__global__ void act_bwd_kernel(const T* __restrict__ up, const T* __restrict__ da,
+                               T* __restrict__ dup, int rows, int F) {
+  constexpr int VEC = Elt<T>::VEC;
+  const int per_row = F / VEC;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)rows * per_row) return;
+  const long t = gid / per_row;
+  const int c = (int)(gid % per_row) * VEC;
+  float d[VEC];
+  load16(da + t * F + c, d);
+  if (ACT == BM_ACT_GELU) {
+    float z[VEC], out[VEC];
+    load16(up + t * F + c, z);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = d[e] * gelu_grad_f(z[e]);
+    store16(dup + t * F + c, out);
+  } else {
+    float g[VEC], u[VEC], dg[VEC], du[VEC];
+    load16(up + t * 2 * F + c, g); load16(up + t * 2 * F + F + c, u);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      float s = sigmoid_f(g[e]);
+      dg[e] = d[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
+      du[e] = d[e] * g[e] * s;
+    }
+    store16(dup + t * 2 * F + c, dg); store16(dup + t * 2 * F + F + c, du);
+  }
+}
+
+bm_status act_forward(int dtype, int act, const void* up, void* a, int T, int F, hipStream_t st) {
+  if (T == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  if (F % vec) { set_error("activation: mlp_hidden %d not a multiple of %d", F, vec); return BM_ERR_UNSUPPORTED; }
+  long n = (long)T * (F / vec);
+  dim3 grid(cdiv(n, 256)), block(256);
+#define BM_L(TT, AA) hipLaunchKernelGGL((act_fwd_kernel<TT, AA>), grid, block, 0, st, (const TT*)up, (TT*)a, T, F)
+  if (dtype == BM_DTYPE_BF16) { if (act == BM_ACT_GELU) BM_L(bf16_t, BM_ACT_GELU); else BM_L(bf16_t, BM_ACT_SWIGLU); }
+  else { if (act == BM_ACT_GELU) BM_L(float, BM_ACT_GELU); else BM_L(float, BM_ACT_SWIGLU); }
+#undef BM_L
+  BM_CHECK_LAUNCH("act_fwd");
+  return BM_OK;
+}
+
+bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, int T, int F,
+                       hipStream_t st) {
+  if (T == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  if (F % vec) { set_error("activation: mlp_hidden %d not a multiple of %d", F, vec); return BM_ERR_UNSUPPORTED; }
+  long n = (long)T * (F / vec);
+  dim3 grid(cdiv(n, 256)), block(256);
+#define BM_L(TT, AA) hipLaunchKernelGGL((act_bwd_kernel<TT, AA>), grid, block, 0, st, (const TT*)up, (const TT*)da, (TT*)dup, T, F)
+  if (dtype == BM_DTYPE_BF16) { if (act == BM_ACT_GELU) BM_L(bf16_t, BM_ACT_GELU); else BM_L(bf16_t, BM_ACT_SWIGLU); }
+  else { if (act == BM_ACT_GELU) BM_L(float, BM_ACT_GELU); else BM_L(float, BM_ACT_SWIGLU); }
+#undef BM_L
+  BM_CHECK_LAUNCH("act_bwd");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ column sums (bias grads)
+// stage 1: grid (column spans, row chunks); a wavefront reads 64*VEC contiguous
+// columns of one row per step.  stage 2: fixed-order sum of the chunk partials.
+static void colsum_plan(int T, int N, int vec, int* spans, int* chunks) {
+  *spans = cdiv(N, WAVE * vec);
+  int r = cdiv(1024, *spans);
+  int rmax = cdiv(T, 4);
+  if (r > rmax) r = rmax;
+  if (r > 256) r = 256;
+  if (r < 1) r = 1;
+  *chunks = r;
+}
+
+size_t colsum_scratch_bytes(int T, int N) {
+  // chunks * N <= 1024 * 64 * VEC + N for any width up to N, and chunks <= 256
+  (void)T;
+  size_t bound = (size_t)1024 * 512 + N;
+  size_t cap = (size_t)256 * N;
+  return (bound < cap ? bound : cap) * sizeof(float);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stage1_kernel(const T* __restrict__ a, int lda, int rows,
+                                                            int N, float* __restrict__ partial) {
+  constexpr int VEC = Elt<T>::VEC;
+  __shared__ float sm[4][WAVE * VEC];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = (blockIdx.x * WAVE + lane) * VEC;
+  const int chunks = gridDim.y;
+  const int per = (rows + chunks - 1) / chunks;
+  const int r0 = blockIdx.y * per;
+  const int r1 = min(rows, r0 + per);
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (col < N) {
+    for (int r = r0 + wave; r < r1; r += 4) {
+      float v[VEC];
+      load16(a + (size_t)r * lda + col, v);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) sm[wave][lane * VEC + e] = acc[e];
+  __syncthreads();
+  if (wave == 0 && col < N) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      int i = lane * VEC + e;
+      partial[(size_t)blockIdx.y * N + col + e] = sm[0][i] + sm[1][i] + sm[2][i] + sm[3][i];
+    }
+  }
+}
+
+bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, float* out,
+                            void* scratch, hipStream_t st) {
+  if (T == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  if (N % vec || lda % vec) { set_error("colsum: width %d/%d not a multiple of %d", N, lda, vec); return BM_ERR_UNSUPPORTED; }
+  int spans, chunks;
+  colsum_plan(T, N, vec, &spans, &chunks);
+  float* partial = (float*)scratch;
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(colsum_stage1_kernel<bf16_t>, dim3(spans, chunks), dim3(256), 0, st,
+                       (const bf16_t*)a, lda, T, N, partial);
+  else
+    hipLaunchKernelGGL(colsum_stage1_kernel<float>, dim3(spans, chunks), dim3(256), 0, st,
+                       (const float*)a, lda, T, N, partial);
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(N, 256)), dim3(256), 0, st, partial, chunks, N,
+                     N, out);
+  BM_CHECK_LAUNCH("colsum");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ per-sequence column sums
+template <typename T>
+__global__ __launch_bounds__(256) void segment_colsum_kernel(const T* __restrict__ a,
+                                                             const T* __restrict__ b, int ld, int N,
+                                                             const int32_t* __restrict__ cu,
+                                                             float* __restrict__ out, int ld_out) {
+  __shared__ float sm[4][64];
+  const int s = blockIdx.x;
+  const int c = blockIdx.y * 64 + (threadIdx.x & 63);
+  const int rg = threadIdx.x >> 6;
+  float acc = 0.f;
+  if (c < N) {
+    for (int t = cu[s] + rg; t < cu[s + 1]; t += 4) {
+      float v = Elt<T>::to_f(a[(size_t)t * ld + c]);
+      if (b) v *= Elt<T>::to_f(b[(size_t)t * ld + c]);
+      acc += v;
+    }
+  }
+  sm[rg][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (rg == 0 && c < N) {
+    int l = threadIdx.x;
+    out[(size_t)s * ld_out + c] = sm[0][l] + sm[1][l] + sm[2][l] + sm[3][l];
+  }
+}
+
+bm_status segment_colsum(int dtype, const void* a, const void* b, int ld, int N,
+                         const int32_t* cu_dev, int S, float* out, int ld_out, hipStream_t st) {
+  if (S == 0) return BM_OK;
+  dim3 grid(S, cdiv(N, 64));
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(segment_colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)a,
+                       (const bf16_t*)b, ld, N, cu_dev, out, ld_out);
+  else
+    hipLaunchKernelGGL(segment_colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)a,
+                       (const float*)b, ld, N, cu_dev, out, ld_out);
+  BM_CHECK_LAUNCH("segment_colsum");
+  return BM_OK;
+}
+
+// ------------------------------------------------------------------ small elementwise helpers
+template <typename T>
+__global__ void gate_mul_kernel(const T* __restrict__ a, const float* __restrict__ gate, int ld_gate,
+                                const int32_t* __restrict__ tok_seq, const T* __restrict__ residual,
+                                T* __restrict__ out, int rows, int N) {
+  constexpr int VEC = Elt<T>::VEC;
+  const int per_row = N / VEC;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)rows * per_row) return;
+  const long t = gid / per_row;
+  const int c = (int)(gid % per_row) * VEC;
+  const float* g = gate + (size_t)tok_seq[t] * ld_gate + c;
+  float v[VEC];
+  load16(a + t * N + c, v);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) v[e] *= g[e];
+  if (residual) {
+    float r[VEC];
+    load16(residual + t * N + c, r);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] += r[e];
+  }
+  store16(out + t * N + c, v);
+}
+
+bm_status gate_mul(int dtype, const void* a, const float* gate, int ld_gate, const int32_t* tok_seq,
+                   const void* residual, void* out, int T, int N, hipStream_t st) {
+  if (T == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  long n = (long)T * (N / vec);
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(gate_mul_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st,
+                       (const bf16_t*)a, gate, ld_gate, tok_seq, (const bf16_t*)residual, (bf16_t*)out, T, N);
+  else
+    hipLaunchKernelGGL(gate_mul_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st,
+                       (const float*)a, gate, ld_gate, tok_seq, (const float*)residual, (float*)out, T, N);
+  BM_CHECK_LAUNCH("gate_mul");
+  return BM_OK;
+}
+
+template <typename T>
+__global__ void silu_fwd_kernel(const T* __restrict__ in, T* __restrict__ out, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float z = Elt<T>::to_f(in[i]);
+  out[i] = Elt<T>::from_f(z * sigmoid_f(z));
+}
+
+template <typename T>
+__global__ void silu_bwd_f32_kernel(const T* __restrict__ in, const float* __restrict__ g,
+                                    T* __restrict__ out, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float z = Elt<T>::to_f(in[i]);
+  float s = sigmoid_f(z);
+  out[i] = Elt<T>::from_f(g[i] * s * (1.0f + z * (1.0f - s)));
+}
+
+template <typename T>
+__global__ void cast_from_f32_kernel(const float* __restrict__ in, T* __restrict__ out, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = Elt<T>::from_f(in[i]);
+}
+
+bm_status silu_forward(int dtype, const void* in, void* out, long n, hipStream_t st) {
+  if (n == 0) return BM_OK;
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(silu_fwd_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)in, (bf16_t*)out, n);
+  else
+    hipLaunchKernelGGL(silu_fwd_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st, (const float*)in, (float*)out, n);
+  BM_CHECK_LAUNCH("silu_fwd");
+  return BM_OK;
+}
+
+bm_status silu_backward_f32(int dtype, const void* in, const float* g, void* out, long n, hipStream_t st) {
+  if (n == 0) return BM_OK;
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(silu_bwd_f32_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)in, g, (bf16_t*)out, n);
+  else
+    hipLaunchKernelGGL(silu_bwd_f32_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st, (const float*)in, g, (float*)out, n);
+  BM_CHECK_LAUNCH("silu_bwd");
+  return BM_OK;
+}
+
+bm_status cast_from_f32(int dtype, const float* in, void* out, long n, hipStream_t st) {
+  if (n == 0) return BM_OK;
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(cast_from_f32_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st, in, (bf16_t*)out, n);
+  else
+    hipLaunchKernelGGL(cast_from_f32_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st, in, (float*)out, n);
+  BM_CHECK_LAUNCH("cast");
+  return BM_OK;
+}
+
+}  // namespace bm

@@ -1,0 +1,94 @@
+"""Host-side checks of the C-ABI library (no GPU): it loads, exports every
+symbol the header declares, validates arguments, and its schedule generator
+agrees with the schedule oracle."""
+import os
+import re
+
+import pytest
+
+from oracle import schedule_oracle as so
+from paper_2605_25451_amd import binding as bm
+from paper_2605_25451_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CODE = {"E": bm.OP_ENC_FWD, "e": bm.OP_ENC_BWD, "F": bm.OP_LLM_FWD, "B": bm.OP_LLM_BWD,
+        "G": bm.OP_GEN_FWD, "H": bm.OP_GEN_BWD}
+
+
+def test_library_exports_every_declared_symbol():
+    text = ""
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        text += re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+    names = set(re.findall(r"\b(bm_[a-z_0-9]+)\s*\(", text))
+    assert {"bm_block_forward", "bm_block_backward", "bm_block_sizes", "bm_gemm",
+            "bm_attention_forward", "bm_attention_backward", "bm_build_schedule"} <= names
+    lib = bm.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 16, 32])
+@pytest.mark.parametrize("us", [1, 2, 4])
+@pytest.mark.parametrize("gen", [0, 1])
+def test_schedule_matches_oracle(M, us, gen):
+    cols = so.llm_schedule_1f1b(M, us, 3)
+    want = {
+        bm.ORDER_NESTED: so.build_schedule(cols, M, us, 3, bool(gen)),
+        bm.ORDER_COMPUTE_EFFICIENT: so.compute_efficient_schedule(cols, M, us, bool(gen)),
+        bm.ORDER_SEQUENTIAL: so.sequential_schedule(M, us, bool(gen)),
+    }
+    for order, ref in want.items():
+        got = bm.build_schedule(order, M, us, 3, 3, gen)
+        assert got == [(CODE[k], i) for k, i in ref]
+        peak = bm.check_schedule(got, M, us, gen)
+        ref_peak = so.live_counts(ref, M, us)
+        assert peak == (ref_peak["enc"], ref_peak["gen"], ref_peak["llm"])
+
+
+def test_check_schedule_rejects_unsafe_orders():
+    ops = bm.build_schedule(bm.ORDER_NESTED, 4, 1, 3, 3, 1)
+    i = ops.index((bm.OP_LLM_FWD, 0)); j = ops.index((bm.OP_ENC_FWD, 0))
+    bad = list(ops); bad[i], bad[j] = bad[j], bad[i]          # LLM forward before its encoder unit
+    with pytest.raises(bm.BmError):
+        bm.check_schedule(bad, 4, 1, 1)
+    i = ops.index((bm.OP_GEN_BWD, 0)); j = ops.index((bm.OP_LLM_BWD, 0))
+    bad = list(ops); bad[i], bad[j] = bad[j], bad[i]          # LLM backward before generator backward
+    with pytest.raises(bm.BmError):
+        bm.check_schedule(bad, 4, 1, 1)
+    with pytest.raises(bm.BmError):
+        bm.check_schedule(ops[:-1], 4, 1, 1)                   # an op is missing
+    with pytest.raises(bm.BmError):
+        bm.check_schedule(ops + [ops[-1]], 4, 1, 1)            # an op appears twice
+
+
+def test_build_schedule_argument_errors():
+    with pytest.raises(bm.BmError):
+        bm.build_schedule(bm.ORDER_NESTED, 0, 1, 3, 3, 1)
+    with pytest.raises(bm.BmError):
+        bm.build_schedule(bm.ORDER_NESTED, 8, 1, 2, 3, 1)      # W too small for 3 units in flight
+    with pytest.raises(bm.BmError):
+        bm.build_schedule(7, 8, 1, 3, 3, 1)
+
+
+def test_block_sizes_and_descriptor_validation():
+    desc = bm.make_desc(synth.vit_large())
+    saved, scratch = bm.block_sizes(desc, 16384, 26, 1024)
+    T, d, F = 16384, 1024, 4096
+    assert saved >= T * (3 * d + d + d + F) * 2 + 16 * T * 4
+    assert scratch >= T * F * 2
+    s2, _ = bm.block_sizes(desc, 2 * T, 52, 1024)
+    assert 1.9 < s2 / saved < 2.1                              # activation bytes scale with tokens
+    bad = bm.make_desc(synth.scaled(synth.vit_large(), n_kv_heads=5))
+    with pytest.raises(bm.BmError) as e:
+        bm.block_sizes(bad, 128, 1, 128)
+    assert e.value.status == bm.BM_ERR_INVALID_ARG
+    bad = bm.make_desc(synth.scaled(synth.vit_large(), hidden=1000))
+    with pytest.raises(bm.BmError):
+        bm.block_sizes(bad, 128, 1, 128)
+    odd = bm.make_desc(synth.scaled(synth.vit_large(), n_q_heads=16, n_kv_heads=16, head_dim=40, hidden=640))
+    with pytest.raises(bm.BmError) as e:
+        bm.block_sizes(odd, 128, 1, 128)
+    assert e.value.status == bm.BM_ERR_UNSUPPORTED
+    with pytest.raises(bm.BmError):
+        bm.block_sizes(desc, 0, 1, 1)
