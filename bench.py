@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: forward + backward of one packed variable-length
+transformer block on one MI355X, through the C-ABI library.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit]
+
+One step = bm_block_forward + bm_block_backward over one batch of seeded
+synthetic packed tokens that is already resident in HBM.  Prints ONE JSON line:
+block fwd+bwd TFLOP/s (algorithmic flops: 3 x GEMM-forward + 3.5 x
+attention-forward over unmasked within-sequence pairs), the roofline figures
+of the dominant kernel class measured with HIP events on the launch stream,
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until such a run has been summarised there.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_flops(cfg, cu):
+    """(gemm_fwd, attn_fwd) flops of one block over the packed batch."""
+    import numpy as np
+    T = int(cu[-1])
+    d, F = cfg.hidden, cfg.mlp_hidden
+    qd = cfg.n_q_heads * cfg.head_dim
+    gemm = 2.0 * T * d * cfg.qkv_dim + 2.0 * T * qd * d + 2.0 * T * d * cfg.up_dim + 2.0 * T * F * d
+    if cfg.norm == 2:
+        gemm += 2.0 * (len(cu) - 1) * d * 6 * d
+    L = np.diff(cu).astype(np.float64)
+    pairs = (L * (L + 1) / 2).sum() if cfg.mask else (L * L).sum()
+    attn = 4.0 * cfg.head_dim * cfg.n_q_heads * pairs
+    return gemm, attn
+
+
+def make_workload(name):
+    from paper_2605_25451_amd import synth
+    if name == "config2":
+        return synth.config2()
+    if name == "config3":
+        return synth.config3()
+    if name == "config4":
+        return synth.config4()
+    if name == "dit":
+        return synth.dit_case()
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(case, budget_tokens=2048):
+    """The oracle as it stands, timed on a bounded sample: the first sequences of
+    the same pack up to about budget_tokens tokens."""
+    import numpy as np
+    from oracle import block_oracle as bo
+    from paper_2605_25451_amd import synth
+    ids, tok = [], 0
+    for s in range(case.S):
+        n = int(case.cu_seqlens[s + 1] - case.cu_seqlens[s])
+        if ids and tok + n > budget_tokens:
+            break
+        ids.append(s); tok += n
+    sub = synth.sub_case(case, ids)
+    t0 = time.perf_counter()
+    bo.block_fwd_bwd(sub.cfg, sub.params, sub.x, sub.cu_seqlens, sub.dy, sub.cond)
+    dt = time.perf_counter() - t0
+    g, a = algorithmic_flops(sub.cfg, sub.cu_seqlens)
+    flops = 3.0 * g + 3.5 * a
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"numpy fp64 oracle fwd+bwd on the first {len(ids)} sequences "
+                      f"({sub.T} of {case.T} tokens) of the same pack, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd.runner import CaseOnDevice
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    bm.lib()                                    # fail loudly if the HIP library is missing
+    case = make_workload(args.workload)
+    dev = CaseOnDevice(case)
+    gemm_f, attn_f = algorithmic_flops(case.cfg, case.cu_seqlens)
+    step_flops = 3.0 * gemm_f + 3.5 * attn_f
+
+    for _ in range(args.warmup):
+        dev.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dev.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel-class durations: HIP events on the launch stream, same K steps
+    bm.profile_begin()
+    for _ in range(args.steps):
+        dev.step()
+    prof = bm.profile_end()
+    torch.cuda.synchronize()
+    breakdown = {}
+    for cls, (ms, work, n) in prof.items():
+        if n == 0:
+            continue
+        per_launch_ms = ms / n
+        entry = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                 "avg_launch_us": per_launch_ms * 1e3}
+        if cls.startswith("gemm") or cls.startswith("attn"):
+            entry["tflops"] = work / (ms * 1e-3) / 1e12 if ms > 0 else None
+        elif work > 0:
+            entry["gbs"] = work / (ms * 1e-3) / 1e9 if ms > 0 else None
+        breakdown[cls] = entry
+    dom = max(breakdown, key=lambda c: breakdown[c]["ms_per_step"])
+    d_ms, d_work, d_n = prof[dom]
+    if dom.startswith("gemm") or dom.startswith("attn"):
+        achieved = d_work / (d_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": MEASURED_TRAFFIC_BYTES}
+    else:
+        achieved = d_work / (d_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": MEASURED_TRAFFIC_BYTES}
+    gemm_ms = sum(prof[c][0] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
+    gemm_work = sum(prof[c][1] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
+    attn_ms = prof["attn_fwd"][0] + prof["attn_bwd"][0]
+    attn_work = prof["attn_fwd"][1] + prof["attn_bwd"][1]
+
+    out = {
+        "metric": "block fwd+bwd TFLOP/s + MFMA util% on packed varlen multimodal tokens (bf16)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": case.name, "tokens": case.T, "sequences": case.S,
+                   "max_seqlen": case.max_seqlen, "hidden": case.cfg.hidden,
+                   "heads": f"{case.cfg.n_q_heads}q/{case.cfg.n_kv_heads}kv x {case.cfg.head_dim}",
+                   "mlp_hidden": case.cfg.mlp_hidden,
+                   "step": "one block forward + backward (weight grads accumulated in fp32)",
+                   "flops_per_step": step_flops},
+        "mfma_util_pct": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+        "gemm_tflops": gemm_work / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+        "attention_tflops": attn_work / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None,
+        "tokens_per_s": case.T / (ms_per_step * 1e-3),
+        "roofline": roofline,
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

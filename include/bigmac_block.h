@@ -167,6 +167,20 @@ bm_status bm_attention_backward(int32_t dtype, int32_t mask, int32_t Hq, int32_t
                                 void* dq, void* dk, void* dv, int32_t ld_dqkv,
                                 void* scratch, size_t scratch_bytes, void* hip_stream);
 
+/* ---- measurement: per-kernel-class timing ------------------------------------------- */
+
+/* Between bm_profile_begin() and bm_profile_end() every kernel group the library
+ * launches is bracketed by a pair of HIP events recorded on the launch stream.
+ * bm_profile_end synchronises with those events and returns, per class, the
+ * summed elapsed milliseconds, the summed algorithmic work (flops for GEMM and
+ * attention classes, bytes for the HBM-bound classes) and the number of launches.
+ * Outputs are host arrays of BM_PROF_CLASSES entries.  Not thread safe; measuring
+ * tool only (it serialises neighbouring kernels at the event boundaries). */
+enum { BM_PROF_GEMM_NT = 0, BM_PROF_GEMM_NN = 1, BM_PROF_GEMM_TN = 2, BM_PROF_ATTN_FWD = 3,
+       BM_PROF_ATTN_BWD = 4, BM_PROF_NORM = 5, BM_PROF_ELEMENTWISE = 6, BM_PROF_CLASSES = 7 };
+bm_status bm_profile_begin(void);
+bm_status bm_profile_end(double* ms /* host */, double* work /* host */, int64_t* launches /* host */);
+
 /* ---- nested schedule (host only; Sec. 3.1 and the BuildSchedule figure) ------------ */
 
 enum { BM_OP_ENC_FWD = 0, BM_OP_ENC_BWD = 1, BM_OP_LLM_FWD = 2, BM_OP_LLM_BWD = 3,

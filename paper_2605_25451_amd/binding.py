@@ -73,11 +73,13 @@ def lib() -> C.CDLL:
         l.bm_attention_backward_scratch_bytes.restype = sz
         l.bm_attention_backward.argtypes = ([i32] * 5 + [vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32,
                                                           i32, vp, vp, vp, i32, vp, sz, vp])
+        l.bm_profile_begin.argtypes = []
+        l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.bm_build_schedule.argtypes = [i32] * 6 + [pi32, pi32]
         l.bm_check_schedule.argtypes = [pi32, i32, i32, i32, i32, pi32]
         for name in ("bm_block_sizes", "bm_block_forward", "bm_block_backward", "bm_gemm",
                      "bm_attention_forward", "bm_attention_backward", "bm_build_schedule",
-                     "bm_check_schedule"):
+                     "bm_check_schedule", "bm_profile_begin", "bm_profile_end"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -181,6 +183,21 @@ def attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, c
                                        cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
                                        _ptr(dv), ld_dqkv, _ptr(scratch), scratch_bytes,
                                        _stream() if stream is None else stream))
+
+
+PROF_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "norm", "elementwise")
+
+
+def profile_begin():
+    _check(lib().bm_profile_begin())
+
+
+def profile_end():
+    """{class: (milliseconds, work, launches)}; work = flops (gemm/attn) or bytes."""
+    n = len(PROF_CLASSES)
+    ms, work, cnt = (C.c_double * n)(), (C.c_double * n)(), (C.c_int64 * n)()
+    _check(lib().bm_profile_end(ms, work, cnt))
+    return {PROF_CLASSES[i]: (ms[i], work[i], cnt[i]) for i in range(n)}
 
 
 def build_schedule(order, M, unit_size, W, llm_depth, has_generator):

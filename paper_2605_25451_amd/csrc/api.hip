@@ -6,6 +6,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <vector>
+
 namespace bm {
 
 static thread_local char g_err[512] = "";
@@ -22,6 +24,27 @@ bm_status hip_fail(hipError_t e, const char* what) {
   return BM_ERR_HIP;
 }
 
+// ---- profiling -----------------------------------------------------------
+namespace {
+struct ProfRec { int cls; double work; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+
+ProfScope::ProfScope(int cls, double work, hipStream_t stream) : slot(-1), st(stream) {
+  if (!g_prof_on) return;
+  ProfRec r; r.cls = cls; r.work = work;
+  if (hipEventCreate(&r.a) != hipSuccess) return;
+  if (hipEventCreate(&r.b) != hipSuccess) { hipEventDestroy(r.a); return; }
+  hipEventRecord(r.a, st);
+  g_prof.push_back(r);
+  slot = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+  if (slot >= 0) hipEventRecord(g_prof[slot].b, st);
+}
+
 size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype) {
   if (dtype != BM_DTYPE_BF16) return 0;
   return gemm_mfma_scratch_bytes(layout, M, N, K);
@@ -31,6 +54,7 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
                int ldb, void* C, int ldc, const GemmEpilogue& epi, void* scratch,
                size_t scratch_bytes, hipStream_t st) {
   if (M <= 0 || N <= 0) return BM_OK;
+  ProfScope prof(PROF_GEMM_NT + layout, 2.0 * M * N * K, st);
   if (gemm_mfma_supported(layout, dtype, M, N, K, lda, ldb, ldc, epi))
     return gemm_mfma(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
   return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, st);
@@ -41,6 +65,30 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
 using namespace bm;
 
 extern "C" const char* bm_last_error(void) { return g_err; }
+
+extern "C" bm_status bm_profile_begin(void) {
+  for (auto& r : g_prof) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  g_prof.clear();
+  g_prof_on = true;
+  return BM_OK;
+}
+
+extern "C" bm_status bm_profile_end(double* ms, double* work, int64_t* launches) {
+  g_prof_on = false;
+  BM_ARG_CHECK(ms && work && launches, "bm_profile_end: NULL output");
+  for (int c = 0; c < PROF_CLASSES; ++c) { ms[c] = 0; work[c] = 0; launches[c] = 0; }
+  bm_status rc = BM_OK;
+  for (auto& r : g_prof) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    if (e != hipSuccess) rc = hip_fail(e, "bm_profile_end");
+    ms[r.cls] += t; work[r.cls] += r.work; launches[r.cls] += 1;
+    hipEventDestroy(r.a); hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+  return rc;
+}
 
 static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 

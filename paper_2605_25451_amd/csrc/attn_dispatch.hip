@@ -11,7 +11,18 @@ bm_status attention_backward_mfma(const AttnArgs& a, const void* o, const void* 
                                   void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
                                   size_t scratch_bytes, hipStream_t st);
 
+// unmasked (query, key) pairs inside the sequences
+static double attn_pairs(const AttnArgs& a) {
+  double pairs = 0;
+  for (int s = 0; s < a.S; ++s) {
+    double L = a.cu_host[s + 1] - a.cu_host[s];
+    pairs += a.causal ? L * (L + 1) / 2 : L * L;
+  }
+  return pairs;
+}
+
 bm_status attention_forward(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
+  ProfScope prof(PROF_ATTN_FWD, 4.0 * a.dh * a.Hq * attn_pairs(a), st);
   if (attention_mfma_supported(a)) return attention_forward_mfma(a, o, lse, st);
   return attention_forward_generic(a, o, lse, st);
 }
@@ -25,6 +36,7 @@ size_t attention_backward_scratch_bytes(int Hq, int Hkv, int dh, int T) {
 bm_status attention_backward(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
                              void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
                              size_t scratch_bytes, hipStream_t st) {
+  ProfScope prof(PROF_ATTN_BWD, 10.0 * a.dh * a.Hq * attn_pairs(a), st);
   if (attention_mfma_supported(a))
     return attention_backward_mfma(a, o, d_o, lse, dq, dk, dv, ld_dqkv, scratch, scratch_bytes, st);
   return attention_backward_generic(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);

@@ -1,16 +1,565 @@
-// bf16 MFMA flash attention (placeholder: nothing is routed here yet).
+// Variable-length flash attention on the gfx950 matrix cores (bf16 in, fp32
+// accumulate, online softmax in base 2), forward and backward.
+//
+// Packing: a workgroup owns one 128-row tile of ONE sequence and one head, so
+// attention is block-diagonal by construction; tiles are enumerated by walking
+// cu_seqlens (no padded grid), longest-running tiles first.
+//
+// Layout trick.  All score matrices are produced TRANSPOSED by the MFMA
+// (keys x queries for forward/dQ, queries x keys for dK/dV), so that the
+// softmax statistic of a row lives in ONE lane (two lanes for the two 32-lane
+// halves) instead of being spread over a wavefront, and the fp32 accumulator
+// of one MFMA is -- after conversion to bf16 -- exactly the B operand of the
+// next MFMA (P feeds P*V, dS feeds dS*K / dS*Q): probabilities never touch LDS.
+// The matching A operands (V^T, K^T, Q^T, dO^T) come from the LDS transpose
+// read (ds_read_b64_tr_b16) of tiles stored in their natural [row][dh] form.
+// Tiles are XOR-swizzled with a pattern that is conflict-free for both the
+// 16-byte row reads and the transpose reads.
+//
+// Backward is split in two kernels (dK/dV per key tile, dQ per query tile),
+// each recomputing P from the saved log-sum-exp: every output element has one
+// owner, so there are no floating-point atomics and results are reproducible.
 #include "common.h"
 
 namespace bm {
 
-bool attention_mfma_supported(const AttnArgs&) { return false; }
-bm_status attention_forward_mfma(const AttnArgs&, void*, float*, hipStream_t) {
-  set_error("attention_forward_mfma: not built"); return BM_ERR_UNSUPPORTED;
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// ---- swizzled [rows][DH] bf16 tile ------------------------------------------
+template <int DH>
+__device__ inline int tile_off(int row, int c) {   // element offset of 16-byte chunk c of a row
+  int f;
+  if (DH == 128) f = ((row & 3) << 2) | ((row >> 2) & 3);
+  else { const int v = row >> 1; f = ((v & 1) << 2) | ((v >> 1) & 3); }
+  return row * DH + ((c ^ f) << 3);
 }
-size_t attention_backward_mfma_scratch_bytes(int, int, int, int) { return 0; }
-bm_status attention_backward_mfma(const AttnArgs&, const void*, const void*, const float*, void*,
-                                  void*, void*, int, void*, size_t, hipStream_t) {
-  set_error("attention_backward_mfma: not built"); return BM_ERR_UNSUPPORTED;
+
+// operand fragment, rows of the tile are the MFMA row/col index, dh is the k index:
+// lane l -> tile row row0 + l%32, dh = ks*16 + (l/32)*8 .. +7
+template <int DH>
+__device__ inline bf16x8 frag_rows(const bf16_t* t, int row0, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(t + tile_off<DH>(row0 + (lane & 31), ks * 2 + (lane >> 5)));
+}
+
+// A operand X^T: MFMA row = dh index col0 + l%32, k index = tile rows, in the
+// order the fp32 accumulator of a transposed score block hands them over:
+// half h = l/32 supplies tile rows r0+4h..+3 and r0+8+4h..+3.
+template <int DH>
+__device__ inline bf16x8 frag_cols(const bf16_t* t, int col0, int r0, int lane) {
+  const int gi = lane >> 4, s = lane & 15;
+  const int col = col0 + (gi & 1) * 16 + (s & 3) * 4;
+  const int row = r0 + (gi >> 1) * 4 + (s >> 2);
+  const bf16_t* p0 = t + tile_off<DH>(row, col >> 3) + (col & 7);
+  const bf16_t* p1 = t + tile_off<DH>(row + 8, col >> 3) + (col & 7);
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p1);
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+// accumulator rows 8t..8t+7 of a 32x32 block -> bf16 B operand of a k=16 step
+__device__ inline bf16x8 acc_to_operand(const f32x16& a, int t) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)a[t * 8 + e];
+  return r;
+}
+
+// ---- global <-> LDS staging of a [ROWS][DH] tile by NT threads ----------------
+template <int ROWS, int DH, int NT>
+struct TileStage {
+  static constexpr int CPR = DH / 8;
+  static constexpr int CH = ROWS * CPR / NT;
+  u32x4 v[CH];
+  // rows beyond nrows are clamped to the last valid row (their results are masked or unused)
+  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int row0, int nrows, int tid) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int id = tid + i * NT;
+      int row = row0 + id / CPR;
+      if (row >= nrows) row = nrows - 1;
+      v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + (id % CPR) * 8);
+    }
+  }
+  __device__ inline void store(bf16_t* t, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int id = tid + i * NT;
+      *reinterpret_cast<u32x4*>(t + tile_off<DH>(id / CPR, id % CPR)) = v[i];
+    }
+  }
+};
+
+// which (sequence, tile) a linear tile id is; tiles of `rows` rows, later tiles of a
+// sequence first (under a causal mask they are the long ones)
+__device__ inline bool find_tile(const int32_t* __restrict__ cu, int S, int rows, int id, int* seq,
+                                 int* tile, int* ntiles) {
+  for (int s = 0; s < S; ++s) {
+    const int L = cu[s + 1] - cu[s];
+    const int nt = (L + rows - 1) / rows;
+    if (id < nt) { *seq = s; *tile = nt - 1 - id; *ntiles = nt; return true; }
+    id -= nt;
+  }
+  return false;
+}
+
+// =============================================================================
+// forward
+// =============================================================================
+constexpr int FQ = 128;   // query rows per workgroup (32 per wavefront)
+constexpr int FK = 64;    // keys per step
+
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
+    const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ o, int ldo, float* __restrict__ lse,
+    int Ttot, int group, float scale_log2) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
+  int seq, qt, nqt;
+  if (!find_tile(cu, S, FQ, blockIdx.x, &seq, &qt, &nqt)) return;
+  const int hq = blockIdx.y, hk = hq / group;
+  const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int q0 = qt * FQ;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5;
+  const int qpos = q0 + wave * 32 + (lane & 31);          // this lane's query (column of S^T)
+  const int qrow = min(qpos, L - 1);
+
+  bf16x8 qf[DH / 16];
+  {
+    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+  f32x16 oacc[DH / 32];
+#pragma unroll
+  for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[j][r] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+
+  const int kend = CAUSAL ? min(L, q0 + FQ) : L;
+  const int nkt = (kend + FK - 1) / FK;
+  const bf16_t* kbase = k + (size_t)lo * ld + hk * DH;
+  const bf16_t* vbase = v + (size_t)lo * ld + hk * DH;
+  TileStage<FK, DH, 256> sk, sv;
+  sk.load(kbase, ld, 0, L, tid);
+  sv.load(vbase, ld, 0, L, tid);
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    __syncthreads();                       // previous step's readers are done
+    sk.store(Ks, tid);
+    sv.store(Vs, tid);
+    __syncthreads();
+    if (kt + 1 < nkt) {
+      sk.load(kbase, ld, (kt + 1) * FK, L, tid);
+      sv.load(vbase, ld, (kt + 1) * FK, L, tid);
+    }
+    const int key0 = kt * FK;
+    // S^T = K Q^T : 2 blocks of 32 keys x 32 queries
+    f32x16 sacc[FK / 32];
+#pragma unroll
+    for (int b = 0; b < FK / 32; ++b) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks)
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks],
+                                                          sacc[b], 0, 0, 0);
+    }
+    // mask: keys past the sequence end, and keys after the query under a causal mask
+    const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < FK / 32; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float s = sacc[b][r] * scale_log2;
+        if (need_mask) {
+          const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (key >= L || (CAUSAL && key > qpos)) s = -INFINITY;
+        }
+        sacc[b][r] = s;
+        mx = fmaxf(mx, s);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);                 // finite: key 0 is visible to every query
+    const float corr = exp2f(m - m_new);
+    m = m_new;
+    float psum = 0.f;
+    bf16x8 pb[FK / 32][2];
+#pragma unroll
+    for (int b = 0; b < FK / 32; ++b) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(sacc[b][r] - m_new);
+        sacc[b][r] = p;
+        psum += p;
+      }
+      pb[b][0] = acc_to_operand(sacc[b], 0);
+      pb[b][1] = acc_to_operand(sacc[b], 1);
+    }
+    lsum = lsum * corr + psum;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[j][r] *= corr;
+      // O^T += V^T P^T
+#pragma unroll
+      for (int b = 0; b < FK / 32; ++b)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols<DH>(Vs, j * 32, b * 32 + t * 16, lane), pb[b][t], oacc[j], 0, 0, 0);
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (qpos < L) {
+    const float inv = 1.0f / lsum;
+    bf16_t* op = o + (size_t)(lo + qpos) * ldo + hq * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(oacc[j][g * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + j * 32 + g * 8 + half * 4) = w;
+      }
+    if (half == 0) lse[(size_t)hq * Ttot + lo + qpos] = (m + log2f(lsum)) * LN2;
+  }
+}
+
+int count_tiles(const int32_t* cu_host, int S, int rows) {
+  long n = 0;
+  for (int s = 0; s < S; ++s) n += (cu_host[s + 1] - cu_host[s] + rows - 1) / rows;
+  return (int)n;
+}
+
+template <int DH>
+bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
+  dim3 grid(count_tiles(a.cu_host, a.S, FQ), a.Hq), block(256);
+  const float sl2 = LOG2E / sqrtf((float)a.dh);
+#define BM_L(C)                                                                                  \
+  hipLaunchKernelGGL((fa_fwd_kernel<DH, C>), grid, block, 0, st, (const bf16_t*)a.q,             \
+                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.cu_dev, a.S, (bf16_t*)o, \
+                     a.Hq * a.dh, lse, a.T, a.Hq / a.Hkv, sl2)
+  if (a.causal) BM_L(true); else BM_L(false);
+#undef BM_L
+  BM_CHECK_LAUNCH("fa_fwd");
+  return BM_OK;
+}
+
+// =============================================================================
+// backward
+// =============================================================================
+// delta[h, t] = sum_c dO[t,h,c] * O[t,h,c]
+template <int DH>
+__global__ void fa_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int ldo,
+                                float* __restrict__ delta, int Ttot, int Hq) {
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)Ttot * Hq) return;
+  const int t = (int)(gid / Hq), hq = (int)(gid % Hq);
+  const bf16_t* po = o + (size_t)t * ldo + hq * DH;
+  const bf16_t* pd = d_o + (size_t)t * ldo + hq * DH;
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < DH; c += 8) {
+    float a[8], b[8];
+    load16(po + c, a); load16(pd + c, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = fmaf(a[e], b[e], s);
+  }
+  delta[(size_t)hq * Ttot + t] = s;
+}
+
+constexpr int BK_KEYS = 128;   // keys per workgroup in the dK/dV kernel (32 per wavefront)
+constexpr int BK_Q = 64;       // query rows per step
+
+// dK, dV of one 128-key tile of one kv head: walks the q heads of the group and the
+// query tiles; scores are kept as S[q, key] so that P and dS are B operands as they are.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void fa_bwd_dkdv_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
+    const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
+    const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dk,
+    bf16_t* __restrict__ dv, int ldd, int Ttot, int group, float scale, float scale_log2) {
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * DH];
+  __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
+  __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
+  int seq, kt, nkt;
+  if (!find_tile(cu, S, BK_KEYS, blockIdx.x, &seq, &kt, &nkt)) return;
+  kt = nkt - 1 - kt;                                   // early key tiles see the most queries
+  const int hk = blockIdx.y;
+  const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int kb0 = kt * BK_KEYS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int kpos = kb0 + wave * 32 + (lane & 31);       // this lane's key (column of S)
+  const int krow = min(kpos, L - 1);
+
+  bf16x8 kf[DH / 16], vf[DH / 16];
+  {
+    const bf16_t* kp = k + (size_t)(lo + krow) * ld + hk * DH + half * 8;
+    const bf16_t* vp = v + (size_t)(lo + krow) * ld + hk * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(vp + ks * 16);
+    }
+  }
+  f32x16 dkacc[DH / 32], dvacc[DH / 32];
+#pragma unroll
+  for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[j][r] = 0.f; dvacc[j][r] = 0.f; }
+
+  const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
+  const int nqt = (L - qstart + BK_Q - 1) / BK_Q;
+  const int iters = nqt * group;
+  TileStage<BK_Q, DH, 256> sq, sd;
+  float st_l = 0.f, st_d = 0.f;
+  auto fetch = [&](int it) {
+    const int hq = hk * group + it / nqt;
+    const int q0 = qstart + (it % nqt) * BK_Q;
+    sq.load(q + (size_t)lo * ld + hq * DH, ld, q0, L, tid);
+    sd.load(d_o + (size_t)lo * ldo + hq * DH, ldo, q0, L, tid);
+    if (tid < BK_Q) {
+      const int qi = min(q0 + tid, L - 1);
+      st_l = lse[(size_t)hq * Ttot + lo + qi] * LOG2E;
+      st_d = delta[(size_t)hq * Ttot + lo + qi];
+    }
+  };
+  fetch(0);
+  for (int it = 0; it < iters; ++it) {
+    __syncthreads();
+    sq.store(Qs, tid);
+    sd.store(Ds, tid);
+    if (tid < BK_Q) { Ls[tid] = st_l; Dl[tid] = st_d; }
+    __syncthreads();
+    if (it + 1 < iters) fetch(it + 1);
+    const int q0 = qstart + (it % nqt) * BK_Q;
+    const bool need_mask = (q0 + BK_Q > L) || (kb0 + BK_KEYS > L) ||
+                           (CAUSAL && q0 < kb0 + wave * 32 + 32);
+    bf16x8 pb[BK_Q / 32][2], dsb[BK_Q / 32][2];
+#pragma unroll
+    for (int qb = 0; qb < BK_Q / 32; ++qb) {
+      f32x16 sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Qs, qb * 32, ks, lane), kf[ks], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ds, qb * 32, ks, lane), vf[ks], dpacc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int qoff = qb * 32 + g * 8 + half * 4;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(Ls + qoff);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(Dl + qoff);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = g * 4 + e;
+          float p = exp2f(sacc[r] * scale_log2 - l4[e]);
+          if (need_mask) {
+            const int qi = q0 + qoff + e;
+            if (qi >= L || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
+          }
+          sacc[r] = p;
+          dpacc[r] = p * (dpacc[r] - d4[e]);
+        }
+      }
+      pb[qb][0] = acc_to_operand(sacc, 0); pb[qb][1] = acc_to_operand(sacc, 1);
+      dsb[qb][0] = acc_to_operand(dpacc, 0); dsb[qb][1] = acc_to_operand(dpacc, 1);
+    }
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+      for (int qb = 0; qb < BK_Q / 32; ++qb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols<DH>(Ds, j * 32, qb * 32 + t * 16, lane), pb[qb][t], dvacc[j], 0, 0, 0);
+          dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols<DH>(Qs, j * 32, qb * 32 + t * 16, lane), dsb[qb][t], dkacc[j], 0, 0, 0);
+        }
+  }
+  if (kpos < L) {
+    bf16_t* pk = dk + (size_t)(lo + kpos) * ldd + hk * DH;
+    bf16_t* pv = dv + (size_t)(lo + kpos) * ldd + hk * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 wk, wv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wk[e] = (bf16_t)(dkacc[j][g * 4 + e] * scale);
+          wv[e] = (bf16_t)dvacc[j][g * 4 + e];
+        }
+        *reinterpret_cast<bf16x4*>(pk + j * 32 + g * 8 + half * 4) = wk;
+        *reinterpret_cast<bf16x4*>(pv + j * 32 + g * 8 + half * 4) = wv;
+      }
+  }
+}
+
+// dQ of one 128-row query tile of one q head: walks the key tiles, scores kept as
+// S^T[key, q] as in the forward kernel.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void fa_bwd_dq_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
+    const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
+    const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dq,
+    int ldd, int Ttot, int group, float scale, float scale_log2) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
+  int seq, qt, nqt;
+  if (!find_tile(cu, S, FQ, blockIdx.x, &seq, &qt, &nqt)) return;
+  const int hq = blockIdx.y, hk = hq / group;
+  const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int q0 = qt * FQ;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int qpos = q0 + wave * 32 + (lane & 31);
+  const int qrow = min(qpos, L - 1);
+
+  bf16x8 qf[DH / 16], dof[DH / 16];
+  {
+    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH + half * 8;
+    const bf16_t* dp = d_o + (size_t)(lo + qrow) * ldo + hq * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(dp + ks * 16);
+    }
+  }
+  const float my_lse = lse[(size_t)hq * Ttot + lo + qrow] * LOG2E;
+  const float my_delta = delta[(size_t)hq * Ttot + lo + qrow];
+  f32x16 dqacc[DH / 32];
+#pragma unroll
+  for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[j][r] = 0.f;
+
+  const int kend = CAUSAL ? min(L, q0 + FQ) : L;
+  const int nkt = (kend + FK - 1) / FK;
+  const bf16_t* kbase = k + (size_t)lo * ld + hk * DH;
+  const bf16_t* vbase = v + (size_t)lo * ld + hk * DH;
+  TileStage<FK, DH, 256> sk, sv;
+  sk.load(kbase, ld, 0, L, tid);
+  sv.load(vbase, ld, 0, L, tid);
+  for (int kt = 0; kt < nkt; ++kt) {
+    __syncthreads();
+    sk.store(Ks, tid);
+    sv.store(Vs, tid);
+    __syncthreads();
+    if (kt + 1 < nkt) {
+      sk.load(kbase, ld, (kt + 1) * FK, L, tid);
+      sv.load(vbase, ld, (kt + 1) * FK, L, tid);
+    }
+    const int key0 = kt * FK;
+    const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
+    bf16x8 dsb[FK / 32][2];
+#pragma unroll
+    for (int b = 0; b < FK / 32; ++b) {
+      f32x16 sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Vs, b * 32, ks, lane), dof[ks], dpacc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = exp2f(sacc[r] * scale_log2 - my_lse);
+        if (need_mask) {
+          const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (key >= L || (CAUSAL && key > qpos)) p = 0.f;
+        }
+        dpacc[r] = p * (dpacc[r] - my_delta);
+      }
+      dsb[b][0] = acc_to_operand(dpacc, 0); dsb[b][1] = acc_to_operand(dpacc, 1);
+    }
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+      for (int b = 0; b < FK / 32; ++b)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols<DH>(Ks, j * 32, b * 32 + t * 16, lane), dsb[b][t], dqacc[j], 0, 0, 0);
+  }
+  if (qpos < L) {
+    bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(dqacc[j][g * 4 + e] * scale);
+        *reinterpret_cast<bf16x4*>(pq + j * 32 + g * 8 + half * 4) = w;
+      }
+  }
+}
+
+template <int DH>
+bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const float* lse, void* dq,
+                     void* dk, void* dv, int ldd, float* delta, hipStream_t st) {
+  const int ldo = a.Hq * a.dh;
+  const float scale = 1.0f / sqrtf((float)a.dh);
+  const float sl2 = scale * LOG2E;
+  const long n = (long)a.T * a.Hq;
+  hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
+                     (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
+  dim3 gkv(count_tiles(a.cu_host, a.S, BK_KEYS), a.Hkv), gq(count_tiles(a.cu_host, a.S, FQ), a.Hq);
+#define BM_L(C)                                                                                  \
+  hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,      \
+                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
+                     lse, delta, a.cu_dev, a.S, (bf16_t*)dk, (bf16_t*)dv, ldd, a.T,              \
+                     a.Hq / a.Hkv, scale, sl2);                                                  \
+  hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,        \
+                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
+                     lse, delta, a.cu_dev, a.S, (bf16_t*)dq, ldd, a.T, a.Hq / a.Hkv, scale, sl2)
+  if (a.causal) { BM_L(true); } else { BM_L(false); }
+#undef BM_L
+  BM_CHECK_LAUNCH("fa_bwd");
+  return BM_OK;
+}
+
+}  // namespace
+
+bool attention_mfma_supported(const AttnArgs& a) {
+  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 128) && a.ld_qkv % 8 == 0 &&
+         a.Hq <= 65535;
+}
+
+bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
+  if (a.dh == 128) return fwd_launch<128>(a, o, lse, st);
+  return fwd_launch<64>(a, o, lse, st);
+}
+
+size_t attention_backward_mfma_scratch_bytes(int Hq, int, int, int T) {
+  return align_up((size_t)Hq * T * sizeof(float), 256);
+}
+
+bm_status attention_backward_mfma(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
+                                  void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
+                                  size_t, hipStream_t st) {
+  if (a.dh == 128) return bwd_launch<128>(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
+  return bwd_launch<64>(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
 }
 
 }  // namespace bm

@@ -263,15 +263,15 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
                       nullptr, 0, st));
   }
   // attention half
-  BM_RETURN_IF(norm_forward(norm_args(c, m, 1, w, sv.mod, ws.tok_seq), x, ws.h, sv.stats1, 1, st));
+  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(norm_args(c, m, 1, w, sv.mod, ws.tok_seq), x, ws.h, sv.stats1, 1, st)); }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_qkv : nullptr;
     BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.QKV, m.d, ws.h, m.d, w->w_qkv, m.d, sv.qkv, m.QKV, e,
                       nullptr, 0, st));
   }
   if (c.rope)
-    BM_RETURN_IF(rope_inplace(dt, sv.qkv, m.QKV, T, m.Hq + m.Hkv, m.dh, c.rope_base, cu_dev,
-                              ws.tok_seq, 1.0f, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 2.0 * T * (m.Hq + m.Hkv) * m.dh * (double)m.es, st); BM_RETURN_IF(rope_inplace(dt, sv.qkv, m.QKV, T, m.Hq + m.Hkv, m.dh, c.rope_base, cu_dev,
+                              ws.tok_seq, 1.0f, st)); }
   AttnArgs at;
   at.dtype = dt; at.causal = c.mask == BM_MASK_CAUSAL; at.Hq = m.Hq; at.Hkv = m.Hkv; at.dh = m.dh;
   at.q = sv.qkv; at.k = sv.qkv + (size_t)m.QD * m.es; at.v = sv.qkv + (size_t)(m.QD + m.Hkv * m.dh) * m.es;
@@ -283,7 +283,7 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
     if (m.ada) {
       BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.d, m.QD, sv.o, m.QD, w->w_o, m.QD, sv.attn, m.d, e,
                         nullptr, 0, st));
-      BM_RETURN_IF(gate_mul(dt, sv.attn, sv.mod + 2 * m.d, 6 * m.d, ws.tok_seq, x, sv.x1, T, m.d, st));
+      { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, sv.attn, sv.mod + 2 * m.d, 6 * m.d, ws.tok_seq, x, sv.x1, T, m.d, st)); }
     } else {
       e.residual = x;
       BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.d, m.QD, sv.o, m.QD, w->w_o, m.QD, sv.x1, m.d, e,
@@ -291,19 +291,19 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
     }
   }
   // MLP half
-  BM_RETURN_IF(norm_forward(norm_args(c, m, 2, w, sv.mod, ws.tok_seq), sv.x1, ws.h, sv.stats2, 1, st));
+  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(norm_args(c, m, 2, w, sv.mod, ws.tok_seq), sv.x1, ws.h, sv.stats2, 1, st)); }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_up : nullptr;
     BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.UP, m.d, ws.h, m.d, w->w_up, m.d, sv.up, m.UP, e,
                       nullptr, 0, st));
   }
-  BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st));
+  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st)); }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_down : nullptr;
     if (m.ada) {
       BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.d, m.F, ws.a, m.F, w->w_down, m.F, sv.m, m.d, e,
                         nullptr, 0, st));
-      BM_RETURN_IF(gate_mul(dt, sv.m, sv.mod + 5 * m.d, 6 * m.d, ws.tok_seq, sv.x1, y, T, m.d, st));
+      { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, sv.m, sv.mod + 5 * m.d, 6 * m.d, ws.tok_seq, sv.x1, y, T, m.d, st)); }
     } else {
       e.residual = sv.x1;
       BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.d, m.F, ws.a, m.F, w->w_down, m.F, y, m.d, e,
@@ -344,40 +344,40 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   // ---- y = x1 + [g2 *] m,  m = a W_down^T + b_down
   const void* dm = dy;
   if (m.ada) {
-    BM_RETURN_IF(segment_colsum(dt, dy, sv.m, d, d, cu_dev, S, ws.dmod + 5 * d, 6 * d, st));
-    BM_RETURN_IF(gate_mul(dt, dy, sv.mod + 5 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(segment_colsum(dt, dy, sv.m, d, d, cu_dev, S, ws.dmod + 5 * d, 6 * d, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, dy, sv.mod + 5 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
     dm = ws.dgated;
   }
-  BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st));
+  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.F, T, dm, d, ws.a, m.F, grads->w_down, m.F, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
   if (c.linear_bias)
-    BM_RETURN_IF(colsum_accumulate(dt, dm, d, T, d, (float*)grads->b_down, ws.colsum_ws, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dm, d, T, d, (float*)grads->b_down, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
-  BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, T, m.F, st));
+  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (2.0 * m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, T, m.F, st)); }
 
   // ---- up = h2 W_up^T + b_up,  h2 = N2(x1)
   NormArgs n2 = norm_args(c, m, 2, w, sv.mod, ws.tok_seq);
-  BM_RETURN_IF(norm_forward(n2, sv.x1, ws.h, nullptr, 0, st));
+  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(n2, sv.x1, ws.h, nullptr, 0, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, m.UP, d, T, ws.dup, m.UP, ws.h, d, grads->w_up, d, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
   if (c.linear_bias)
-    BM_RETURN_IF(colsum_accumulate(dt, ws.dup, m.UP, T, m.UP, (float*)grads->b_up, ws.colsum_ws, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dup, m.UP, T, m.UP, (float*)grads->b_up, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.UP, ws.dup, m.UP, w->w_up, d, ws.dh, d, none, nullptr, 0, st));
-  BM_RETURN_IF(norm_backward(n2, sv.x1, sv.stats2, ws.dh, dy, ws.dx1, (float*)grads->norm2_g,
-                             (float*)grads->norm2_b, ws.dmod, cu_dev, S, ws.norm_ws, st));
+  { ProfScope _p(PROF_NORM, 4.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_backward(n2, sv.x1, sv.stats2, ws.dh, dy, ws.dx1, (float*)grads->norm2_g,
+                             (float*)grads->norm2_b, ws.dmod, cu_dev, S, ws.norm_ws, st)); }
 
   // ---- x1 = x + [g1 *] attn,  attn = o W_o^T + b_o
   const void* dattn = ws.dx1;
   if (m.ada) {
-    BM_RETURN_IF(segment_colsum(dt, ws.dx1, sv.attn, d, d, cu_dev, S, ws.dmod + 2 * d, 6 * d, st));
-    BM_RETURN_IF(gate_mul(dt, ws.dx1, sv.mod + 2 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(segment_colsum(dt, ws.dx1, sv.attn, d, d, cu_dev, S, ws.dmod + 2 * d, 6 * d, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, ws.dx1, sv.mod + 2 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
     dattn = ws.dgated;
   }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.QD, T, dattn, d, sv.o, m.QD, grads->w_o, m.QD, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
   if (c.linear_bias)
-    BM_RETURN_IF(colsum_accumulate(dt, dattn, d, T, d, (float*)grads->b_o, ws.colsum_ws, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dattn, d, T, d, (float*)grads->b_o, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.QD, d, dattn, d, w->w_o, m.QD, ws.d_o, m.QD, none, nullptr, 0, st));
 
   // ---- attention
@@ -392,19 +392,19 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   BM_RETURN_IF(attention_backward(at, sv.o, ws.d_o, sv.lse, dq, dk, dv, m.QKV, ws.attn_ws,
                                   ws.attn_ws_bytes, st));
   if (c.rope)
-    BM_RETURN_IF(rope_inplace(dt, ws.dqkv, m.QKV, T, m.Hq + m.Hkv, m.dh, c.rope_base, cu_dev,
-                              ws.tok_seq, -1.0f, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 2.0 * T * (m.Hq + m.Hkv) * m.dh * (double)m.es, st); BM_RETURN_IF(rope_inplace(dt, ws.dqkv, m.QKV, T, m.Hq + m.Hkv, m.dh, c.rope_base, cu_dev,
+                              ws.tok_seq, -1.0f, st)); }
 
   // ---- qkv = h W_qkv^T + b_qkv,  h = N1(x)
   NormArgs n1 = norm_args(c, m, 1, w, sv.mod, ws.tok_seq);
-  BM_RETURN_IF(norm_forward(n1, x, ws.h, nullptr, 0, st));
+  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(n1, x, ws.h, nullptr, 0, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, m.QKV, d, T, ws.dqkv, m.QKV, ws.h, d, grads->w_qkv, d, none,
                     ws.gemm_ws, ws.gemm_ws_bytes, st));
   if (c.linear_bias)
-    BM_RETURN_IF(colsum_accumulate(dt, ws.dqkv, m.QKV, T, m.QKV, (float*)grads->b_qkv, ws.colsum_ws, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dqkv, m.QKV, T, m.QKV, (float*)grads->b_qkv, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.QKV, ws.dqkv, m.QKV, w->w_qkv, d, ws.dh, d, none, nullptr, 0, st));
-  BM_RETURN_IF(norm_backward(n1, x, sv.stats1, ws.dh, ws.dx1, dx, (float*)grads->norm1_g,
-                             (float*)grads->norm1_b, ws.dmod, cu_dev, S, ws.norm_ws, st));
+  { ProfScope _p(PROF_NORM, 4.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_backward(n1, x, sv.stats1, ws.dh, ws.dx1, dx, (float*)grads->norm1_g,
+                             (float*)grads->norm1_b, ws.dmod, cu_dev, S, ws.norm_ws, st)); }
 
   // ---- adaLN: mod = silu(cond) W_ada^T + b_ada
   if (m.ada) {
@@ -413,7 +413,7 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
     BM_RETURN_IF(silu_forward(dt, cond, ws.sc, (long)S * d, st));
     BM_RETURN_IF(gemm(GEMM_TN, dt, 6 * d, d, S, ws.dmod_e, 6 * d, ws.sc, d, grads->w_ada, d, none,
                       ws.gemm_ws, ws.gemm_ws_bytes, st));
-    BM_RETURN_IF(colsum_accumulate(dt, ws.dmod_e, 6 * d, S, 6 * d, (float*)grads->b_ada, ws.colsum_ws, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dmod_e, 6 * d, S, 6 * d, (float*)grads->b_ada, ws.colsum_ws, st)); }
     GemmEpilogue e; e.out_fp32 = 1;
     BM_RETURN_IF(gemm(GEMM_NN, dt, S, d, 6 * d, ws.dmod_e, 6 * d, w->w_ada, d, ws.dsc, d, e, nullptr, 0, st));
     BM_RETURN_IF(silu_backward_f32(dt, cond, ws.dsc, dcond, (long)S * d, st));

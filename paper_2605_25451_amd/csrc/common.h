@@ -42,6 +42,18 @@ bm_status hip_fail(hipError_t e, const char* what);
     }                                                              \
   } while (0)
 
+// ---------------------------------------------------------------- profiling
+// Optional per-kernel-class timing with HIP events recorded on the launch
+// stream (bm_profile_begin / bm_profile_end).  Off: a scope costs one branch.
+enum { PROF_GEMM_NT = 0, PROF_GEMM_NN, PROF_GEMM_TN, PROF_ATTN_FWD, PROF_ATTN_BWD, PROF_NORM,
+       PROF_ELEMENTWISE, PROF_CLASSES };
+struct ProfScope {
+  int slot;
+  hipStream_t st;
+  ProfScope(int cls, double work, hipStream_t stream);
+  ~ProfScope();
+};
+
 // ---------------------------------------------------------------- device helpers
 constexpr int WAVE = 64;
 

@@ -141,7 +141,7 @@ bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, 
 // Each wavefront walks rows with a grid stride; every lane owns the same
 // columns on every row, so the gamma/beta column sums accumulate in registers
 // and leave the kernel as one partial row per workgroup.
-constexpr int NORM_BWD_MAX_BLOCKS = 1024;
+constexpr int NORM_BWD_MAX_BLOCKS = 512;
 
 template <typename T, int KIND, int NV>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(
@@ -240,13 +240,23 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
   }
 }
 
-__global__ void partial_reduce_kernel(const float* __restrict__ partial, int nparts, int stride,
-                                      int n, float* __restrict__ out) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
+// out[c] += sum over parts of partial[p*stride + c]; 64 columns per workgroup,
+// four groups of parts combined through LDS in a fixed order.
+__global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __restrict__ partial,
+                                                             int nparts, int stride, int n,
+                                                             float* __restrict__ out) {
+  __shared__ float sm[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int g = threadIdx.x >> 6;
   float s = 0.f;
-  for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * stride + c];
-  out[c] += s;
+  if (c < n)
+    for (int p = g; p < nparts; p += 4) s += partial[(size_t)p * stride + c];
+  sm[g][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (g == 0 && c < n) {
+    const int l = threadIdx.x;
+    out[c] += sm[0][l] + sm[1][l] + sm[2][l] + sm[3][l];
+  }
 }
 
 // adaLN: dshift[s,:] = sum_{t in s} dh,  dscale[s,:] = sum_{t in s} dh * xhat
@@ -334,10 +344,10 @@ bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, co
     BM_CHECK_LAUNCH("adaln_seg_grads");
     return BM_OK;
   }
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 256)), dim3(256), 0, st, partial, nb,
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(256), 0, st, partial, nb,
                      2 * a.d, a.d, dgamma);
   if (a.kind == BM_NORM_LAYERNORM)
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(256), 0, st,
                        partial + a.d, nb, 2 * a.d, a.d, dbeta);
   BM_CHECK_LAUNCH("norm_bwd_reduce");
   return BM_OK;
@@ -561,7 +571,7 @@ bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, flo
   else
     hipLaunchKernelGGL(colsum_stage1_kernel<float>, dim3(spans, chunks), dim3(256), 0, st,
                        (const float*)a, lda, T, N, partial);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(N, 256)), dim3(256), 0, st, partial, chunks, N,
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(N, 64)), dim3(256), 0, st, partial, chunks, N,
                      N, out);
   BM_CHECK_LAUNCH("colsum");
   return BM_OK;

@@ -1,13 +1,350 @@
-// bf16 MFMA GEMM (placeholder: nothing is routed here yet).
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+//
+//   NT: C[M,N]  = A[M,K] B[N,K]^T (+bias)(+residual)   linear forward
+//   NN: C[M,N]  = A[M,K] B[K,N]                        input gradient
+//   TN: C[M,N] += A[K,M]^T B[K,N]     (C fp32)         weight gradient
+//
+// One workgroup owns a BM x BN tile of C and walks K in slices of BK=64.  Both
+// operand slices are staged in LDS (two buffers: the next slice is fetched
+// from HBM into registers while the current one feeds the MFMAs, one barrier per
+// slice).  An operand whose K index is contiguous in memory is kept as
+// [row][k] with its 16-byte chunks XOR-swizzled by the row, and fragments are
+// read with ds_read_b128.  An operand whose K index is the slow one (B of NN,
+// both operands of TN) is kept as [k][row] and fragments are read with the
+// LDS transpose read (ds_read_b64_tr_b16), so no transposed copy is ever made.
+// Workgroup ids are remapped so that the workgroups of one XCD (they share an
+// L2) cover a compact block of tiles.  The K split of TN writes fp32 partial
+// tiles that a second kernel sums in a fixed order: no floating-point atomics.
 #include "common.h"
 
 namespace bm {
 
-bool gemm_mfma_supported(int, int, int, int, int, int, int, int, const GemmEpilogue&) { return false; }
-size_t gemm_mfma_scratch_bytes(int, int, int, int) { return 0; }
-bm_status gemm_mfma(int, int, int, int, const void*, int, const void*, int, void*, int,
-                    const GemmEpilogue&, void*, size_t, hipStream_t) {
-  set_error("gemm_mfma: not built"); return BM_ERR_UNSUPPORTED;
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BK = 64;          // k slice
+constexpr int KCH = BK / 8;     // 16-byte chunks per k-contiguous row
+
+struct GemmParams {
+  const bf16_t* A; const bf16_t* B; void* C;
+  const bf16_t* bias; const bf16_t* residual;
+  float* partial;               // TN with splits > 1
+  int M, N, K, lda, ldb, ldc;
+  int tiles_m, tiles_n, splits, k_per_split;
+  int out_fp32;
+};
+
+// ---- LDS layouts ---------------------------------------------------------
+// k-contiguous operand: [rows][KCH chunks]; chunk c of row r sits at c ^ ((r>>1)&7).
+__device__ inline int kc_offset(int row, int c) {          // in bf16 elements
+  return row * BK + ((c ^ ((row >> 1) & (KCH - 1))) << 3);
+}
+// transposed operand: [BK k-rows][R/8 chunks]; chunk c of k-row k sits at
+// c ^ ((k&3)<<2): a transpose read touches 4 consecutive k-rows x 32 bytes per
+// 16 lanes, and this spreads the rows of two neighbouring lane groups over
+// eight different 32-byte bank groups.
+template <int R>
+__device__ inline int tr_offset(int k, int c) {             // in bf16 elements
+  const int pos = c ^ ((k & 3) << 2);
+  return k * R + (pos << 3);
+}
+
+template <int R>
+__device__ inline bf16x8 tr_fragment(const bf16_t* lds, int row0, int k0, int lane) {
+  // 32(row) x 16(k) fragment of an operand stored [k][row]; lane l gets row
+  // row0 + l%32 and k = k0 + (l/32)*8 .. +7
+  const int gi = lane >> 4, s = lane & 15;
+  const int r = row0 + (gi & 1) * 16 + (s & 3) * 4;        // 4 consecutive rows (8 bytes)
+  const int k = k0 + (gi >> 1) * 8 + (s >> 2);
+  const int c = r >> 3, within = r & 7;
+  const bf16_t* p0 = lds + tr_offset<R>(k, c) + within;
+  const bf16_t* p1 = lds + tr_offset<R>(k + 4, c) + within;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p1);
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+__device__ inline bf16x8 kc_fragment(const bf16_t* lds, int row0, int ks, int lane) {
+  const int row = row0 + (lane & 31);
+  const int c = ks * 2 + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(lds + kc_offset(row, c));
+}
+
+// ---- global -> registers -> LDS staging -----------------------------------
+// Each thread moves CH = (R*BK/8)/NT chunks of 16 bytes per slice and operand.
+template <int R, int NT, bool TR>
+struct Stage {
+  static constexpr int CH = (R * BK / 8) / NT;
+  u32x4 v[CH];
+
+  // rows: extent of the R dimension (M or N); kmax: end of this split's k range
+  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int r0, int rows, int k0,
+                              int kmax, int tid) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int id = tid + i * NT;
+      int row, k;
+      if (TR) {            // memory [k][row]: chunk = 8 consecutive rows
+        const int kk = id / (R / 8), c = id % (R / 8);
+        k = k0 + kk; row = r0 + c * 8;
+        if (row >= rows) row = 0;
+      } else {             // memory [row][k]: chunk = 8 consecutive k
+        const int rr = id / KCH, c = id % KCH;
+        row = r0 + rr; k = k0 + c * 8;
+        if (row >= rows) row = rows - 1;
+      }
+      u32x4 val = {0u, 0u, 0u, 0u};
+      if (k < kmax) {
+        const bf16_t* p = TR ? g + (size_t)k * ld + row : g + (size_t)row * ld + k;
+        val = *reinterpret_cast<const u32x4*>(p);
+      }
+      v[i] = val;
+    }
+  }
+
+  __device__ inline void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int id = tid + i * NT;
+      int off;
+      if (TR) off = tr_offset<R>(id / (R / 8), id % (R / 8));
+      else off = kc_offset(id / KCH, id % KCH);
+      *reinterpret_cast<u32x4*>(lds + off) = v[i];
+    }
+  }
+};
+
+// XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give
+// each XCD a contiguous run of tiles, walked in column-major groups of GROUP_M
+// tile rows (operand reuse in that XCD's L2).
+__device__ inline void tile_of_block(int pid, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
+  constexpr int XCDS = 8, GROUP_M = 8;
+  int id = pid;
+  if (total % XCDS == 0) id = (pid % XCDS) * (total / XCDS) + pid / XCDS;
+  const int per_group = GROUP_M * tiles_n;
+  const int g = id / per_group;
+  const int first_m = g * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in = id % per_group;
+  *tm = first_m + in % gsize;
+  *tn = in / gsize;
+}
+
+template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACCUM_F32>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN_ = BN / WN;       // wave tile
+  constexpr int FM = TM / 32, FN = TN_ / 32;       // 32x32 fragments per wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* As[2] = {smem, smem + BM * BK};
+  bf16_t* Bs[2] = {smem + 2 * BM * BK, smem + 2 * BM * BK + BN * BK};
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int split = blockIdx.x / tiles;
+  int tm, tn;
+  tile_of_block(blockIdx.x % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int kbeg = split * p.k_per_split;
+  const int kend = min(p.K, kbeg + p.k_per_split);
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Stage<BM, NT, A_TR> sa;
+  Stage<BN, NT, B_TR> sb;
+  sa.load(p.A, p.lda, m0, p.M, kbeg, kend, tid);
+  sb.load(p.B, p.ldb, n0, p.N, kbeg, kend, tid);
+  sa.store(As[0], tid);
+  sb.store(Bs[0], tid);
+  __syncthreads();
+
+  int cur = 0;
+  for (int k0 = kbeg; k0 < kend; k0 += BK) {
+    const bool more = k0 + BK < kend;
+    if (more) {
+      sa.load(p.A, p.lda, m0, p.M, k0 + BK, kend, tid);
+      sb.load(p.B, p.ldb, n0, p.N, k0 + BK, kend, tid);
+    }
+    const bf16_t* a_lds = As[cur];
+    const bf16_t* b_lds = Bs[cur];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[FM], bfr[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int r0 = wm * TM + i * 32;
+        af[i] = A_TR ? tr_fragment<BM>(a_lds, r0, ks * 16, lane) : kc_fragment(a_lds, r0, ks, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int r0 = wn * TN_ + j * 32;
+        bfr[j] = B_TR ? tr_fragment<BN>(b_lds, r0, ks * 16, lane) : kc_fragment(b_lds, r0, ks, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      sa.store(As[cur ^ 1], tid);
+      sb.store(Bs[cur ^ 1], tid);
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+
+  // ---- epilogue: lane holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int gn = n0 + wn * TN_ + j * 32 + col_in;
+      if (gn >= p.N) continue;
+      float bias = 0.f;
+      if (!ACCUM_F32 && p.bias) bias = (float)p.bias[gn];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int gm = m0 + wm * TM + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
+        if (gm >= p.M) continue;
+        const size_t idx = (size_t)gm * p.ldc + gn;
+        float v = acc[i][j][r];
+        if (ACCUM_F32) {
+          if (p.splits > 1) p.partial[((size_t)split * p.M + gm) * p.N + gn] = v;
+          else ((float*)p.C)[idx] += v;
+        } else {
+          v += bias;
+          if (p.residual) v += (float)p.residual[idx];
+          if (p.out_fp32) ((float*)p.C)[idx] = v;
+          else ((bf16_t*)p.C)[idx] = (bf16_t)v;
+        }
+      }
+    }
+  }
+}
+
+__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                                     float* __restrict__ C, int ldc) {
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= (long)M * N) return;
+  const int m = (int)(i / N), n = (int)(i % N);
+  float4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < splits; ++k) {
+    float4 v = *reinterpret_cast<const float4*>(partial + (size_t)k * M * N + i);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  float* c = C + (size_t)m * ldc + n;
+  c[0] += s.x; c[1] += s.y; c[2] += s.z; c[3] += s.w;
+}
+
+struct Plan { int bm, bn, tiles_m, tiles_n, splits, k_per_split; };
+
+constexpr int NUM_CU = 256;
+
+Plan make_plan(int layout, int M, int N, int K) {
+  Plan pl;
+  // big tiles when they still fill the chip, else 128x128
+  long big = (long)cdiv(M, 256) * cdiv(N, 256);
+  const bool use_big = big >= NUM_CU || (layout == GEMM_TN && big * cdiv(K, 2048) >= NUM_CU);
+  pl.bm = pl.bn = use_big ? 256 : 128;
+  pl.tiles_m = cdiv(M, pl.bm); pl.tiles_n = cdiv(N, pl.bn);
+  pl.splits = 1; pl.k_per_split = cdiv(K, BK) * BK;
+  if (layout == GEMM_TN) {
+    long tiles = (long)pl.tiles_m * pl.tiles_n;
+    int want = (int)((2 * NUM_CU + tiles - 1) / tiles);          // about two workgroups per CU
+    int max_by_k = cdiv(K, 4 * BK);                               // at least 4 slices per split
+    int s = want < max_by_k ? want : max_by_k;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    pl.k_per_split = cdiv(cdiv(K, s), BK) * BK;
+    pl.splits = cdiv(K, pl.k_per_split);
+  }
+  return pl;
+}
+
+template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC>
+bm_status launch(const GemmParams& p, hipStream_t st) {
+  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    BM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_done = true;
+  }
+  dim3 grid(p.tiles_m * p.tiles_n * p.splits), block(WM * WN * 64);
+  hipLaunchKernelGGL(kern, grid, block, lds, st, p);
+  BM_CHECK_LAUNCH("gemm_mfma");
+  return BM_OK;
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc,
+                         const GemmEpilogue& epi) {
+  (void)epi; (void)ldc;
+  if (dtype != BM_DTYPE_BF16) return false;
+  if (M < 64 || N < 64 || K < 64) return false;          // tiny problems: generic kernel
+  if (lda % 8 || ldb % 8) return false;                  // 16-byte rows
+  if (layout == GEMM_NT) return K % 8 == 0;
+  if (layout == GEMM_NN) return K % 8 == 0 && N % 8 == 0;
+  return M % 8 == 0 && N % 8 == 0;                       // TN: rows are the contiguous index
+}
+
+size_t gemm_mfma_scratch_bytes(int layout, int M, int N, int K) {
+  if (layout != GEMM_TN) return 0;
+  Plan pl = make_plan(layout, M, N, K);
+  return pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
+}
+
+bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+                    void* C, int ldc, const GemmEpilogue& epi, void* scratch, size_t scratch_bytes,
+                    hipStream_t st) {
+  Plan pl = make_plan(layout, M, N, K);
+  GemmParams p;
+  p.A = (const bf16_t*)A; p.B = (const bf16_t*)B; p.C = C;
+  p.bias = (const bf16_t*)epi.bias; p.residual = (const bf16_t*)epi.residual;
+  p.partial = (float*)scratch;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
+  p.out_fp32 = epi.out_fp32;
+  if (pl.splits > 1 && (!scratch || scratch_bytes < (size_t)pl.splits * M * N * sizeof(float))) {
+    set_error("gemm TN: split reduction needs %zu scratch bytes, got %zu",
+              (size_t)pl.splits * M * N * sizeof(float), scratch_bytes);
+    return BM_ERR_WORKSPACE_TOO_SMALL;
+  }
+  bm_status rc;
+  const bool big = pl.bm == 256;
+  if (layout == GEMM_NT)
+    rc = big ? launch<256, 256, 2, 2, false, false, false>(p, st) : launch<128, 128, 2, 2, false, false, false>(p, st);
+  else if (layout == GEMM_NN)
+    rc = big ? launch<256, 256, 2, 2, false, true, false>(p, st) : launch<128, 128, 2, 2, false, true, false>(p, st);
+  else
+    rc = big ? launch<256, 256, 2, 2, true, true, true>(p, st) : launch<128, 128, 2, 2, true, true, true>(p, st);
+  BM_RETURN_IF(rc);
+  if (layout == GEMM_TN && pl.splits > 1) {
+    long n4 = ((long)M * N) / 4;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(cdiv(n4, 256)), dim3(256), 0, st,
+                       (const float*)scratch, pl.splits, M, N, (float*)C, ldc);
+    BM_CHECK_LAUNCH("splitk_reduce");
+  }
+  return BM_OK;
 }
 
 }  // namespace bm
