@@ -17,6 +17,10 @@
 // tiles that a second kernel sums in a fixed order: no floating-point atomics.
 #include "common.h"
 
+#include <stdlib.h>
+
+#include <type_traits>
+
 namespace bm {
 
 namespace {
@@ -25,6 +29,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;          // k slice
@@ -82,13 +87,20 @@ __device__ inline bf16x8 kc_fragment(const bf16_t* lds, int row0, int ks, int la
 template <int R, int NT, bool TR>
 struct Stage {
   static constexpr int CH = (R * BK / 8) / NT;
+  static constexpr int PARTS = BK / 16;          // one part per k-step of the MFMA loop
+  static constexpr int PER = CH / PARTS;
+  static_assert(CH % PARTS == 0, "tile does not split evenly over the k-steps");
   u32x4 v[CH];
+  unsigned live = 0u;   // bit i: chunk i lies inside the k range (others are stored as zeros)
 
-  // rows: extent of the R dimension (M or N); kmax: end of this split's k range
-  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int r0, int rows, int k0,
-                              int kmax, int tid) {
+  // rows: extent of the R dimension (M or N); kmax: end of this split's k range.
+  // Every load goes to a valid address, so it can stay in flight for a whole
+  // slice; out-of-range chunks are zeroed when they are stored.
+  __device__ inline void load_part(int part, const bf16_t* __restrict__ g, int ld, int r0, int rows,
+                                   int k0, int kmax, int tid) {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
+    for (int ii = 0; ii < PER; ++ii) {
+      const int i = part * PER + ii;
       const int id = tid + i * NT;
       int row, k;
       if (TR) {            // memory [k][row]: chunk = 8 consecutive rows
@@ -100,24 +112,54 @@ struct Stage {
         row = r0 + rr; k = k0 + c * 8;
         if (row >= rows) row = rows - 1;
       }
-      u32x4 val = {0u, 0u, 0u, 0u};
-      if (k < kmax) {
-        const bf16_t* p = TR ? g + (size_t)k * ld + row : g + (size_t)row * ld + k;
-        val = *reinterpret_cast<const u32x4*>(p);
-      }
-      v[i] = val;
+      const bool in = k < kmax;
+      live = (live & ~(1u << i)) | ((in ? 1u : 0u) << i);
+      const int kk = in ? k : kmax - (TR ? 1 : 8);
+      const bf16_t* p = TR ? g + (size_t)kk * ld + row : g + (size_t)row * ld + kk;
+      v[i] = *reinterpret_cast<const u32x4*>(p);
     }
   }
 
-  __device__ inline void store(bf16_t* lds, int tid) const {
+  __device__ inline void store_part(int part, bf16_t* lds, int tid) const {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
+    for (int ii = 0; ii < PER; ++ii) {
+      const int i = part * PER + ii;
       const int id = tid + i * NT;
       int off;
       if (TR) off = tr_offset<R>(id / (R / 8), id % (R / 8));
       else off = kc_offset(id / KCH, id % KCH);
-      *reinterpret_cast<u32x4*>(lds + off) = v[i];
+      u32x4 val = v[i];
+      if (!((live >> i) & 1u)) val = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(lds + off) = val;
     }
+  }
+
+  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int r0, int rows, int k0,
+                              int kmax, int tid) {
+#pragma unroll
+    for (int part = 0; part < PARTS; ++part) load_part(part, g, ld, r0, rows, k0, kmax, tid);
+  }
+  __device__ inline void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int part = 0; part < PARTS; ++part) store_part(part, lds, tid);
+  }
+};
+
+// Scheduling pattern of one k-step: after each MFMA let the scheduler place an even
+// share of the step's LDS reads (next fragments), LDS writes (parking the
+// prefetched slice) and global loads (re-arming the prefetch), so that memory
+// instructions issue in the shadow of the matrix pipeline instead of in bursts.
+template <int M, int NM, int NR, int NW, int NL>
+struct Interleave {
+  static __device__ inline void run() {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+    constexpr int r = NR * (M + 1) / NM - NR * M / NM;
+    constexpr int w = NW * (M + 1) / NM - NW * M / NM;
+    constexpr int l = NL * (M + 1) / NM - NL * M / NM;
+    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);  // DS reads
+    if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);  // DS writes
+    if constexpr (l > 0) __builtin_amdgcn_sched_group_barrier(0x020, l, 0);  // VMEM reads
+    if constexpr (M + 1 < NM) Interleave<M + 1, NM, NR, NW, NL>::run();
   }
 };
 
@@ -144,8 +186,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   constexpr int FM = TM / 32, FN = TN_ / 32;       // 32x32 fragments per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  bf16_t* As[2] = {smem, smem + BM * BK};
-  bf16_t* Bs[2] = {smem + 2 * BM * BK, smem + 2 * BM * BK + BN * BK};
+  constexpr int A_TILE = BM * BK, B_TILE = BN * BK;      // elements; buffers: A0 A1 B0 B1
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
@@ -166,74 +207,153 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Software pipeline, two slices deep: the registers of `sa`/`sb` always hold the
+  // slice after the one being multiplied.  During k-step ks of slice j, part ks of
+  // slice j+1 (fetched one whole slice ago) is written to the free LDS buffer and
+  // the same registers are re-armed with part ks of slice j+2, so HBM/L2 latency is
+  // covered by a full slice of MFMAs and memory instructions are spread between them.
   Stage<BM, NT, A_TR> sa;
   Stage<BN, NT, B_TR> sb;
   sa.load(p.A, p.lda, m0, p.M, kbeg, kend, tid);
   sb.load(p.B, p.ldb, n0, p.N, kbeg, kend, tid);
-  sa.store(As[0], tid);
-  sb.store(Bs[0], tid);
+  sa.store(smem, tid);
+  sb.store(smem + 2 * A_TILE, tid);
+  if (kbeg + BK < kend) {
+    sa.load(p.A, p.lda, m0, p.M, kbeg + BK, kend, tid);
+    sb.load(p.B, p.ldb, n0, p.N, kbeg + BK, kend, tid);
+  }
   __syncthreads();
 
-  int cur = 0;
-  for (int k0 = kbeg; k0 < kend; k0 += BK) {
-    const bool more = k0 + BK < kend;
-    if (more) {
-      sa.load(p.A, p.lda, m0, p.M, k0 + BK, kend, tid);
-      sb.load(p.B, p.ldb, n0, p.N, k0 + BK, kend, tid);
-    }
-    const bf16_t* a_lds = As[cur];
-    const bf16_t* b_lds = Bs[cur];
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[FM], bfr[FN];
+  // one slice; NEXT1: the registers hold a slice to park, NEXT2: one more to fetch.
+  // The flags are compile-time so that the steady-state loop body is branch-free
+  // (the wait-count bookkeeping of the loads then stays exact across iterations).
+  auto slice = [&](auto next1_t, auto next2_t, int k0, int cur) {
+    constexpr bool NEXT1 = decltype(next1_t)::value, NEXT2 = decltype(next2_t)::value;
+    const bf16_t* a_lds = smem + cur * A_TILE;
+    const bf16_t* b_lds = smem + 2 * A_TILE + cur * B_TILE;
+    bf16_t* a_nxt = smem + (cur ^ 1) * A_TILE;
+    bf16_t* b_nxt = smem + 2 * A_TILE + (cur ^ 1) * B_TILE;
+    // fragments of k-step ks+1 are fetched from LDS while the MFMAs of step ks run
+    bf16x8 af[2][FM], bfr[2][FN];
+    auto fetch_frags = [&](int ks, int buf) {
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int r0 = wm * TM + i * 32;
-        af[i] = A_TR ? tr_fragment<BM>(a_lds, r0, ks * 16, lane) : kc_fragment(a_lds, r0, ks, lane);
+        af[buf][i] = A_TR ? tr_fragment<BM>(a_lds, r0, ks * 16, lane) : kc_fragment(a_lds, r0, ks, lane);
       }
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
         const int r0 = wn * TN_ + j * 32;
-        bfr[j] = B_TR ? tr_fragment<BN>(b_lds, r0, ks * 16, lane) : kc_fragment(b_lds, r0, ks, lane);
+        bfr[buf][j] = B_TR ? tr_fragment<BN>(b_lds, r0, ks * 16, lane) : kc_fragment(b_lds, r0, ks, lane);
+      }
+    };
+    fetch_frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      // keep the compiler's scheduler from regrouping the memory operations of
+      // different k-steps: their spacing is what hides the latencies
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < BK / 16) fetch_frags(ks + 1, (ks + 1) & 1);
+      if (NEXT1) {
+        sa.store_part(ks, a_nxt, tid);
+        sb.store_part(ks, b_nxt, tid);
+      }
+      if (NEXT2) {
+        sa.load_part(ks, p.A, p.lda, m0, p.M, k0 + 2 * BK, kend, tid);
+        sb.load_part(ks, p.B, p.ldb, n0, p.N, k0 + 2 * BK, kend, tid);
       }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = ACCUM_F32
+              ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0)
+              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+      constexpr int NR = FM * (A_TR ? 2 : 1) + FN * (B_TR ? 2 : 1);
+      constexpr int NW = NEXT1 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
+      constexpr int NL = NEXT2 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
+      if (ks + 1 < BK / 16) Interleave<0, FM * FN, NR, NW, NL>::run();
+      else Interleave<0, FM * FN, 0, NW, NL>::run();
     }
-    if (more) {
-      sa.store(As[cur ^ 1], tid);
-      sb.store(Bs[cur ^ 1], tid);
-    }
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    cur ^= 1;
-  }
+  };
+  using yes = std::integral_constant<bool, true>;
+  using no = std::integral_constant<bool, false>;
+  int cur = 0, k0 = kbeg;
+  for (; k0 + 2 * BK < kend; k0 += BK, cur ^= 1) slice(yes{}, yes{}, k0, cur);
+  if (k0 + BK < kend) { slice(yes{}, no{}, k0, cur); k0 += BK; cur ^= 1; }
+  slice(no{}, no{}, k0, cur);
 
-  // ---- epilogue: lane holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  if (ACCUM_F32) {
+    // ---- weight-gradient epilogue: acc block (i,j) holds C rows m, lane = column n = l%32,
+    // registers = rows 8*(r/4) + 4*(l/32) + r%4; 32 lanes cover 128 contiguous bytes of fp32
+    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int gn = n0 + wn * TN_ + j * 32 + col_in;
-      if (gn >= p.N) continue;
-      float bias = 0.f;
-      if (!ACCUM_F32 && p.bias) bias = (float)p.bias[gn];
+      for (int j = 0; j < FN; ++j) {
+        const int gn = n0 + wn * TN_ + j * 32 + col_in;
+        if (gn >= p.N) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int gm = m0 + wm * TM + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
-        if (gm >= p.M) continue;
-        const size_t idx = (size_t)gm * p.ldc + gn;
-        float v = acc[i][j][r];
-        if (ACCUM_F32) {
+        for (int r = 0; r < 16; ++r) {
+          const int gm = m0 + wm * TM + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
+          if (gm >= p.M) continue;
+          const float v = acc[i][j][r];
           if (p.splits > 1) p.partial[((size_t)split * p.M + gm) * p.N + gn] = v;
-          else ((float*)p.C)[idx] += v;
-        } else {
-          v += bias;
-          if (p.residual) v += (float)p.residual[idx];
-          if (p.out_fp32) ((float*)p.C)[idx] = v;
-          else ((bf16_t*)p.C)[idx] = (bf16_t)v;
+          else ((float*)p.C)[(size_t)gm * p.ldc + gn] += v;
+        }
+      }
+    }
+  } else {
+    // ---- linear-layer epilogue.  The MFMAs ran with swapped operands, so block (i,j)
+    // holds C^T: lane = row m = l%32, registers = 4 consecutive columns n = 8g + 4*(l/32) + e.
+    // Each wavefront transposes its own 32-row strips through LDS (free after the last
+    // barrier) and then writes whole rows: 16 bytes per lane, 256 contiguous bytes per row.
+    constexpr int SLD = TN_ + 4;                         // padded fp32 row: conflict-free both ways
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * (32 * SLD);
+    constexpr int LPR = TN_ / 8;                          // lanes per output row (8 columns each)
+    constexpr int RPI = 64 / LPR;                         // rows per store instruction
+    const int m_in = lane & 31, h4 = (lane >> 5) * 4;
+    const int rcol = (lane % LPR) * 8, rrow = lane / LPR;
+    const int gn = n0 + wn * TN_ + rcol;
+    float bias[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bias[e] = 0.f;
+    if (p.bias && gn < p.N) load16(p.bias + gn, bias);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+          *reinterpret_cast<f32x4*>(stage + m_in * SLD + j * 32 + g * 8 + h4) = v;
+        }
+#pragma unroll
+      for (int t = 0; t < 32 / RPI; ++t) {
+        const int row = t * RPI + rrow;
+        const int gm = m0 + wm * TM + i * 32 + row;
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol + 4);
+        if (gm < p.M && gn < p.N) {
+          float out[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          const size_t idx = (size_t)gm * p.ldc + gn;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) out[e] += bias[e];
+          if (p.residual) {
+            float res[8];
+            load16(p.residual + idx, res);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out[e] += res[e];
+          }
+          if (p.out_fp32) {
+            float* c = (float*)p.C + idx;
+            *reinterpret_cast<f32x4*>(c) = f32x4{out[0], out[1], out[2], out[3]};
+            *reinterpret_cast<f32x4*>(c + 4) = f32x4{out[4], out[5], out[6], out[7]};
+          } else {
+            store16((bf16_t*)p.C + idx, out);
+          }
         }
       }
     }
@@ -281,7 +401,9 @@ Plan make_plan(int layout, int M, int N, int K) {
 
 template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC>
 bm_status launch(const GemmParams& p, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t lds_pipe = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t lds_epi = ACC ? 0 : (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
+  constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC>;
   static bool attr_done = false;
   if (!attr_done) {
@@ -298,13 +420,12 @@ bm_status launch(const GemmParams& p, hipStream_t st) {
 
 bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc,
                          const GemmEpilogue& epi) {
-  (void)epi; (void)ldc;
+  (void)epi;
   if (dtype != BM_DTYPE_BF16) return false;
   if (M < 64 || N < 64 || K < 64) return false;          // tiny problems: generic kernel
   if (lda % 8 || ldb % 8) return false;                  // 16-byte rows
-  if (layout == GEMM_NT) return K % 8 == 0;
-  if (layout == GEMM_NN) return K % 8 == 0 && N % 8 == 0;
-  return M % 8 == 0 && N % 8 == 0;                       // TN: rows are the contiguous index
+  if (layout == GEMM_TN) return M % 8 == 0 && N % 8 == 0;   // rows are the contiguous index
+  return K % 8 == 0 && N % 8 == 0 && ldc % 8 == 0;          // 16-byte row chunks of C
 }
 
 size_t gemm_mfma_scratch_bytes(int layout, int M, int N, int K) {
@@ -331,7 +452,12 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   }
   bm_status rc;
   const bool big = pl.bm == 256;
-  if (layout == GEMM_NT)
+  static const int variant = getenv("BM_GEMM_VARIANT") ? atoi(getenv("BM_GEMM_VARIANT")) : 0;
+  if (big && variant == 1) {
+    if (layout == GEMM_NT) rc = launch<256, 256, 2, 4, false, false, false>(p, st);
+    else if (layout == GEMM_NN) rc = launch<256, 256, 2, 4, false, true, false>(p, st);
+    else rc = launch<256, 256, 2, 4, true, true, true>(p, st);
+  } else if (layout == GEMM_NT)
     rc = big ? launch<256, 256, 2, 2, false, false, false>(p, st) : launch<128, 128, 2, 2, false, false, false>(p, st);
   else if (layout == GEMM_NN)
     rc = big ? launch<256, 256, 2, 2, false, true, false>(p, st) : launch<128, 128, 2, 2, false, true, false>(p, st);
