@@ -266,9 +266,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = ACCUM_F32
-              ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0)
-              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+          // operands swapped: the accumulator holds C^T blocks (see the epilogue)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
       constexpr int NR = FM * (A_TR ? 2 : 1) + FN * (B_TR ? 2 : 1);
       constexpr int NW = NEXT1 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
       constexpr int NL = NEXT2 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
@@ -285,29 +284,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   if (k0 + BK < kend) { slice(yes{}, no{}, k0, cur); k0 += BK; cur ^= 1; }
   slice(no{}, no{}, k0, cur);
 
-  if (ACCUM_F32) {
-    // ---- weight-gradient epilogue: acc block (i,j) holds C rows m, lane = column n = l%32,
-    // registers = rows 8*(r/4) + 4*(l/32) + r%4; 32 lanes cover 128 contiguous bytes of fp32
-    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int gn = n0 + wn * TN_ + j * 32 + col_in;
-        if (gn >= p.N) continue;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int gm = m0 + wm * TM + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
-          if (gm >= p.M) continue;
-          const float v = acc[i][j][r];
-          if (p.splits > 1) p.partial[((size_t)split * p.M + gm) * p.N + gn] = v;
-          else ((float*)p.C)[(size_t)gm * p.ldc + gn] += v;
-        }
-      }
-    }
-  } else {
-    // ---- linear-layer epilogue.  The MFMAs ran with swapped operands, so block (i,j)
-    // holds C^T: lane = row m = l%32, registers = 4 consecutive columns n = 8g + 4*(l/32) + e.
+  {
+    // ---- epilogue.  The MFMAs ran with swapped operands, so block (i,j) holds C^T:
+    // lane = row m = l%32, registers = 4 consecutive columns n = 8g + 4*(l/32) + e.
     // Each wavefront transposes its own 32-row strips through LDS (free after the last
     // barrier) and then writes whole rows: 16 bytes per lane, 256 contiguous bytes per row.
     constexpr int SLD = TN_ + 4;                         // padded fp32 row: conflict-free both ways
@@ -339,6 +318,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
         if (gm < p.M && gn < p.N) {
           float out[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           const size_t idx = (size_t)gm * p.ldc + gn;
+          if (ACCUM_F32) {
+            // weight gradient: fp32, added to C (or parked as this split's partial tile)
+            float* c = p.splits > 1 ? p.partial + ((size_t)split * p.M + gm) * p.N + gn
+                                    : (float*)p.C + idx;
+            f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+            if (p.splits == 1) {
+              c0 = *reinterpret_cast<const f32x4*>(c);
+              c1 = *reinterpret_cast<const f32x4*>(c + 4);
+            }
+            *reinterpret_cast<f32x4*>(c) = f32x4{c0[0] + out[0], c0[1] + out[1], c0[2] + out[2], c0[3] + out[3]};
+            *reinterpret_cast<f32x4*>(c + 4) = f32x4{c1[0] + out[4], c1[1] + out[5], c1[2] + out[6], c1[3] + out[7]};
+            continue;
+          }
 #pragma unroll
           for (int e = 0; e < 8; ++e) out[e] += bias[e];
           if (p.residual) {
@@ -378,31 +370,42 @@ struct Plan { int bm, bn, tiles_m, tiles_n, splits, k_per_split; };
 
 constexpr int NUM_CU = 256;
 
+// Tile size and K split from a small cost model (microseconds): workgroups run in
+// waves over the free slots (one 256x256 workgroup per CU, two 128x128 ones), each
+// pays a fixed prologue/epilogue plus a per-slice time, and a K split of the weight
+// gradient pays for writing and re-reading its fp32 partial tiles.
 Plan make_plan(int layout, int M, int N, int K) {
-  Plan pl;
-  // big tiles when they still fill the chip, else 128x128
-  long big = (long)cdiv(M, 256) * cdiv(N, 256);
-  const bool use_big = big >= NUM_CU || (layout == GEMM_TN && big * cdiv(K, 2048) >= NUM_CU);
-  pl.bm = pl.bn = use_big ? 256 : 128;
-  pl.tiles_m = cdiv(M, pl.bm); pl.tiles_n = cdiv(N, pl.bn);
-  pl.splits = 1; pl.k_per_split = cdiv(K, BK) * BK;
-  if (layout == GEMM_TN) {
-    long tiles = (long)pl.tiles_m * pl.tiles_n;
-    int want = (int)((2 * NUM_CU + tiles - 1) / tiles);          // about two workgroups per CU
-    int max_by_k = cdiv(K, 4 * BK);                               // at least 4 slices per split
-    int s = want < max_by_k ? want : max_by_k;
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    pl.k_per_split = cdiv(cdiv(K, s), BK) * BK;
-    pl.splits = cdiv(K, pl.k_per_split);
+  Plan best{};
+  double best_t = 1e30;
+  const int slices = cdiv(K, BK);
+  for (int big = 1; big >= 0; --big) {
+    const int tile = big ? 256 : 128;
+    const double t_slice = big ? 1.0 : 0.55, t_fixed = big ? 8.0 : 3.0;
+    const int slots = big ? NUM_CU : 2 * NUM_CU;
+    const long tiles = (long)cdiv(M, tile) * cdiv(N, tile);
+    const int max_split = layout == GEMM_TN ? (slices / 4 > 32 ? 32 : (slices / 4 < 1 ? 1 : slices / 4)) : 1;
+    for (int sp = 1; sp <= max_split; ++sp) {
+      const int per = cdiv(slices, sp);
+      const int splits = cdiv(slices, per);
+      if (splits != sp) continue;
+      const long waves = (tiles * splits + slots - 1) / slots;
+      double t = waves * (per * t_slice + t_fixed);
+      if (splits > 1) t += 3.0 + 2.0 * splits * (double)M * N * 4.0 / 3.0e6;
+      if (t < best_t * 0.97) {            // prefer the earlier candidate on near ties
+        best_t = t;
+        best.bm = best.bn = tile;
+        best.tiles_m = cdiv(M, tile); best.tiles_n = cdiv(N, tile);
+        best.splits = splits; best.k_per_split = per * BK;
+      }
+    }
   }
-  return pl;
+  return best;
 }
 
 template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC>
 bm_status launch(const GemmParams& p, hipStream_t st) {
   constexpr size_t lds_pipe = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  constexpr size_t lds_epi = ACC ? 0 : (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
+  constexpr size_t lds_epi = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
   constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC>;
   static bool attr_done = false;
@@ -424,7 +427,7 @@ bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, in
   if (dtype != BM_DTYPE_BF16) return false;
   if (M < 64 || N < 64 || K < 64) return false;          // tiny problems: generic kernel
   if (lda % 8 || ldb % 8) return false;                  // 16-byte rows
-  if (layout == GEMM_TN) return M % 8 == 0 && N % 8 == 0;   // rows are the contiguous index
+  if (layout == GEMM_TN) return M % 8 == 0 && N % 8 == 0 && ldc % 4 == 0;   // rows are contiguous
   return K % 8 == 0 && N % 8 == 0 && ldc % 8 == 0;          // 16-byte row chunks of C
 }
 
