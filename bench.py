@@ -56,18 +56,18 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(case, budget_tokens=2048):
+def cpu_baseline(case, budget_flops=2.0e12):
     """The oracle as it stands, timed on a bounded sample: the first sequences of
-    the same pack up to about budget_tokens tokens."""
+    the same pack up to about budget_flops algorithmic flops (10-30 s of fp64 BLAS)."""
     import numpy as np
     from oracle import block_oracle as bo
     from paper_2605_25451_amd import synth
-    ids, tok = [], 0
+    ids = []
     for s in range(case.S):
-        n = int(case.cu_seqlens[s + 1] - case.cu_seqlens[s])
-        if ids and tok + n > budget_tokens:
+        ids.append(s)
+        g, a = algorithmic_flops(case.cfg, synth.sub_case(case, ids).cu_seqlens)
+        if 3.0 * g + 3.5 * a >= budget_flops:
             break
-        ids.append(s); tok += n
     sub = synth.sub_case(case, ids)
     t0 = time.perf_counter()
     bo.block_fwd_bwd(sub.cfg, sub.params, sub.x, sub.cu_seqlens, sub.dy, sub.cond)
@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a counter yardstick for "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -173,6 +176,12 @@ def main():
         "roofline": roofline,
         "breakdown": breakdown,
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case)
     print(json.dumps(out))

@@ -114,6 +114,17 @@ __device__ inline bool find_tile(const int32_t* __restrict__ cu, int S, int rows
   return false;
 }
 
+// Linear workgroup id -> (tile id, head).  Heads vary fastest, and since workgroup
+// ids go round-robin over the 8 XCDs, head index i lands on XCD i%8: give XCD x
+// the consecutive heads x*(H/8).., so every tile of one head -- and the q heads of
+// one GQA group -- meet their K/V in the same XCD's L2.
+__device__ inline void tile_and_head(int H, int* tile, int* head) {
+  const int b = blockIdx.x;
+  const int i = b % H;
+  *tile = b / H;
+  *head = (H % 8 == 0) ? (i % 8) * (H / 8) + i / 8 : i;
+}
+
 // =============================================================================
 // forward
 // =============================================================================
@@ -124,12 +135,13 @@ template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ o, int ldo, float* __restrict__ lse,
-    int Ttot, int group, float scale_log2) {
+    int Ttot, int Hq, int group, float scale_log2) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
-  int seq, qt, nqt;
-  if (!find_tile(cu, S, FQ, blockIdx.x, &seq, &qt, &nqt)) return;
-  const int hq = blockIdx.y, hk = hq / group;
+  int seq, qt, nqt, tile_id, hq;
+  tile_and_head(Hq, &tile_id, &hq);
+  if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
+  const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int q0 = qt * FQ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -250,12 +262,12 @@ int count_tiles(const int32_t* cu_host, int S, int rows) {
 
 template <int DH>
 bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
-  dim3 grid(count_tiles(a.cu_host, a.S, FQ), a.Hq), block(256);
+  dim3 grid(count_tiles(a.cu_host, a.S, FQ) * a.Hq), block(256);
   const float sl2 = LOG2E / sqrtf((float)a.dh);
 #define BM_L(C)                                                                                  \
   hipLaunchKernelGGL((fa_fwd_kernel<DH, C>), grid, block, 0, st, (const bf16_t*)a.q,             \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.cu_dev, a.S, (bf16_t*)o, \
-                     a.Hq * a.dh, lse, a.T, a.Hq / a.Hkv, sl2)
+                     a.Hq * a.dh, lse, a.T, a.Hq, a.Hq / a.Hkv, sl2)
   if (a.causal) BM_L(true); else BM_L(false);
 #undef BM_L
   BM_CHECK_LAUNCH("fa_fwd");
@@ -291,19 +303,19 @@ constexpr int BK_Q = 64;       // query rows per step
 // dK, dV of one 128-key tile of one kv head: walks the q heads of the group and the
 // query tiles; scores are kept as S[q, key] so that P and dS are B operands as they are.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void fa_bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dk,
-    bf16_t* __restrict__ dv, int ldd, int Ttot, int group, float scale, float scale_log2) {
+    bf16_t* __restrict__ dv, int ldd, int Ttot, int Hkv, int group, float scale, float scale_log2) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * DH];
   __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * DH];
   __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
   __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
-  int seq, kt, nkt;
-  if (!find_tile(cu, S, BK_KEYS, blockIdx.x, &seq, &kt, &nkt)) return;
+  int seq, kt, nkt, tile_id, hk;
+  tile_and_head(Hkv, &tile_id, &hk);
+  if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
   kt = nkt - 1 - kt;                                   // early key tiles see the most queries
-  const int hk = blockIdx.y;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int kb0 = kt * BK_KEYS;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -418,16 +430,17 @@ __global__ __launch_bounds__(256, 1) void fa_bwd_dkdv_kernel(
 // dQ of one 128-row query tile of one q head: walks the key tiles, scores kept as
 // S^T[key, q] as in the forward kernel.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, 1) void fa_bwd_dq_kernel(
+__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dq,
-    int ldd, int Ttot, int group, float scale, float scale_log2) {
+    int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
-  int seq, qt, nqt;
-  if (!find_tile(cu, S, FQ, blockIdx.x, &seq, &qt, &nqt)) return;
-  const int hq = blockIdx.y, hk = hq / group;
+  int seq, qt, nqt, tile_id, hq;
+  tile_and_head(Hq, &tile_id, &hq);
+  if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
+  const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int q0 = qt * FQ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -524,15 +537,15 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const long n = (long)a.T * a.Hq;
   hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
                      (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
-  dim3 gkv(count_tiles(a.cu_host, a.S, BK_KEYS), a.Hkv), gq(count_tiles(a.cu_host, a.S, FQ), a.Hq);
+  dim3 gkv(count_tiles(a.cu_host, a.S, BK_KEYS) * a.Hkv), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
 #define BM_L(C)                                                                                  \
   hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,      \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
-                     lse, delta, a.cu_dev, a.S, (bf16_t*)dk, (bf16_t*)dv, ldd, a.T,              \
+                     lse, delta, a.cu_dev, a.S, (bf16_t*)dk, (bf16_t*)dv, ldd, a.T, a.Hkv,       \
                      a.Hq / a.Hkv, scale, sl2);                                                  \
   hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,        \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
-                     lse, delta, a.cu_dev, a.S, (bf16_t*)dq, ldd, a.T, a.Hq / a.Hkv, scale, sl2)
+                     lse, delta, a.cu_dev, a.S, (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2)
   if (a.causal) { BM_L(true); } else { BM_L(false); }
 #undef BM_L
   BM_CHECK_LAUNCH("fa_bwd");
@@ -542,8 +555,7 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
 }  // namespace
 
 bool attention_mfma_supported(const AttnArgs& a) {
-  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 128) && a.ld_qkv % 8 == 0 &&
-         a.Hq <= 65535;
+  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 128) && a.ld_qkv % 8 == 0;
 }
 
 bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStream_t st) {

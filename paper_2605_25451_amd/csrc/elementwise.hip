@@ -241,21 +241,30 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
 }
 
 // out[c] += sum over parts of partial[p*stride + c]; 64 columns per workgroup,
-// four groups of parts combined through LDS in a fixed order.
-__global__ __launch_bounds__(256) void partial_reduce_kernel(const float* __restrict__ partial,
-                                                             int nparts, int stride, int n,
-                                                             float* __restrict__ out) {
-  __shared__ float sm[4][64];
+// sixteen groups of parts combined through LDS in a fixed order.
+constexpr int PR_GROUPS = 16;
+__global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_kernel(
+    const float* __restrict__ partial, int nparts, int stride, int n, float* __restrict__ out) {
+  __shared__ float sm[PR_GROUPS][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int g = threadIdx.x >> 6;
-  float s = 0.f;
-  if (c < n)
-    for (int p = g; p < nparts; p += 4) s += partial[(size_t)p * stride + c];
-  sm[g][threadIdx.x & 63] = s;
+  float s0 = 0.f, s1 = 0.f;
+  if (c < n) {
+    int p = g;
+    for (; p + PR_GROUPS < nparts; p += 2 * PR_GROUPS) {
+      s0 += partial[(size_t)p * stride + c];
+      s1 += partial[(size_t)(p + PR_GROUPS) * stride + c];
+    }
+    if (p < nparts) s0 += partial[(size_t)p * stride + c];
+  }
+  sm[g][threadIdx.x & 63] = s0 + s1;
   __syncthreads();
   if (g == 0 && c < n) {
     const int l = threadIdx.x;
-    out[c] += sm[0][l] + sm[1][l] + sm[2][l] + sm[3][l];
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < PR_GROUPS; ++i) t += sm[i][l];
+    out[c] += t;
   }
 }
 
@@ -344,10 +353,10 @@ bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, co
     BM_CHECK_LAUNCH("adaln_seg_grads");
     return BM_OK;
   }
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(256), 0, st, partial, nb,
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(64 * PR_GROUPS), 0, st, partial, nb,
                      2 * a.d, a.d, dgamma);
   if (a.kind == BM_NORM_LAYERNORM)
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(256), 0, st,
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(64 * PR_GROUPS), 0, st,
                        partial + a.d, nb, 2 * a.d, a.d, dbeta);
   BM_CHECK_LAUNCH("norm_bwd_reduce");
   return BM_OK;
@@ -571,7 +580,7 @@ bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, flo
   else
     hipLaunchKernelGGL(colsum_stage1_kernel<float>, dim3(spans, chunks), dim3(256), 0, st,
                        (const float*)a, lda, T, N, partial);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(N, 64)), dim3(256), 0, st, partial, chunks, N,
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(N, 64)), dim3(64 * PR_GROUPS), 0, st, partial, chunks, N,
                      N, out);
   BM_CHECK_LAUNCH("colsum");
   return BM_OK;
