@@ -206,6 +206,83 @@ bm_status bm_build_schedule(int32_t order, int32_t M, int32_t unit_size, int32_t
 bm_status bm_check_schedule(const int32_t* ops /* host */, int32_t n_ops, int32_t M,
                             int32_t unit_size, int32_t has_generator, int32_t* peak_out);
 
+/* ---- single-GPU micro-unit executor (Sec. 3.2: opcode interpreter, runtime buffers,
+ *      module handoff; local part only, no communication operators) --------------------
+ *
+ * One pipeline stage's share on one GPU: M LLM microbatches through n_llm_blocks decoder
+ * blocks, with encoder units (n_enc_blocks ViT blocks over the images of unit_size
+ * microbatches) and generator units (n_gen_blocks adaLN blocks, one sequence of
+ * gen_tokens_per_image latent tokens per image) nested between them by an op stream from
+ * bm_build_schedule.  Glue (stand-in structure, the paper only says "projectors"):
+ *   feat   = enc_out proj_in^T                  [enc tokens, llm.hidden]
+ *   llm_in = base, with row image_rows[i] replaced by feat row i     (embed_preprocess)
+ *   cond   = llm_out[image_last_row] proj_out^T [images, gen.hidden]
+ *   loss_u = 0.5 * mean((gen_out - targets)^2)  per unit (written to loss[u]);
+ *   without generator: loss_m = <llm_out, out_grad> per microbatch (written to loss[m]).
+ * Activations live in fixed slots carved from the caller's arena (enc_slots encoder
+ * units, llm_slots LLM microbatches, one generator unit); an op that finds no free slot
+ * fails with BM_ERR_WORKSPACE_TOO_SMALL.  Weight gradients accumulate (+=) as in
+ * bm_block_backward.  All structs are host memory; pointers inside are device pointers
+ * unless named *_host. */
+typedef struct bm_executor bm_executor;
+
+typedef struct {
+  bm_block_desc enc, llm, gen;                 /* same dtype; gen.norm must be BM_NORM_ADALN     */
+  int32_t n_enc_blocks, n_llm_blocks, n_gen_blocks;   /* n_gen_blocks = 0: no generator          */
+  int32_t M, unit_size;
+  int32_t gen_tokens_per_image;
+} bm_executor_config;
+
+typedef struct {
+  const bm_block_params *enc, *llm, *gen;     /* host arrays [n_*_blocks]                        */
+  void *proj_in;                              /* [llm.hidden, enc.hidden]                        */
+  void *proj_out;                             /* [gen.hidden, llm.hidden] (with generator)       */
+} bm_executor_params;                         /* gradients: same layout, fp32                    */
+
+typedef struct {                              /* one LLM microbatch                              */
+  int32_t T, S;
+  const int32_t *cu_dev, *cu_host;            /* [S+1] documents                                 */
+  const void* base;                           /* [T, llm.hidden] text-token activations          */
+  int32_t n_image_rows;
+  const int32_t* image_rows;                  /* [n_image_rows] LLM row of each encoder token of
+                                                 this microbatch, in the unit's encoder order    */
+  int32_t n_images;
+  const int32_t* image_last_row;              /* [n_images] LLM row conditioning each image      */
+  const void* out_grad;                       /* [T, llm.hidden], used without generator         */
+} bm_microbatch;
+
+typedef struct {                              /* one unit: the images of its microbatches, in
+                                                 microbatch order                                */
+  int32_t T, S;                               /* encoder tokens and images                       */
+  const int32_t *cu_dev, *cu_host;            /* [S+1] one sequence per image                    */
+  const void* patches;                        /* [T, enc.hidden] encoder input                   */
+  const int32_t *gen_cu_dev, *gen_cu_host;    /* [S+1] = k * gen_tokens_per_image (generator)    */
+  const void* latents;                        /* [S*gen_tokens_per_image, gen.hidden]            */
+  const void* targets;                        /* same shape                                      */
+} bm_unit;
+
+/* Arena bytes needed for the given slot counts (sized for the largest unit/microbatch). */
+bm_status bm_executor_arena_bytes(const bm_executor_config* cfg, const bm_microbatch* mbs,
+                                  const bm_unit* units, int32_t enc_slots, int32_t llm_slots,
+                                  size_t* bytes);
+/* The executor keeps every pointer it is given (they must outlive it); arena is dev memory. */
+bm_status bm_executor_create(const bm_executor_config* cfg, const bm_executor_params* w,
+                             const bm_executor_params* grads, const bm_microbatch* mbs /* [M] */,
+                             const bm_unit* units /* [ceil(M/unit_size)] */, void* arena,
+                             size_t arena_bytes, int32_t enc_slots, int32_t llm_slots,
+                             bm_executor** out);
+/* ops: (opcode, index) pairs as written by bm_build_schedule; checked with bm_check_schedule. */
+bm_status bm_executor_load_schedule(bm_executor* ex, const int32_t* ops, int32_t n_ops);
+/* Runs the loaded op stream once on the stream. loss: dev float[M], overwritten per unit or
+ * microbatch as described above.  No host synchronisation. */
+bm_status bm_executor_execute(bm_executor* ex, float* loss, void* hip_stream);
+/* High-water mark, over the last execute, of the bytes of saved activations and
+ * inter-module feature/gradient buffers that were alive at the same time (weights,
+ * gradients and scratch excluded), and its encoder-unit part. */
+size_t bm_executor_peak_activation_bytes(const bm_executor* ex);
+size_t bm_executor_peak_encoder_bytes(const bm_executor* ex);
+void   bm_executor_destroy(bm_executor* ex);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,29 @@ class BlockParams(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
 
 
+class ExecutorConfig(C.Structure):
+    _fields_ = [("enc", BlockDesc), ("llm", BlockDesc), ("gen", BlockDesc),
+                ("n_enc_blocks", C.c_int32), ("n_llm_blocks", C.c_int32), ("n_gen_blocks", C.c_int32),
+                ("M", C.c_int32), ("unit_size", C.c_int32), ("gen_tokens_per_image", C.c_int32)]
+
+
+class ExecutorParams(C.Structure):
+    _fields_ = [("enc", C.POINTER(BlockParams)), ("llm", C.POINTER(BlockParams)),
+                ("gen", C.POINTER(BlockParams)), ("proj_in", C.c_void_p), ("proj_out", C.c_void_p)]
+
+
+class Microbatch(C.Structure):
+    _fields_ = [("T", C.c_int32), ("S", C.c_int32), ("cu_dev", C.c_void_p), ("cu_host", C.c_void_p),
+                ("base", C.c_void_p), ("n_image_rows", C.c_int32), ("image_rows", C.c_void_p),
+                ("n_images", C.c_int32), ("image_last_row", C.c_void_p), ("out_grad", C.c_void_p)]
+
+
+class Unit(C.Structure):
+    _fields_ = [("T", C.c_int32), ("S", C.c_int32), ("cu_dev", C.c_void_p), ("cu_host", C.c_void_p),
+                ("patches", C.c_void_p), ("gen_cu_dev", C.c_void_p), ("gen_cu_host", C.c_void_p),
+                ("latents", C.c_void_p), ("targets", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -77,6 +100,21 @@ def lib() -> C.CDLL:
         l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.bm_build_schedule.argtypes = [i32] * 6 + [pi32, pi32]
         l.bm_check_schedule.argtypes = [pi32, i32, i32, i32, i32, pi32]
+        pcfg, ppar = C.POINTER(ExecutorConfig), C.POINTER(ExecutorParams)
+        pmb, pun = C.POINTER(Microbatch), C.POINTER(Unit)
+        l.bm_executor_arena_bytes.argtypes = [pcfg, pmb, pun, i32, i32, C.POINTER(sz)]
+        l.bm_executor_create.argtypes = [pcfg, ppar, ppar, pmb, pun, vp, sz, i32, i32, C.POINTER(vp)]
+        l.bm_executor_load_schedule.argtypes = [vp, pi32, i32]
+        l.bm_executor_execute.argtypes = [vp, vp, vp]
+        l.bm_executor_peak_activation_bytes.argtypes = [vp]
+        l.bm_executor_peak_activation_bytes.restype = sz
+        l.bm_executor_peak_encoder_bytes.argtypes = [vp]
+        l.bm_executor_peak_encoder_bytes.restype = sz
+        l.bm_executor_destroy.argtypes = [vp]
+        l.bm_executor_destroy.restype = None
+        for name in ("bm_executor_arena_bytes", "bm_executor_create", "bm_executor_load_schedule",
+                     "bm_executor_execute"):
+            getattr(l, name).restype = C.c_int
         for name in ("bm_block_sizes", "bm_block_forward", "bm_block_backward", "bm_gemm",
                      "bm_attention_forward", "bm_attention_backward", "bm_build_schedule",
                      "bm_check_schedule", "bm_profile_begin", "bm_profile_end"):
@@ -218,3 +256,40 @@ def check_schedule(ops, M, unit_size, has_generator):
     peak = (C.c_int32 * 3)()
     _check(lib().bm_check_schedule(flat, len(ops), M, unit_size, int(has_generator), peak))
     return tuple(peak)
+
+
+# ---------------------------------------------------------------- executor
+
+def executor_arena_bytes(cfg: ExecutorConfig, mbs, units, enc_slots: int, llm_slots: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().bm_executor_arena_bytes(C.byref(cfg), mbs, units, enc_slots, llm_slots, C.byref(n)))
+    return n.value
+
+
+def executor_create(cfg, w: ExecutorParams, grads: ExecutorParams, mbs, units, arena, arena_bytes,
+                    enc_slots, llm_slots):
+    h = C.c_void_p()
+    _check(lib().bm_executor_create(C.byref(cfg), C.byref(w), C.byref(grads), mbs, units, _ptr(arena),
+                                    arena_bytes, enc_slots, llm_slots, C.byref(h)))
+    return h
+
+
+def executor_load_schedule(ex, ops):
+    flat = (C.c_int32 * (2 * len(ops)))(*[v for op in ops for v in op])
+    _check(lib().bm_executor_load_schedule(ex, flat, len(ops)))
+
+
+def executor_execute(ex, loss, stream=None):
+    _check(lib().bm_executor_execute(ex, _ptr(loss), _stream() if stream is None else stream))
+
+
+def executor_peak_activation_bytes(ex) -> int:
+    return lib().bm_executor_peak_activation_bytes(ex)
+
+
+def executor_peak_encoder_bytes(ex) -> int:
+    return lib().bm_executor_peak_encoder_bytes(ex)
+
+
+def executor_destroy(ex):
+    lib().bm_executor_destroy(ex)

@@ -215,3 +215,16 @@ bm_status silu_backward_f32(int dtype, const void* in, const float* g, void* out
 bm_status cast_from_f32(int dtype, const float* in, void* out, long n, hipStream_t st);
 
 }  // namespace bm
+
+// ---------------------------------------------------------------- handoff (executor)
+namespace bm {
+bm_status row_scatter(int dtype, const void* src, const int32_t* rows, void* dst, int n, int width, hipStream_t st);
+bm_status row_gather(int dtype, const void* src, const int32_t* rows, void* dst, int n, int width, hipStream_t st);
+bm_status fill_zero(void* p, size_t bytes, hipStream_t st);
+bm_status add_inplace(int dtype, void* a, const void* b, long n, hipStream_t st);
+size_t loss_scratch_bytes();
+// grad = (out - target)/n, *loss = 0.5 * mean((out - target)^2)
+bm_status mse_loss(int dtype, const void* out, const void* target, void* grad, long n, float* loss, void* scratch, hipStream_t st);
+// *loss = <out, g>
+bm_status dot_loss(int dtype, const void* out, const void* g, long n, float* loss, void* scratch, hipStream_t st);
+}  // namespace bm

@@ -165,16 +165,17 @@ class Document:
     spans: List[tuple] = field(default_factory=list)   # (kind, start, length), kind in {"image","text"}
 
 
-def documents_interleaved(rng, total: int) -> List[Document]:
+def documents_interleaved(rng, total: int, image_range=(256, 1024), text_range=(32, 512)) -> List[Document]:
     """Documents of 1..3 (image span, text span) pairs, image first.
-    Image spans uniform [256,1024] tokens, text spans uniform [32,512]."""
+    Image spans uniform [256,1024] tokens, text spans uniform [32,512] by default."""
     docs: List[Document] = []
     left = total
     while left > 0:
         n_pairs = int(rng.integers(1, 4))
         spans, pos = [], 0
         for _ in range(n_pairs):
-            li = int(rng.integers(256, 1025)); lt = int(rng.integers(32, 513))
+            li = int(rng.integers(image_range[0], image_range[1] + 1))
+            lt = int(rng.integers(text_range[0], text_range[1] + 1))
             spans.append(("image", pos, li)); pos += li
             spans.append(("text", pos, lt)); pos += lt
         if pos > left:                      # clip the document to what is left
@@ -319,3 +320,95 @@ def sub_case(case: BlockCase, seq_ids) -> BlockCase:
     cond = case.cond[list(seq_ids)] if case.cond is not None else None
     return BlockCase(case.cfg, cu_from_lengths(lens), case.x[rows], case.params, case.dy[rows],
                      cond, None, case.name + "_sub")
+
+
+# --------------------------------------------------------------------------
+# one pipeline stage's share: LLM microbatches with nested encoder / generator units
+# --------------------------------------------------------------------------
+
+@dataclass
+class MicrobatchCase:
+    cu_seqlens: np.ndarray            # documents
+    base: np.ndarray                  # fp32 [T, llm.hidden] text-token activations (image rows get overwritten)
+    image_rows: np.ndarray            # int32: LLM row of every encoder token of this microbatch, image by image
+    image_lens: List[int]             # patch tokens per image
+    image_last_row: np.ndarray        # int32 [n_images]: LLM row of the last token of each image span
+    out_grad: np.ndarray              # fp32 [T, llm.hidden] (loss = <out, out_grad> when there is no generator)
+
+    @property
+    def T(self) -> int:
+        return int(self.cu_seqlens[-1])
+
+
+@dataclass
+class UnitCase:
+    cu_seqlens: np.ndarray            # one sequence per image
+    patches: np.ndarray               # fp32 [T_enc, enc.hidden]
+    latents: Optional[np.ndarray]     # fp32 [S*tokens_per_image, gen.hidden]
+    targets: Optional[np.ndarray]
+
+
+@dataclass
+class StageCase:
+    enc_cfg: BlockConfig
+    llm_cfg: BlockConfig
+    gen_cfg: Optional[BlockConfig]
+    enc_params: List[Dict[str, np.ndarray]]
+    llm_params: List[Dict[str, np.ndarray]]
+    gen_params: List[Dict[str, np.ndarray]]
+    proj_in: np.ndarray               # [llm.hidden, enc.hidden]
+    proj_out: Optional[np.ndarray]    # [gen.hidden, llm.hidden]
+    microbatches: List[MicrobatchCase]
+    units: List[UnitCase]
+    unit_size: int
+    tokens_per_image: int
+
+    @property
+    def M(self) -> int:
+        return len(self.microbatches)
+
+    @property
+    def has_generator(self) -> bool:
+        return self.gen_cfg is not None and len(self.gen_params) > 0
+
+
+def make_stage(enc_cfg: BlockConfig, llm_cfg: BlockConfig, gen_cfg: Optional[BlockConfig], n_enc: int,
+               n_llm: int, n_gen: int, M: int, unit_size: int, llm_tokens: int, seed: int,
+               image_range=(256, 1024), text_range=(32, 512), tokens_per_image: int = 256,
+               proj_std: float = 0.02) -> StageCase:
+    """Draw order: per-block parameters (encoder, LLM, generator), projectors, then per microbatch
+    (documents, base, out_grad), then per unit (patches, latents, targets)."""
+    rng = np.random.default_rng(seed)
+    dt = llm_cfg.dtype
+    enc_p = [draw_params(rng, enc_cfg) for _ in range(n_enc)]
+    llm_p = [draw_params(rng, llm_cfg) for _ in range(n_llm)]
+    gen_p = [draw_params(rng, gen_cfg) for _ in range(n_gen)] if gen_cfg is not None else []
+    proj_in = to_storage(_normal(rng, (llm_cfg.hidden, enc_cfg.hidden), proj_std), dt)
+    proj_out = (to_storage(_normal(rng, (gen_cfg.hidden, llm_cfg.hidden), proj_std), dt)
+                if gen_cfg is not None and n_gen > 0 else None)
+    mbs = []
+    for _ in range(M):
+        docs = documents_interleaved(rng, llm_tokens, image_range, text_range)
+        cu = cu_from_lengths([d.length for d in docs])
+        rows, lens, last = [], [], []
+        for di, d in enumerate(docs):
+            for kind, st, ln in d.spans:
+                if kind == "image" and ln > 0:
+                    r0 = int(cu[di]) + st
+                    rows.extend(range(r0, r0 + ln)); lens.append(ln); last.append(r0 + ln - 1)
+        base = to_storage(_normal(rng, (llm_tokens, llm_cfg.hidden)), dt)
+        og = to_storage(_normal(rng, (llm_tokens, llm_cfg.hidden)), dt)
+        mbs.append(MicrobatchCase(cu, base, np.asarray(rows, dtype=np.int32), lens,
+                                  np.asarray(last, dtype=np.int32), og))
+    units = []
+    for u0 in range(0, M, unit_size):
+        lens = [l for m in mbs[u0:u0 + unit_size] for l in m.image_lens]
+        cu = cu_from_lengths(lens)
+        patches = to_storage(_normal(rng, (int(cu[-1]), enc_cfg.hidden)), dt)
+        lat = tgt = None
+        if proj_out is not None:
+            lat = to_storage(_normal(rng, (len(lens) * tokens_per_image, gen_cfg.hidden)), dt)
+            tgt = to_storage(_normal(rng, (len(lens) * tokens_per_image, gen_cfg.hidden)), dt)
+        units.append(UnitCase(cu, patches, lat, tgt))
+    return StageCase(enc_cfg, llm_cfg, gen_cfg if proj_out is not None else None, enc_p, llm_p, gen_p,
+                     proj_in, proj_out, mbs, units, unit_size, tokens_per_image)

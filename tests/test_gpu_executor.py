@@ -1,0 +1,129 @@
+"""The micro-unit executor on the GPU against the stage oracle (needs a GPU):
+nested order == oracle (sequential) within tolerance, orders agree with each other,
+encoder activation memory stays flat under the nested order and grows with the
+batch under the compute-efficient order (Sec. 2.2 "Performance analysis", Sec. 3.1)."""
+import numpy as np
+import pytest
+
+from oracle import executor_oracle as eo
+from paper_2605_25451_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def stage_fp32(gen=True, M=5, unit_size=1, seed=70):
+    f32 = synth.DTYPE_FP32
+    enc = synth.scaled(synth.vit_tiny(f32), hidden=64, n_q_heads=4, n_kv_heads=4, head_dim=16, mlp_hidden=96)
+    llm = synth.scaled(synth.decoder_7b(f32), hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, mlp_hidden=192)
+    g = synth.scaled(synth.dit_block(f32), hidden=64, n_q_heads=4, n_kv_heads=4, head_dim=16, mlp_hidden=96)
+    return synth.make_stage(enc, llm, g if gen else None, 2, 2, 2 if gen else 0, M, unit_size, 256, seed,
+                            image_range=(16, 48), text_range=(8, 32), tokens_per_image=8, proj_std=0.1)
+
+
+def stage_bf16(gen=True, M=4, unit_size=1, seed=71):
+    enc = synth.scaled(synth.vit_large(), hidden=256, n_q_heads=4, n_kv_heads=4, mlp_hidden=512)
+    llm = synth.scaled(synth.decoder_8b_gqa(), hidden=512, n_q_heads=4, n_kv_heads=2, mlp_hidden=1024)
+    g = synth.scaled(synth.dit_block(), hidden=288, n_q_heads=4, n_kv_heads=4, head_dim=72, mlp_hidden=576)
+    return synth.make_stage(enc, llm, g if gen else None, 2, 2, 2 if gen else 0, M, unit_size, 1024, seed,
+                            image_range=(64, 200), text_range=(16, 64), tokens_per_image=64, proj_std=0.05)
+
+
+def run_gpu(stage, order, enc_slots=3, llm_slots=None, depth=3):
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd.stage import StageOnDevice
+    dev = StageOnDevice(stage)
+    llm_slots = llm_slots or depth * stage.unit_size          # microbatches in flight under 1F1B
+    dev.create(enc_slots, llm_slots)
+    ops = bm.build_schedule(order, stage.M, stage.unit_size, 3, depth, int(stage.has_generator))
+    print("order", order, "ops", len(ops), flush=True)
+    dev.run(ops)
+    loss, grads = dev.results()
+    peak = dev.peak_bytes()
+    dev.destroy()
+    return loss, grads, peak
+
+
+def compare(got, ref, tol):
+    loss, grads = got
+    rloss, rgrads = ref
+    errs = {"loss": rel_err(loss, np.asarray(rloss))}
+    for grp in ("enc", "llm", "gen"):
+        for b, (g, rg) in enumerate(zip(grads[grp], rgrads[grp])):
+            for k in rg:
+                errs[f"{grp}{b}.{k}"] = rel_err(g[k], rg[k])
+    errs["proj_in"] = rel_err(grads["proj_in"], rgrads["proj_in"])
+    if "proj_out" in rgrads:
+        errs["proj_out"] = rel_err(grads["proj_out"], rgrads["proj_out"])
+    worst = max(errs, key=errs.get)
+    print(f"worst {worst} {errs[worst]:.2e}; loss err {errs['loss']:.2e}", flush=True)
+    assert errs[worst] <= tol, {k: v for k, v in errs.items() if v > tol}
+
+
+@pytest.mark.parametrize("gen,unit_size", [(True, 1), (True, 2), (False, 1)])
+def test_nested_order_matches_oracle_fp32(gen, unit_size):
+    from paper_2605_25451_amd import binding as bm
+    stage = stage_fp32(gen, 5, unit_size)
+    loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
+    # a stage chains six blocks and two projectors: ten times the single-block bound
+    compare((loss, grads), eo.run_stage(stage), 1e-4)
+
+
+def test_nested_order_matches_oracle_bf16():
+    from paper_2605_25451_amd import binding as bm
+    stage = stage_bf16(True, 4, 1)
+    loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
+    # bf16 through six chained blocks: twice the single-block bound
+    compare((loss, grads), eo.run_stage(stage), 4e-2)
+
+
+def test_orders_agree_and_encoder_memory_is_flat():
+    from paper_2605_25451_amd import binding as bm
+    peaks = {}
+    for M in (4, 8, 12):
+        stage = stage_fp32(True, M, 1, seed=80)
+        U = len(stage.units)
+        res = {}
+        for order, slots in ((bm.ORDER_NESTED, 3), (bm.ORDER_COMPUTE_EFFICIENT, U), (bm.ORDER_SEQUENTIAL, 1)):
+            loss, grads, peak = run_gpu(stage, order, enc_slots=slots, llm_slots=3)
+            res[order] = (loss, grads)
+            peaks[(M, order)] = peak
+        base_loss, base_grads = res[bm.ORDER_SEQUENTIAL]
+        for order in (bm.ORDER_NESTED, bm.ORDER_COMPUTE_EFFICIENT):
+            loss, grads = res[order]
+            assert np.array_equal(loss, base_loss)                       # same kernels, same inputs per unit
+            for grp in ("enc", "llm", "gen"):
+                for g, rg in zip(grads[grp], base_grads[grp]):
+                    for k in rg:
+                        assert rel_err(g[k], rg[k]) <= 1e-5, (order, grp, k)   # accumulation order only
+    enc_nested = [peaks[(M, bm.ORDER_NESTED)][1] for M in (4, 8, 12)]
+    enc_eff = [peaks[(M, bm.ORDER_COMPUTE_EFFICIENT)][1] for M in (4, 8, 12)]
+    print("encoder peak bytes nested", enc_nested, "compute-efficient", enc_eff, flush=True)
+    assert max(enc_nested) <= 1.35 * min(enc_nested)                      # three live units whatever M is
+    assert enc_eff[2] >= 2.5 * enc_eff[0]                                 # grows with the number of units
+    assert enc_eff[0] >= 1.2 * enc_nested[0] and enc_eff[2] >= 3.0 * enc_nested[2]
+    # total peak: nested stays below the compute-efficient order at the larger batches
+    assert peaks[(12, bm.ORDER_NESTED)][0] < peaks[(12, bm.ORDER_COMPUTE_EFFICIENT)][0]
+
+
+def test_executor_errors():
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd.stage import StageOnDevice
+    stage = stage_fp32(True, 6, 1, seed=81)
+    dev = StageOnDevice(stage)
+    dev.create(2, 3)                                                    # two encoder slots: nested needs three
+    ops = bm.build_schedule(bm.ORDER_NESTED, 6, 1, 3, 3, 1)
+    with pytest.raises(bm.BmError) as e:
+        dev.run(ops)
+    assert e.value.status == bm.BM_ERR_WORKSPACE_TOO_SMALL
+    bad = list(ops)
+    i, j = bad.index((bm.OP_LLM_FWD, 0)), bad.index((bm.OP_ENC_FWD, 0))
+    bad[i], bad[j] = bad[j], bad[i]
+    with pytest.raises(bm.BmError):
+        bm.executor_load_schedule(dev.ex, bad)
+    import torch
+    torch.cuda.synchronize()
+    dev.destroy()
