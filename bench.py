@@ -3,6 +3,7 @@
 transformer block on one MI355X, through the C-ABI library.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit]
+  python bench.py --workload config5 --batch 8|16|32 [--unit-size 1] [--steps K]
 
 One step = bm_block_forward + bm_block_backward over one batch of seeded
 synthetic packed tokens that is already resident in HBM.  Prints ONE JSON line:
@@ -84,12 +85,59 @@ def cpu_baseline(case, budget_flops=2.0e12):
                       f"({sub.T} of {case.T} tokens) of the same pack, {dt:.1f} s"}
 
 
+def run_stage_workload(args):
+    """config 5: one pipeline stage's share -- 4 decoder blocks over `batch` microbatches of
+    8192 packed tokens, with 6 ViT-L blocks per encoder unit and 2 DiT blocks per generator
+    unit nested between them; reports LLM tokens/s and peak activation bytes for the nested
+    and the compute-efficient order."""
+    import torch
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd import synth
+    from paper_2605_25451_amd.stage import StageOnDevice
+    M = args.batch
+    stage = synth.make_stage(synth.vit_large(), synth.decoder_7b(), synth.dit_block(), 6, 4, 2, M,
+                             args.unit_size, 8192, seed=4)
+    dev = StageOnDevice(stage)
+    U = len(stage.units)
+    depth = 3
+    out = {"metric": "stage tokens/s and peak activation bytes (config 5)", "unit": "tokens/s",
+           "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "higher_is_better": True,
+           "config": {"workload": "config5_stage", "microbatches": M, "unit_size": args.unit_size,
+                      "llm_tokens_per_microbatch": 8192, "blocks": "6 ViT-L / 4 decoder-7B / 2 DiT",
+                      "encoder_tokens": [int(u.cu_seqlens[-1]) for u in stage.units]}, "orders": {}}
+    for name, order, slots in (("nested", bm.ORDER_NESTED, min(3, U)),
+                               ("compute_efficient", bm.ORDER_COMPUTE_EFFICIENT, U)):
+        torch.cuda.reset_peak_memory_stats()
+        arena = dev.create(slots, depth * args.unit_size)
+        ops = bm.build_schedule(order, M, args.unit_size, 3, depth, 1)
+        dev.zero_grads()
+        dev.run(ops)                                     # warm-up step
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dev.run(ops)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        peak, peak_enc = dev.peak_bytes()
+        out["orders"][name] = {"ms_per_step": dt * 1e3, "tokens_per_s": M * 8192 / dt,
+                               "peak_activation_bytes": peak, "peak_encoder_bytes": peak_enc,
+                               "arena_bytes": arena,
+                               "torch_max_memory_allocated": torch.cuda.max_memory_allocated()}
+        dev.destroy()
+    out["value"] = out["orders"]["nested"]["tokens_per_s"]
+    out["ms_per_step"] = out["orders"]["nested"]["ms_per_step"]
+    out["steps"] = args.steps
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2")
+    ap.add_argument("--batch", type=int, default=8, help="microbatches (config5 only)")
+    ap.add_argument("--unit-size", type=int, default=1, help="microbatches per unit (config5 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a counter yardstick for "
@@ -107,6 +155,8 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     bm.lib()                                    # fail loudly if the HIP library is missing
+    if args.workload == "config5":
+        return run_stage_workload(args)
     case = make_workload(args.workload)
     dev = CaseOnDevice(case)
     gemm_f, attn_f = algorithmic_flops(case.cfg, case.cu_seqlens)

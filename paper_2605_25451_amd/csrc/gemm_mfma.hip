@@ -85,82 +85,71 @@ __device__ inline bf16x8 kc_fragment(const bf16_t* lds, int row0, int ks, int la
 
 // ---- global -> registers -> LDS staging -----------------------------------
 // Each thread moves CH = (R*BK/8)/NT chunks of 16 bytes per slice and operand.
-template <int R, int NT, bool TR>
+// A chunk's position inside a slice never changes, so its global offset (relative
+// to a wave-uniform slice base pointer that the caller advances) and its LDS offset
+// are computed once; per slice a chunk costs one load and one LDS store.
+template <int R, int NT, bool TR, bool KTAIL>
 struct Stage {
   static constexpr int CH = (R * BK / 8) / NT;
   static constexpr int PARTS = BK / 16;          // one part per k-step of the MFMA loop
   static constexpr int PER = CH / PARTS;
   static_assert(CH % PARTS == 0, "tile does not split evenly over the k-steps");
   u32x4 v[CH];
-  unsigned live = 0u;   // bit i: chunk i lies inside the k range (others are stored as zeros)
+  uint32_t goff[CH];    // element offset from the slice base pointer
+  unsigned live = 0u;   // KTAIL: bit i = chunk i lies inside the k range (else stored as zeros)
 
-  // rows: extent of the R dimension (M or N); kmax: end of this split's k range.
-  // Every load goes to a valid address, so it can stay in flight for a whole
-  // slice; out-of-range chunks are zeroed when they are stored.
-  __device__ inline void load_part(int part, const bf16_t* __restrict__ g, int ld, int r0, int rows,
-                                   int k0, int kmax, int tid) {
+  // k index of chunk i inside a slice
+  __device__ static inline int chunk_k(int i, int tid) {
+    const int id = tid + i * NT;
+    return TR ? id / (R / 8) : (id % KCH) * 8;
+  }
+  // rows_left: how many rows of the R dimension are valid from this tile's first row on
+  __device__ inline void init(int ld, int rows_left, int tid) {
 #pragma unroll
-    for (int ii = 0; ii < PER; ++ii) {
-      const int i = part * PER + ii;
+    for (int i = 0; i < CH; ++i) {
       const int id = tid + i * NT;
-      int row, k;
       if (TR) {            // memory [k][row]: chunk = 8 consecutive rows
-        const int kk = id / (R / 8), c = id % (R / 8);
-        k = k0 + kk; row = r0 + c * 8;
-        if (row >= rows) row = 0;
+        int row = (id % (R / 8)) * 8;
+        if (row >= rows_left) row = 0;
+        goff[i] = (uint32_t)(id / (R / 8)) * (uint32_t)ld + (uint32_t)row;
       } else {             // memory [row][k]: chunk = 8 consecutive k
-        const int rr = id / KCH, c = id % KCH;
-        row = r0 + rr; k = k0 + c * 8;
-        if (row >= rows) row = rows - 1;
+        int row = id / KCH;
+        if (row >= rows_left) row = rows_left - 1;
+        goff[i] = (uint32_t)row * (uint32_t)ld + (uint32_t)(id % KCH) * 8u;
       }
-      const bool in = k < kmax;
+    }
+  }
+
+  // base: this tile's first row at the slice's first k (wave-uniform); k_left = valid k from there
+  __device__ inline void load_one(int i, const bf16_t* __restrict__ base, int ld, int k_left, int tid) {
+    uint32_t o = goff[i];
+    if (KTAIL) {
+      // keep the address valid and remember to store zeros instead
+      const int kk = chunk_k(i, tid);
+      const bool in = kk < k_left;
       live = (live & ~(1u << i)) | ((in ? 1u : 0u) << i);
-      const int kk = in ? k : kmax - (TR ? 1 : 8);
-      const bf16_t* p = TR ? g + (size_t)kk * ld + row : g + (size_t)row * ld + kk;
-      v[i] = *reinterpret_cast<const u32x4*>(p);
+      if (!in) o -= TR ? (uint32_t)(kk - (k_left - 1)) * (uint32_t)ld : (uint32_t)(kk - (k_left - 8));
     }
+    v[i] = *reinterpret_cast<const u32x4*>(base + o);
   }
 
-  __device__ inline void store_part(int part, bf16_t* lds, int tid) const {
-#pragma unroll
-    for (int ii = 0; ii < PER; ++ii) {
-      const int i = part * PER + ii;
-      const int id = tid + i * NT;
-      int off;
-      if (TR) off = tr_offset<R>(id / (R / 8), id % (R / 8));
-      else off = kc_offset(id / KCH, id % KCH);
-      u32x4 val = v[i];
-      if (!((live >> i) & 1u)) val = u32x4{0u, 0u, 0u, 0u};
-      *reinterpret_cast<u32x4*>(lds + off) = val;
-    }
+  __device__ inline void store_one(int i, bf16_t* lds, int tid) const {
+    const int id = tid + i * NT;
+    int off;
+    if (TR) off = tr_offset<R>(id / (R / 8), id % (R / 8));
+    else off = kc_offset(id / KCH, id % KCH);
+    u32x4 val = v[i];
+    if (KTAIL && !((live >> i) & 1u)) val = u32x4{0u, 0u, 0u, 0u};
+    *reinterpret_cast<u32x4*>(lds + off) = val;
   }
 
-  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int r0, int rows, int k0,
-                              int kmax, int tid) {
+  __device__ inline void load(const bf16_t* __restrict__ base, int ld, int k_left, int tid) {
 #pragma unroll
-    for (int part = 0; part < PARTS; ++part) load_part(part, g, ld, r0, rows, k0, kmax, tid);
+    for (int i = 0; i < CH; ++i) load_one(i, base, ld, k_left, tid);
   }
   __device__ inline void store(bf16_t* lds, int tid) const {
 #pragma unroll
-    for (int part = 0; part < PARTS; ++part) store_part(part, lds, tid);
-  }
-};
-
-// Scheduling pattern of one k-step: after each MFMA let the scheduler place an even
-// share of the step's LDS reads (next fragments), LDS writes (parking the
-// prefetched slice) and global loads (re-arming the prefetch), so that memory
-// instructions issue in the shadow of the matrix pipeline instead of in bursts.
-template <int M, int NM, int NR, int NW, int NL>
-struct Interleave {
-  static __device__ inline void run() {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
-    constexpr int r = NR * (M + 1) / NM - NR * M / NM;
-    constexpr int w = NW * (M + 1) / NM - NW * M / NM;
-    constexpr int l = NL * (M + 1) / NM - NL * M / NM;
-    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);  // DS reads
-    if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);  // DS writes
-    if constexpr (l > 0) __builtin_amdgcn_sched_group_barrier(0x020, l, 0);  // VMEM reads
-    if constexpr (M + 1 < NM) Interleave<M + 1, NM, NR, NW, NL>::run();
+    for (int i = 0; i < CH; ++i) store_one(i, lds, tid);
   }
 };
 
@@ -180,7 +169,7 @@ __device__ inline void tile_of_block(int pid, int total, int tiles_m, int tiles_
   *tn = in / gsize;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACCUM_F32>
+template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACCUM_F32, bool KTAIL>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN_ = BN / WN;       // wave tile
@@ -213,15 +202,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   // slice j+1 (fetched one whole slice ago) is written to the free LDS buffer and
   // the same registers are re-armed with part ks of slice j+2, so HBM/L2 latency is
   // covered by a full slice of MFMAs and memory instructions are spread between them.
-  Stage<BM, NT, A_TR> sa;
-  Stage<BN, NT, B_TR> sb;
-  sa.load(p.A, p.lda, m0, p.M, kbeg, kend, tid);
-  sb.load(p.B, p.ldb, n0, p.N, kbeg, kend, tid);
+  Stage<BM, NT, A_TR, KTAIL> sa;
+  Stage<BN, NT, B_TR, KTAIL> sb;
+  sa.init(p.lda, p.M - m0, tid);
+  sb.init(p.ldb, p.N - n0, tid);
+  // slice base pointers (wave-uniform): first row of the tile at k = kbeg
+  const bf16_t* a_base = A_TR ? p.A + (size_t)kbeg * p.lda + m0 : p.A + (size_t)m0 * p.lda + kbeg;
+  const bf16_t* b_base = B_TR ? p.B + (size_t)kbeg * p.ldb + n0 : p.B + (size_t)n0 * p.ldb + kbeg;
+  const size_t a_step = A_TR ? (size_t)BK * p.lda : (size_t)BK;
+  const size_t b_step = B_TR ? (size_t)BK * p.ldb : (size_t)BK;
+  sa.load(a_base, p.lda, kend - kbeg, tid);
+  sb.load(b_base, p.ldb, kend - kbeg, tid);
   sa.store(smem, tid);
   sb.store(smem + 2 * A_TILE, tid);
   if (kbeg + BK < kend) {
-    sa.load(p.A, p.lda, m0, p.M, kbeg + BK, kend, tid);
-    sb.load(p.B, p.ldb, n0, p.N, kbeg + BK, kend, tid);
+    sa.load(a_base + a_step, p.lda, kend - kbeg - BK, tid);
+    sb.load(b_base + b_step, p.ldb, kend - kbeg - BK, tid);
   }
   __syncthreads();
 
@@ -249,31 +245,49 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
       }
     };
     fetch_frags(0, 0);
+    // One k-step = FM*FN MFMAs.  Its memory operations -- the FM+FN fragment reads of
+    // the next k-step, the LDS parks of this step's share of slice j+1 and the global
+    // loads that re-arm the same registers with slice j+2 -- are dealt out evenly, one
+    // small group after each MFMA, and pinned there with scheduling barriers so that
+    // they issue in the shadow of the matrix pipeline instead of in bursts.
+    constexpr int PA = Stage<BM, NT, A_TR, KTAIL>::PER, PB = Stage<BN, NT, B_TR, KTAIL>::PER;
+    const bf16_t* a_g2 = a_base + (size_t)((k0 - kbeg) / BK + 2) * a_step;   // slice j+2
+    const bf16_t* b_g2 = b_base + (size_t)((k0 - kbeg) / BK + 2) * b_step;
+    const int k_left2 = kend - k0 - 2 * BK;
+    constexpr int SLOTS = FM * FN;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      // keep the compiler's scheduler from regrouping the memory operations of
-      // different k-steps: their spacing is what hides the latencies
-      __builtin_amdgcn_sched_barrier(0);
-      if (ks + 1 < BK / 16) fetch_frags(ks + 1, (ks + 1) & 1);
-      if (NEXT1) {
-        sa.store_part(ks, a_nxt, tid);
-        sb.store_part(ks, b_nxt, tid);
-      }
-      if (NEXT2) {
-        sa.load_part(ks, p.A, p.lda, m0, p.M, k0 + 2 * BK, kend, tid);
-        sb.load_part(ks, p.B, p.ldb, n0, p.N, k0 + 2 * BK, kend, tid);
-      }
+      const int nb = (ks + 1) & 1;
+      constexpr int NOPS = FM + FN + 2 * (PA + PB);
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int t = 0; t < SLOTS; ++t) {
+        const int i = t / FN, j = t % FN;
+        // operands swapped: the accumulator holds C^T blocks (see the epilogue)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-          // operands swapped: the accumulator holds C^T blocks (see the epilogue)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
-      constexpr int NR = FM * (A_TR ? 2 : 1) + FN * (B_TR ? 2 : 1);
-      constexpr int NW = NEXT1 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
-      constexpr int NL = NEXT2 ? Stage<BM, NT, A_TR>::PER + Stage<BN, NT, B_TR>::PER : 0;
-      if (ks + 1 < BK / 16) Interleave<0, FM * FN, NR, NW, NL>::run();
-      else Interleave<0, FM * FN, 0, NW, NL>::run();
+        for (int o = t * NOPS / SLOTS; o < (t + 1) * NOPS / SLOTS; ++o) {
+          if (o < FM) {
+            if (ks + 1 < BK / 16) {
+              const int r0 = wm * TM + o * 32;
+              af[nb][o] = A_TR ? tr_fragment<BM>(a_lds, r0, (ks + 1) * 16, lane) : kc_fragment(a_lds, r0, ks + 1, lane);
+            }
+          } else if (o < FM + FN) {
+            if (ks + 1 < BK / 16) {
+              const int r0 = wn * TN_ + (o - FM) * 32;
+              bfr[nb][o - FM] = B_TR ? tr_fragment<BN>(b_lds, r0, (ks + 1) * 16, lane) : kc_fragment(b_lds, r0, ks + 1, lane);
+            }
+          } else if (o < FM + FN + PA) {
+            if (NEXT1) sa.store_one(ks * PA + (o - FM - FN), a_nxt, tid);
+          } else if (o < FM + FN + PA + PB) {
+            if (NEXT1) sb.store_one(ks * PB + (o - FM - FN - PA), b_nxt, tid);
+          } else if (o < FM + FN + 2 * PA + PB) {
+            if (NEXT2) sa.load_one(ks * PA + (o - FM - FN - PA - PB), a_g2, p.lda, k_left2, tid);
+          } else {
+            if (NEXT2) sb.load_one(ks * PB + (o - FM - FN - 2 * PA - PB), b_g2, p.ldb, k_left2, tid);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
@@ -413,12 +427,12 @@ Plan make_plan(int layout, int M, int N, int K) {
   return best;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC>
-bm_status launch(const GemmParams& p, hipStream_t st) {
+template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC, bool KTAIL>
+bm_status launch_k(const GemmParams& p, hipStream_t st) {
   constexpr size_t lds_pipe = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
   constexpr size_t lds_epi = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
   constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC, KTAIL>;
   static bool attr_done = false;
   if (!attr_done) {
     BM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -428,6 +442,13 @@ bm_status launch(const GemmParams& p, hipStream_t st) {
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);
   BM_CHECK_LAUNCH("gemm_mfma");
   return BM_OK;
+}
+
+// the zero-filling variant only when a k range is not a whole number of slices
+template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC>
+bm_status launch(const GemmParams& p, hipStream_t st) {
+  if (p.K % BK) return launch_k<BM, BN, WM, WN, A_TR, B_TR, ACC, true>(p, st);
+  return launch_k<BM, BN, WM, WN, A_TR, B_TR, ACC, false>(p, st);
 }
 
 }  // namespace
@@ -466,12 +487,7 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   }
   bm_status rc;
   const bool big = pl.bm == 256;
-  static const int variant = getenv("BM_GEMM_VARIANT") ? atoi(getenv("BM_GEMM_VARIANT")) : 0;
-  if (big && variant == 1) {
-    if (layout == GEMM_NT) rc = launch<256, 256, 2, 4, false, false, false>(p, st);
-    else if (layout == GEMM_NN) rc = launch<256, 256, 2, 4, false, true, false>(p, st);
-    else rc = launch<256, 256, 2, 4, true, true, true>(p, st);
-  } else if (layout == GEMM_NT)
+  if (layout == GEMM_NT)
     rc = big ? launch<256, 256, 2, 2, false, false, false>(p, st) : launch<128, 128, 2, 2, false, false, false>(p, st);
   else if (layout == GEMM_NN)
     rc = big ? launch<256, 256, 2, 2, false, true, false>(p, st) : launch<128, 128, 2, 2, false, true, false>(p, st);
