@@ -44,6 +44,28 @@ def algorithmic_flops(cfg, cu):
     return gemm, attn
 
 
+def measured_peaks():
+    """What this chip sustains: register-resident MFMA loop and a streaming copy."""
+    import torch
+    from paper_2605_25451_amd import binding as bm
+    out = torch.zeros(16, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    blocks, iters = 256 * 4, 4000
+    bm.probe_mfma(blocks, 200, out)
+    e0.record(); bm.probe_mfma(blocks, iters, out); e1.record(); torch.cuda.synchronize()
+    mfma = blocks * 4 * iters * 16 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
+    src.zero_()
+    bm.probe_copy(src, dst, n)
+    e0.record()
+    for _ in range(5):
+        bm.probe_copy(src, dst, n)
+    e1.record(); torch.cuda.synchronize()
+    hbm = 5 * 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": hbm}
+
+
 def make_workload(name):
     from paper_2605_25451_amd import synth
     if name == "config2":
@@ -225,6 +247,7 @@ def main():
         "tokens_per_s": case.T / (ms_per_step * 1e-3),
         "roofline": roofline,
         "breakdown": breakdown,
+        "measured_peaks": measured_peaks(),
     }
     if args.copy_calibration:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()

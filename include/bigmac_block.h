@@ -181,6 +181,13 @@ enum { BM_PROF_GEMM_NT = 0, BM_PROF_GEMM_NN = 1, BM_PROF_GEMM_TN = 2, BM_PROF_AT
 bm_status bm_profile_begin(void);
 bm_status bm_profile_end(double* ms /* host */, double* work /* host */, int64_t* launches /* host */);
 
+/* Yardsticks for the roofline denominators (the caller times them on the stream):
+ * bm_probe_mfma launches `blocks` workgroups of 4 wavefronts that each issue iters*16
+ * register-resident v_mfma_f32_32x32x16_bf16 (32768 flop each) with no memory traffic;
+ * bm_probe_copy streams bytes (multiple of 16) from src to dst (dev), 2*bytes of HBM traffic. */
+bm_status bm_probe_mfma(int32_t blocks, int32_t iters, float* out_dev, void* hip_stream);
+bm_status bm_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+
 /* ---- nested schedule (host only; Sec. 3.1 and the BuildSchedule figure) ------------ */
 
 enum { BM_OP_ENC_FWD = 0, BM_OP_ENC_BWD = 1, BM_OP_LLM_FWD = 2, BM_OP_LLM_BWD = 3,

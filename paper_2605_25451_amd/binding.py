@@ -98,6 +98,10 @@ def lib() -> C.CDLL:
                                                           i32, vp, vp, vp, i32, vp, sz, vp])
         l.bm_profile_begin.argtypes = []
         l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        l.bm_probe_mfma.argtypes = [i32, i32, vp, vp]
+        l.bm_probe_copy.argtypes = [vp, vp, sz, vp]
+        l.bm_probe_mfma.restype = C.c_int
+        l.bm_probe_copy.restype = C.c_int
         l.bm_build_schedule.argtypes = [i32] * 6 + [pi32, pi32]
         l.bm_check_schedule.argtypes = [pi32, i32, i32, i32, i32, pi32]
         pcfg, ppar = C.POINTER(ExecutorConfig), C.POINTER(ExecutorParams)
@@ -221,6 +225,14 @@ def attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, c
                                        cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
                                        _ptr(dv), ld_dqkv, _ptr(scratch), scratch_bytes,
                                        _stream() if stream is None else stream))
+
+
+def probe_mfma(blocks, iters, out, stream=None):
+    _check(lib().bm_probe_mfma(blocks, iters, _ptr(out), _stream() if stream is None else stream))
+
+
+def probe_copy(src, dst, nbytes, stream=None):
+    _check(lib().bm_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream() if stream is None else stream))
 
 
 PROF_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "norm", "elementwise")

@@ -180,7 +180,9 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
       sv.load(vbase, ld, (kt + 1) * FK, L, tid);
     }
     const int key0 = kt * FK;
-    // S^T = K Q^T : 2 blocks of 32 keys x 32 queries
+    // S^T = K Q^T for both 32-key blocks first: the MFMAs of block 1 run while the
+    // softmax arithmetic of block 0 occupies the vector unit, and the P V MFMAs of
+    // block 0 run under the softmax of block 1.
     f32x16 sacc[FK / 32];
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
@@ -193,48 +195,46 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     }
     // mask: keys past the sequence end, and keys after the query under a causal mask
     const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
-    float mx = -INFINITY;
-#pragma unroll
-    for (int b = 0; b < FK / 32; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float s = sacc[b][r] * scale_log2;
-        if (need_mask) {
-          const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          if (key >= L || (CAUSAL && key > qpos)) s = -INFINITY;
-        }
-        sacc[b][r] = s;
-        mx = fmaxf(mx, s);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);                 // finite: key 0 is visible to every query
-    const float corr = exp2f(m - m_new);
-    m = m_new;
-    float psum = 0.f;
-    bf16x8 pb[FK / 32][2];
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
+      float mx = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(sacc[b][r] - m_new);
+        if (need_mask) {
+          const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (key >= L || (CAUSAL && key > qpos)) sacc[b][r] = -INFINITY;
+        }
+        mx = fmaxf(mx, sacc[b][r]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+      // Lazy rescaling: the running maximum only moves (and O, l are only rescaled)
+      // when some row's maximum grew by more than 2^8; until then probabilities are
+      // taken relative to the older maximum (they stay below 2^8, exact in fp32).
+      if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
+        const float m_new = fmaxf(m, mx);
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);   // m = -inf at the start: 0
+        m = m_new;
+        lsum *= corr;
+#pragma unroll
+        for (int j = 0; j < DH / 32; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[j][r] *= corr;
+      }
+      float psum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], scale_log2, -m));   // masked: exp2(-inf) = 0
         sacc[b][r] = p;
         psum += p;
       }
-      pb[b][0] = acc_to_operand(sacc[b], 0);
-      pb[b][1] = acc_to_operand(sacc[b], 1);
-    }
-    lsum = lsum * corr + psum;
-#pragma unroll
-    for (int j = 0; j < DH / 32; ++j) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[j][r] *= corr;
+      lsum += psum;
+      const bf16x8 p0 = acc_to_operand(sacc[b], 0), p1 = acc_to_operand(sacc[b], 1);
       // O^T += V^T P^T
 #pragma unroll
-      for (int b = 0; b < FK / 32; ++b)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols<DH>(Vs, j * 32, b * 32 + t * 16, lane), pb[b][t], oacc[j], 0, 0, 0);
+      for (int j = 0; j < DH / 32; ++j) {
+        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Vs, j * 32, b * 32, lane), p0, oacc[j], 0, 0, 0);
+        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Vs, j * 32, b * 32 + 16, lane), p1, oacc[j], 0, 0, 0);
+      }
     }
   }
   lsum += __shfl_xor(lsum, 32, 64);
@@ -365,17 +365,21 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const int q0 = qstart + (it % nqt) * BK_Q;
     const bool need_mask = (q0 + BK_Q > L) || (kb0 + BK_KEYS > L) ||
                            (CAUSAL && q0 < kb0 + wave * 32 + 32);
-    bf16x8 pb[BK_Q / 32][2], dsb[BK_Q / 32][2];
+    // S = Q K^T and dP = dO V^T for both 32-query blocks first, then per block the
+    // softmax arithmetic (under the other block's MFMAs) followed by its dV / dK MFMAs.
+    f32x16 sacc[BK_Q / 32], dpacc[BK_Q / 32];
 #pragma unroll
     for (int qb = 0; qb < BK_Q / 32; ++qb) {
-      f32x16 sacc, dpacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; dpacc[qb][r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Qs, qb * 32, ks, lane), kf[ks], sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ds, qb * 32, ks, lane), vf[ks], dpacc, 0, 0, 0);
+        sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Qs, qb * 32, ks, lane), kf[ks], sacc[qb], 0, 0, 0);
+        dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ds, qb * 32, ks, lane), vf[ks], dpacc[qb], 0, 0, 0);
       }
+    }
+#pragma unroll
+    for (int qb = 0; qb < BK_Q / 32; ++qb) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int qoff = qb * 32 + g * 8 + half * 4;
@@ -384,29 +388,25 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
-          float p = exp2f(sacc[r] * scale_log2 - l4[e]);
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][r], scale_log2, -l4[e]));
           if (need_mask) {
             const int qi = q0 + qoff + e;
             if (qi >= L || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
           }
-          sacc[r] = p;
-          dpacc[r] = p * (dpacc[r] - d4[e]);
+          sacc[qb][r] = p;
+          dpacc[qb][r] = p * (dpacc[qb][r] - d4[e]);
         }
       }
-      pb[qb][0] = acc_to_operand(sacc, 0); pb[qb][1] = acc_to_operand(sacc, 1);
-      dsb[qb][0] = acc_to_operand(dpacc, 0); dsb[qb][1] = acc_to_operand(dpacc, 1);
+      const bf16x8 p0 = acc_to_operand(sacc[qb], 0), p1 = acc_to_operand(sacc[qb], 1);
+      const bf16x8 s0 = acc_to_operand(dpacc[qb], 0), s1 = acc_to_operand(dpacc[qb], 1);
+#pragma unroll
+      for (int j = 0; j < DH / 32; ++j) {
+        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ds, j * 32, qb * 32, lane), p0, dvacc[j], 0, 0, 0);
+        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ds, j * 32, qb * 32 + 16, lane), p1, dvacc[j], 0, 0, 0);
+        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Qs, j * 32, qb * 32, lane), s0, dkacc[j], 0, 0, 0);
+        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Qs, j * 32, qb * 32 + 16, lane), s1, dkacc[j], 0, 0, 0);
+      }
     }
-#pragma unroll
-    for (int j = 0; j < DH / 32; ++j)
-#pragma unroll
-      for (int qb = 0; qb < BK_Q / 32; ++qb)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols<DH>(Ds, j * 32, qb * 32 + t * 16, lane), pb[qb][t], dvacc[j], 0, 0, 0);
-          dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols<DH>(Qs, j * 32, qb * 32 + t * 16, lane), dsb[qb][t], dkacc[j], 0, 0, 0);
-        }
   }
   if (kpos < L) {
     bf16_t* pk = dk + (size_t)(lo + kpos) * ldd + hk * DH;
@@ -483,36 +483,35 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
     }
     const int key0 = kt * FK;
     const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
-    bf16x8 dsb[FK / 32][2];
+    f32x16 sacc[FK / 32], dpacc[FK / 32];
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
-      f32x16 sacc, dpacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { sacc[b][r] = 0.f; dpacc[b][r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks], sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Vs, b * 32, ks, lane), dof[ks], dpacc, 0, 0, 0);
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks], sacc[b], 0, 0, 0);
+        dpacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Vs, b * 32, ks, lane), dof[ks], dpacc[b], 0, 0, 0);
       }
+    }
+#pragma unroll
+    for (int b = 0; b < FK / 32; ++b) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = exp2f(sacc[r] * scale_log2 - my_lse);
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], scale_log2, -my_lse));
         if (need_mask) {
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (key >= L || (CAUSAL && key > qpos)) p = 0.f;
         }
-        dpacc[r] = p * (dpacc[r] - my_delta);
+        dpacc[b][r] = p * (dpacc[b][r] - my_delta);
       }
-      dsb[b][0] = acc_to_operand(dpacc, 0); dsb[b][1] = acc_to_operand(dpacc, 1);
+      const bf16x8 s0 = acc_to_operand(dpacc[b], 0), s1 = acc_to_operand(dpacc[b], 1);
+#pragma unroll
+      for (int j = 0; j < DH / 32; ++j) {
+        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ks, j * 32, b * 32, lane), s0, dqacc[j], 0, 0, 0);
+        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ks, j * 32, b * 32 + 16, lane), s1, dqacc[j], 0, 0, 0);
+      }
     }
-#pragma unroll
-    for (int j = 0; j < DH / 32; ++j)
-#pragma unroll
-      for (int b = 0; b < FK / 32; ++b)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols<DH>(Ks, j * 32, b * 32 + t * 16, lane), dsb[b][t], dqacc[j], 0, 0, 0);
   }
   if (qpos < L) {
     bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
