@@ -46,8 +46,10 @@ ProfScope::~ProfScope() {
 }
 
 size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype) {
-  if (dtype != BM_DTYPE_BF16) return 0;
-  return gemm_mfma_scratch_bytes(layout, M, N, K);
+  // an upper bound over both back ends (the choice also depends on strides)
+  const size_t g = gemm_generic_scratch_bytes(M, N, K);
+  const size_t m = dtype == BM_DTYPE_BF16 ? gemm_mfma_scratch_bytes(layout, M, N, K) : 0;
+  return g > m ? g : m;
 }
 
 bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int lda, const void* B,
@@ -57,7 +59,7 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
   ProfScope prof(PROF_GEMM_NT + layout, 2.0 * M * N * K, st);
   if (gemm_mfma_supported(layout, dtype, M, N, K, lda, ldb, ldc, epi))
     return gemm_mfma(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
-  return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, st);
+  return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
 }
 
 }  // namespace bm

@@ -35,13 +35,35 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// ---- swizzled [rows][DH] bf16 tile ------------------------------------------
+// Head sizes: 64 and 128 fit the 32x32x16 MFMA exactly; 72 (the DiT blocks) is run
+// with its contraction padded to 80 and its output rows padded to 96 by zero chunks
+// that exist only in LDS and registers, never in HBM.
 template <int DH>
+struct HeadDim {
+  static constexpr int KS = (DH + 15) / 16;    // k=16 steps when dh is the contraction index
+  static constexpr int NB = (DH + 31) / 32;    // 32-row blocks when dh is an output index
+  static constexpr int DHL = NB * 32;          // LDS row width in elements
+  static constexpr int VCH = DH / 8;           // 16-byte chunks of a row that hold data
+};
+
+// ---- swizzled [rows][DHL] bf16 tile -----------------------------------------
+template <int DHL>
 __device__ inline int tile_off(int row, int c) {   // element offset of 16-byte chunk c of a row
   int f;
-  if (DH == 128) f = ((row & 3) << 2) | ((row >> 2) & 3);
+  if (DHL == 128) f = ((row & 3) << 2) | ((row >> 2) & 3);
+  else if (DHL == 96) f = (row >> 2) & 3;
   else { const int v = row >> 1; f = ((v & 1) << 2) | ((v >> 1) & 3); }
-  return row * DH + ((c ^ f) << 3);
+  return row * DHL + ((c ^ f) << 3);
+}
+
+// 8 consecutive dh values (chunk c) of a global row as an MFMA operand; zeros past dh
+template <int DH>
+__device__ inline bf16x8 load_chunk(const bf16_t* row, int c) {
+  if (DH % 16 == 0 || c < HeadDim<DH>::VCH) return *reinterpret_cast<const bf16x8*>(row + c * 8);
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.f;
+  return z;
 }
 
 // operand fragment, rows of the tile are the MFMA row/col index, dh is the k index:
@@ -79,8 +101,10 @@ __device__ inline bf16x8 acc_to_operand(const f32x16& a, int t) {
 // ---- global <-> LDS staging of a [ROWS][DH] tile by NT threads ----------------
 template <int ROWS, int DH, int NT>
 struct TileStage {
-  static constexpr int CPR = DH / 8;
+  static constexpr int DHL = HeadDim<DH>::DHL;
+  static constexpr int CPR = DHL / 8;
   static constexpr int CH = ROWS * CPR / NT;
+  static_assert((ROWS * CPR) % NT == 0, "tile does not split evenly over the threads");
   u32x4 v[CH];
   // rows beyond nrows are clamped to the last valid row (their results are masked or unused)
   __device__ inline void load(const bf16_t* __restrict__ g, int ld, int row0, int nrows, int tid) {
@@ -89,14 +113,17 @@ struct TileStage {
       const int id = tid + i * NT;
       int row = row0 + id / CPR;
       if (row >= nrows) row = nrows - 1;
-      v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + (id % CPR) * 8);
+      if (DHL == DH || id % CPR < HeadDim<DH>::VCH)
+        v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + (id % CPR) * 8);
+      else
+        v[i] = u32x4{0u, 0u, 0u, 0u};                 // padding chunks of the LDS row
     }
   }
   __device__ inline void store(bf16_t* t, int tid) const {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int id = tid + i * NT;
-      *reinterpret_cast<u32x4*>(t + tile_off<DH>(id / CPR, id % CPR)) = v[i];
+      *reinterpret_cast<u32x4*>(t + tile_off<DHL>(id / CPR, id % CPR)) = v[i];
     }
   }
 };
@@ -136,8 +163,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ o, int ldo, float* __restrict__ lse,
     int Ttot, int Hq, int group, float scale_log2) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
@@ -149,15 +176,15 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   const int qpos = q0 + wave * 32 + (lane & 31);          // this lane's query (column of S^T)
   const int qrow = min(qpos, L - 1);
 
-  bf16x8 qf[DH / 16];
+  bf16x8 qf[HeadDim<DH>::KS];
   {
-    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH + half * 8;
+    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH;
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) qf[ks] = load_chunk<DH>(qp, ks * 2 + half);
   }
-  f32x16 oacc[DH / 32];
+  f32x16 oacc[HeadDim<DH>::NB];
 #pragma unroll
-  for (int j = 0; j < DH / 32; ++j)
+  for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[j][r] = 0.f;
   float m = -INFINITY, lsum = 0.f;
@@ -189,8 +216,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < DH / 16; ++ks)
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks],
+      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks)
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ks, b * 32, ks, lane), qf[ks],
                                                           sacc[b], 0, 0, 0);
     }
     // mask: keys past the sequence end, and keys after the query under a causal mask
@@ -216,7 +243,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
         m = m_new;
         lsum *= corr;
 #pragma unroll
-        for (int j = 0; j < DH / 32; ++j)
+        for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[j][r] *= corr;
       }
@@ -231,9 +258,9 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
       const bf16x8 p0 = acc_to_operand(sacc[b], 0), p1 = acc_to_operand(sacc[b], 1);
       // O^T += V^T P^T
 #pragma unroll
-      for (int j = 0; j < DH / 32; ++j) {
-        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Vs, j * 32, b * 32, lane), p0, oacc[j], 0, 0, 0);
-        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Vs, j * 32, b * 32 + 16, lane), p1, oacc[j], 0, 0, 0);
+      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
+        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Vs, j * 32, b * 32, lane), p0, oacc[j], 0, 0, 0);
+        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Vs, j * 32, b * 32 + 16, lane), p1, oacc[j], 0, 0, 0);
       }
     }
   }
@@ -242,13 +269,14 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     const float inv = 1.0f / lsum;
     bf16_t* op = o + (size_t)(lo + qpos) * ldo + hq * DH;
 #pragma unroll
-    for (int j = 0; j < DH / 32; ++j)
+    for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         bf16x4 w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(oacc[j][g * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + j * 32 + g * 8 + half * 4) = w;
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH)
+          *reinterpret_cast<bf16x4*>(op + j * 32 + g * 8 + half * 4) = w;
       }
     if (half == 0) lse[(size_t)hq * Ttot + lo + qpos] = (m + log2f(lsum)) * LN2;
   }
@@ -303,13 +331,13 @@ constexpr int BK_Q = 64;       // query rows per step
 // dK, dV of one 128-key tile of one kv head: walks the q heads of the group and the
 // query tiles; scores are kept as S[q, key] so that P and dS are B operands as they are.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dk,
     bf16_t* __restrict__ dv, int ldd, int Ttot, int Hkv, int group, float scale, float scale_log2) {
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * HeadDim<DH>::DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
   __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
   int seq, kt, nkt, tile_id, hk;
@@ -322,19 +350,19 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   const int kpos = kb0 + wave * 32 + (lane & 31);       // this lane's key (column of S)
   const int krow = min(kpos, L - 1);
 
-  bf16x8 kf[DH / 16], vf[DH / 16];
+  bf16x8 kf[HeadDim<DH>::KS], vf[HeadDim<DH>::KS];
   {
-    const bf16_t* kp = k + (size_t)(lo + krow) * ld + hk * DH + half * 8;
-    const bf16_t* vp = v + (size_t)(lo + krow) * ld + hk * DH + half * 8;
+    const bf16_t* kp = k + (size_t)(lo + krow) * ld + hk * DH;
+    const bf16_t* vp = v + (size_t)(lo + krow) * ld + hk * DH;
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(vp + ks * 16);
+    for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
+      kf[ks] = load_chunk<DH>(kp, ks * 2 + half);
+      vf[ks] = load_chunk<DH>(vp, ks * 2 + half);
     }
   }
-  f32x16 dkacc[DH / 32], dvacc[DH / 32];
+  f32x16 dkacc[HeadDim<DH>::NB], dvacc[HeadDim<DH>::NB];
 #pragma unroll
-  for (int j = 0; j < DH / 32; ++j)
+  for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[j][r] = 0.f; dvacc[j][r] = 0.f; }
 
@@ -373,9 +401,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; dpacc[qb][r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < DH / 16; ++ks) {
-        sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Qs, qb * 32, ks, lane), kf[ks], sacc[qb], 0, 0, 0);
-        dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ds, qb * 32, ks, lane), vf[ks], dpacc[qb], 0, 0, 0);
+      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
+        sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Qs, qb * 32, ks, lane), kf[ks], sacc[qb], 0, 0, 0);
+        dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ds, qb * 32, ks, lane), vf[ks], dpacc[qb], 0, 0, 0);
       }
     }
 #pragma unroll
@@ -400,11 +428,11 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
       const bf16x8 p0 = acc_to_operand(sacc[qb], 0), p1 = acc_to_operand(sacc[qb], 1);
       const bf16x8 s0 = acc_to_operand(dpacc[qb], 0), s1 = acc_to_operand(dpacc[qb], 1);
 #pragma unroll
-      for (int j = 0; j < DH / 32; ++j) {
-        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ds, j * 32, qb * 32, lane), p0, dvacc[j], 0, 0, 0);
-        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ds, j * 32, qb * 32 + 16, lane), p1, dvacc[j], 0, 0, 0);
-        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Qs, j * 32, qb * 32, lane), s0, dkacc[j], 0, 0, 0);
-        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Qs, j * 32, qb * 32 + 16, lane), s1, dkacc[j], 0, 0, 0);
+      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
+        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32, lane), p0, dvacc[j], 0, 0, 0);
+        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32 + 16, lane), p1, dvacc[j], 0, 0, 0);
+        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32, lane), s0, dkacc[j], 0, 0, 0);
+        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32 + 16, lane), s1, dkacc[j], 0, 0, 0);
       }
     }
   }
@@ -412,7 +440,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     bf16_t* pk = dk + (size_t)(lo + kpos) * ldd + hk * DH;
     bf16_t* pv = dv + (size_t)(lo + kpos) * ldd + hk * DH;
 #pragma unroll
-    for (int j = 0; j < DH / 32; ++j)
+    for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         bf16x4 wk, wv;
@@ -421,8 +449,10 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
           wk[e] = (bf16_t)(dkacc[j][g * 4 + e] * scale);
           wv[e] = (bf16_t)dvacc[j][g * 4 + e];
         }
-        *reinterpret_cast<bf16x4*>(pk + j * 32 + g * 8 + half * 4) = wk;
-        *reinterpret_cast<bf16x4*>(pv + j * 32 + g * 8 + half * 4) = wv;
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH) {
+          *reinterpret_cast<bf16x4*>(pk + j * 32 + g * 8 + half * 4) = wk;
+          *reinterpret_cast<bf16x4*>(pv + j * 32 + g * 8 + half * 4) = wv;
+        }
       }
   }
 }
@@ -430,13 +460,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 // dQ of one 128-row query tile of one q head: walks the key tiles, scores kept as
 // S^T[key, q] as in the forward kernel.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
+__global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dq,
     int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
@@ -447,21 +477,21 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
   const int qpos = q0 + wave * 32 + (lane & 31);
   const int qrow = min(qpos, L - 1);
 
-  bf16x8 qf[DH / 16], dof[DH / 16];
+  bf16x8 qf[HeadDim<DH>::KS], dof[HeadDim<DH>::KS];
   {
-    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH + half * 8;
-    const bf16_t* dp = d_o + (size_t)(lo + qrow) * ldo + hq * DH + half * 8;
+    const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH;
+    const bf16_t* dp = d_o + (size_t)(lo + qrow) * ldo + hq * DH;
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-      dof[ks] = *reinterpret_cast<const bf16x8*>(dp + ks * 16);
+    for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
+      qf[ks] = load_chunk<DH>(qp, ks * 2 + half);
+      dof[ks] = load_chunk<DH>(dp, ks * 2 + half);
     }
   }
   const float my_lse = lse[(size_t)hq * Ttot + lo + qrow] * LOG2E;
   const float my_delta = delta[(size_t)hq * Ttot + lo + qrow];
-  f32x16 dqacc[DH / 32];
+  f32x16 dqacc[HeadDim<DH>::NB];
 #pragma unroll
-  for (int j = 0; j < DH / 32; ++j)
+  for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqacc[j][r] = 0.f;
 
@@ -489,9 +519,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[b][r] = 0.f; dpacc[b][r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < DH / 16; ++ks) {
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Ks, b * 32, ks, lane), qf[ks], sacc[b], 0, 0, 0);
-        dpacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(Vs, b * 32, ks, lane), dof[ks], dpacc[b], 0, 0, 0);
+      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ks, b * 32, ks, lane), qf[ks], sacc[b], 0, 0, 0);
+        dpacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Vs, b * 32, ks, lane), dof[ks], dpacc[b], 0, 0, 0);
       }
     }
 #pragma unroll
@@ -507,22 +537,23 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void fa_bwd_dq_kernel(
       }
       const bf16x8 s0 = acc_to_operand(dpacc[b], 0), s1 = acc_to_operand(dpacc[b], 1);
 #pragma unroll
-      for (int j = 0; j < DH / 32; ++j) {
-        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ks, j * 32, b * 32, lane), s0, dqacc[j], 0, 0, 0);
-        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(Ks, j * 32, b * 32 + 16, lane), s1, dqacc[j], 0, 0, 0);
+      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
+        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ks, j * 32, b * 32, lane), s0, dqacc[j], 0, 0, 0);
+        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ks, j * 32, b * 32 + 16, lane), s1, dqacc[j], 0, 0, 0);
       }
     }
   }
   if (qpos < L) {
     bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
 #pragma unroll
-    for (int j = 0; j < DH / 32; ++j)
+    for (int j = 0; j < HeadDim<DH>::NB; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         bf16x4 w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(dqacc[j][g * 4 + e] * scale);
-        *reinterpret_cast<bf16x4*>(pq + j * 32 + g * 8 + half * 4) = w;
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH)
+          *reinterpret_cast<bf16x4*>(pq + j * 32 + g * 8 + half * 4) = w;
       }
   }
 }
@@ -554,11 +585,12 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
 }  // namespace
 
 bool attention_mfma_supported(const AttnArgs& a) {
-  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 128) && a.ld_qkv % 8 == 0;
+  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 72 || a.dh == 128) && a.ld_qkv % 8 == 0;
 }
 
 bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
   if (a.dh == 128) return fwd_launch<128>(a, o, lse, st);
+  if (a.dh == 72) return fwd_launch<72>(a, o, lse, st);
   return fwd_launch<64>(a, o, lse, st);
 }
 
@@ -570,6 +602,7 @@ bm_status attention_backward_mfma(const AttnArgs& a, const void* o, const void* 
                                   void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
                                   size_t, hipStream_t st) {
   if (a.dh == 128) return bwd_launch<128>(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
+  if (a.dh == 72) return bwd_launch<72>(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
   return bwd_launch<64>(a, o, d_o, lse, dq, dk, dv, ld_dqkv, (float*)scratch, st);
 }
 

@@ -92,7 +92,10 @@ size_t max_gemm_tn_scratch(const Dims& m, int dtype) {
   v = gemm_scratch_bytes(GEMM_TN, m.UP, m.d, m.T, dtype); b = v > b ? v : b;
   v = gemm_scratch_bytes(GEMM_TN, m.d, m.QD, m.T, dtype); b = v > b ? v : b;
   v = gemm_scratch_bytes(GEMM_TN, m.QKV, m.d, m.T, dtype); b = v > b ? v : b;
-  if (m.ada) { v = gemm_scratch_bytes(GEMM_TN, 6 * m.d, m.d, m.S, dtype); b = v > b ? v : b; }
+  if (m.ada) {
+    v = gemm_scratch_bytes(GEMM_TN, 6 * m.d, m.d, m.S, dtype); b = v > b ? v : b;
+    v = gemm_scratch_bytes(GEMM_NN, m.S, m.d, 6 * m.d, dtype); b = v > b ? v : b;
+  }
   return b;
 }
 
@@ -415,7 +418,8 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
                       ws.gemm_ws, ws.gemm_ws_bytes, st));
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dmod_e, 6 * d, S, 6 * d, (float*)grads->b_ada, ws.colsum_ws, st)); }
     GemmEpilogue e; e.out_fp32 = 1;
-    BM_RETURN_IF(gemm(GEMM_NN, dt, S, d, 6 * d, ws.dmod_e, 6 * d, w->w_ada, d, ws.dsc, d, e, nullptr, 0, st));
+    BM_RETURN_IF(gemm(GEMM_NN, dt, S, d, 6 * d, ws.dmod_e, 6 * d, w->w_ada, d, ws.dsc, d, e, ws.gemm_ws,
+                      ws.gemm_ws_bytes, st));
     BM_RETURN_IF(silu_backward_f32(dt, cond, ws.dsc, dcond, (long)S * d, st));
   }
   return BM_OK;

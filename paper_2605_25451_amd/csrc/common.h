@@ -134,9 +134,10 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
                size_t scratch_bytes, hipStream_t st);
 
 // generic (any shape, fp32 FMA) and MFMA (bf16) back ends
+size_t gemm_generic_scratch_bytes(int M, int N, int K);
 bm_status gemm_generic(int layout, int dtype, int M, int N, int K, const void* A, int lda,
                        const void* B, int ldb, void* C, int ldc, const GemmEpilogue& epi,
-                       hipStream_t st);
+                       void* scratch, size_t scratch_bytes, hipStream_t st);
 bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc,
                          const GemmEpilogue& epi);
 size_t gemm_mfma_scratch_bytes(int layout, int M, int N, int K);

@@ -16,11 +16,14 @@ namespace {
 constexpr int GT = 64;   // tile edge
 constexpr int GK = 16;   // k slice
 
+// With k_per_split < K the grid's z index selects a k range and the workgroup stores
+// its fp32 partial tile into `partial` [z][M][N]; finish_kernel then sums the ranges
+// in order and applies the epilogue (skinny problems: few output tiles, long K).
 template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     int M, int N, int K, const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
     void* __restrict__ Cv, int ldc, const T* __restrict__ bias, const T* __restrict__ residual,
-    int out_fp32) {
+    int out_fp32, int k_per_split, float* __restrict__ partial) {
   __shared__ float As[GK][GT + 4];
   __shared__ float Bs[GK][GT + 4];
   const int tid = threadIdx.x;
@@ -32,21 +35,23 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-  for (int k0 = 0; k0 < K; k0 += GK) {
+  const int kbeg = blockIdx.z * k_per_split;
+  const int kfin = min(K, kbeg + k_per_split);
+  for (int k0 = kbeg; k0 < kfin; k0 += GK) {
     // A slice -> As[k][m]
     if (LAYOUT == GEMM_TN) {
       int k = tid >> 4, m = (tid & 15) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int gm = m0 + m + e, gk = k0 + k;
-        As[k][m + e] = (gm < M && gk < K) ? Elt<T>::to_f(A[(size_t)gk * lda + gm]) : 0.f;
+        As[k][m + e] = (gm < M && gk < kfin) ? Elt<T>::to_f(A[(size_t)gk * lda + gm]) : 0.f;
       }
     } else {
       int m = tid >> 2, k = (tid & 3) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int gm = m0 + m, gk = k0 + k + e;
-        As[k + e][m] = (gm < M && gk < K) ? Elt<T>::to_f(A[(size_t)gm * lda + gk]) : 0.f;
+        As[k + e][m] = (gm < M && gk < kfin) ? Elt<T>::to_f(A[(size_t)gm * lda + gk]) : 0.f;
       }
     }
     // B slice -> Bs[k][n]
@@ -55,14 +60,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int gn = n0 + n, gk = k0 + k + e;
-        Bs[k + e][n] = (gn < N && gk < K) ? Elt<T>::to_f(B[(size_t)gn * ldb + gk]) : 0.f;
+        Bs[k + e][n] = (gn < N && gk < kfin) ? Elt<T>::to_f(B[(size_t)gn * ldb + gk]) : 0.f;
       }
     } else {
       int k = tid >> 4, n = (tid & 15) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int gn = n0 + n + e, gk = k0 + k;
-        Bs[k][n + e] = (gn < N && gk < K) ? Elt<T>::to_f(B[(size_t)gk * ldb + gn]) : 0.f;
+        Bs[k][n + e] = (gn < N && gk < kfin) ? Elt<T>::to_f(B[(size_t)gk * ldb + gn]) : 0.f;
       }
     }
     __syncthreads();
@@ -91,7 +96,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
       if (gn >= N) continue;
       size_t idx = (size_t)gm * ldc + gn;
       float v = acc[i][j];
-      if (LAYOUT == GEMM_TN) {
+      if (partial) {
+        partial[((size_t)blockIdx.z * M + gm) * N + gn] = v;
+      } else if (LAYOUT == GEMM_TN) {
         ((float*)Cv)[idx] += v;
       } else {
         if (bias) v += Elt<T>::to_f(bias[gn]);
@@ -103,30 +110,79 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
   }
 }
 
+template <typename T, int LAYOUT>
+__global__ void finish_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                              void* __restrict__ Cv, int ldc, const T* __restrict__ bias,
+                              const T* __restrict__ residual, int out_fp32) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)M * N) return;
+  const int gm = (int)(i / N), gn = (int)(i % N);
+  float v = 0.f;
+  for (int z = 0; z < splits; ++z) v += partial[(size_t)z * M * N + i];
+  const size_t idx = (size_t)gm * ldc + gn;
+  if (LAYOUT == GEMM_TN) { ((float*)Cv)[idx] += v; return; }
+  if (bias) v += Elt<T>::to_f(bias[gn]);
+  if (residual) v += Elt<T>::to_f(residual[idx]);
+  if (out_fp32) ((float*)Cv)[idx] = v;
+  else ((T*)Cv)[idx] = Elt<T>::from_f(v);
+}
+
+int generic_splits(int M, int N, int K) {
+  const long tiles = (long)cdiv(M, GT) * cdiv(N, GT);
+  if (tiles >= 128 || K < 1024) return 1;
+  int s = (int)(512 / tiles);
+  const int by_k = K / 128;
+  if (s > by_k) s = by_k;
+  if (s > 64) s = 64;
+  return s < 1 ? 1 : s;
+}
+
 template <typename T>
 bm_status launch(int layout, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
-                 void* C, int ldc, const GemmEpilogue& epi, hipStream_t st) {
-  dim3 grid(cdiv(N, GT), cdiv(M, GT)), block(256);
+                 void* C, int ldc, const GemmEpilogue& epi, void* scratch, size_t scratch_bytes,
+                 hipStream_t st) {
+  int splits = generic_splits(M, N, K);
+  if ((size_t)splits * M * N * sizeof(float) > scratch_bytes || !scratch) splits = 1;
+  const int per = cdiv(cdiv(K, splits), GK) * GK;
+  splits = cdiv(K, per);
+  float* partial = splits > 1 ? (float*)scratch : nullptr;
+  dim3 grid(cdiv(N, GT), cdiv(M, GT), splits), block(256);
 #define BM_L(LAY)                                                                               \
   hipLaunchKernelGGL((gemm_generic_kernel<T, LAY>), grid, block, 0, st, M, N, K, (const T*)A,   \
                      lda, (const T*)B, ldb, C, ldc, (const T*)epi.bias, (const T*)epi.residual, \
-                     epi.out_fp32)
+                     epi.out_fp32, per, partial)
   if (layout == GEMM_NT) BM_L(GEMM_NT);
   else if (layout == GEMM_NN) BM_L(GEMM_NN);
   else BM_L(GEMM_TN);
 #undef BM_L
+  if (partial) {
+    const long n = (long)M * N;
+#define BM_F(LAY)                                                                               \
+  hipLaunchKernelGGL((finish_kernel<T, LAY>), dim3(cdiv(n, 256)), dim3(256), 0, st, partial,    \
+                     splits, M, N, C, ldc, (const T*)epi.bias, (const T*)epi.residual, epi.out_fp32)
+    if (layout == GEMM_NT) BM_F(GEMM_NT);
+    else if (layout == GEMM_NN) BM_F(GEMM_NN);
+    else BM_F(GEMM_TN);
+#undef BM_F
+  }
   BM_CHECK_LAUNCH("gemm_generic");
   return BM_OK;
 }
 
 }  // namespace
 
+size_t gemm_generic_scratch_bytes(int M, int N, int K) {
+  const int s = generic_splits(M, N, K);
+  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+}
+
 bm_status gemm_generic(int layout, int dtype, int M, int N, int K, const void* A, int lda,
                        const void* B, int ldb, void* C, int ldc, const GemmEpilogue& epi,
-                       hipStream_t st) {
+                       void* scratch, size_t scratch_bytes, hipStream_t st) {
   if (M == 0 || N == 0) return BM_OK;
-  if (dtype == BM_DTYPE_BF16) return launch<bf16_t>(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, st);
-  return launch<float>(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, st);
+  if (dtype == BM_DTYPE_BF16)
+    return launch<bf16_t>(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
+  return launch<float>(layout, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
 }
 
 }  // namespace bm

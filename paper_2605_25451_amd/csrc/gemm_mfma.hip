@@ -17,8 +17,6 @@
 // tiles that a second kernel sums in a fixed order: no floating-point atomics.
 #include "common.h"
 
-#include <stdio.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -412,16 +410,6 @@ Plan make_plan(int layout, int M, int N, int K) {
         best.tiles_m = cdiv(M, tile); best.tiles_n = cdiv(N, tile);
         best.splits = splits; best.k_per_split = per * BK;
       }
-    }
-  }
-  if (const char* e = getenv("BM_GEMM_PLAN")) {      // tuning aid: "tile,splits"
-    int tile = 0, sp = 0;
-    if (sscanf(e, "%d,%d", &tile, &sp) == 2 && (tile == 128 || tile == 256) && sp >= 1) {
-      if (layout != GEMM_TN) sp = 1;
-      const int per = cdiv(slices, sp);
-      best.bm = best.bn = tile;
-      best.tiles_m = cdiv(M, tile); best.tiles_n = cdiv(N, tile);
-      best.splits = cdiv(slices, per); best.k_per_split = per * BK;
     }
   }
   return best;

@@ -22,6 +22,8 @@ GEMM_SHAPES = [
     # M, N, K  (tile multiples, ragged M, ragged K for the weight-gradient layout, tiny)
     (512, 512, 256), (300, 384, 512), (1000, 1152, 1152), (777, 3456, 1152), (256, 256, 64),
     (2048, 1024, 1000 * 8), (40, 64, 24), (515, 640, 1096),
+    # skinny outputs with a long contraction (k ranges split over workgroups)
+    (32, 1152, 6912), (5, 200, 3001),
 ]
 
 
@@ -70,6 +72,7 @@ ATTN_CASES = [
     (synth.DTYPE_BF16, 8, 2, 128, [333, 64, 515, 7], 1),
     (synth.DTYPE_BF16, 4, 4, 128, [200, 1100], 0),
     (synth.DTYPE_BF16, 2, 2, 72, [256, 256, 100], 0),
+    (synth.DTYPE_BF16, 4, 2, 72, [130, 77, 1], 1),
     (synth.DTYPE_BF16, 2, 1, 128, [2049], 1),
 ]
 
