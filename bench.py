@@ -24,9 +24,19 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); None until such a run has been summarised there.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch (fetched + written, mean over the class's launches in one step) from
+# the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, scaled by what
+# the same counters read for a plain 1 GiB copy (fetch x2.000, write x1.000).  The split-k
+# reduction that follows a weight-gradient GEMM is part of that class's launch.  Workloads
+# or classes without a summarised counter run report null.
+MIB = 1048576.0
+MEASURED_TRAFFIC_BYTES = {
+    "config2_vit_large_bf16": {
+        "gemm_tn": (400.0 + 28.0 + 40.0 + 12.0) * MIB,
+        "gemm_nt": (160.3 + 72.0) * MIB,
+        "gemm_nn": (144.3 + 56.0) * MIB,
+    },
+}
 
 
 def algorithmic_flops(cfg, cu):
@@ -215,16 +225,17 @@ def main():
         breakdown[cls] = entry
     dom = max(breakdown, key=lambda c: breakdown[c]["ms_per_step"])
     d_ms, d_work, d_n = prof[dom]
+    traffic = MEASURED_TRAFFIC_BYTES.get(case.name, {}).get(dom)
     if dom.startswith("gemm") or dom.startswith("attn"):
         achieved = d_work / (d_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": MEASURED_TRAFFIC_BYTES}
+                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": traffic}
     else:
         achieved = d_work / (d_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": MEASURED_TRAFFIC_BYTES}
+                    "avg_launch_us": d_ms / d_n * 1e3, "traffic": traffic}
     gemm_ms = sum(prof[c][0] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     gemm_work = sum(prof[c][1] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     attn_ms = prof["attn_fwd"][0] + prof["attn_bwd"][0]
