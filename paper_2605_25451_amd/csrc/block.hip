@@ -4,8 +4,8 @@
 //
 // Saved for backward: norm statistics, post-RoPE qkv, attention output and its
 // log-sum-exp, the mid-block residual x1, the MLP pre-activation.  Norm outputs
-// and the activation output are recomputed in backward (HBM-bound, cheap)
-// rather than stored.  The adaLN variant also keeps the modulation vectors and
+// and the activation output are not stored: the backward kernels of the norm
+// and of the activation write them again next to the gradients they produce.  The adaLN variant also keeps the modulation vectors and
 // the two ungated branch outputs (their products with dy give the gate grads).
 #include "common.h"
 
@@ -351,24 +351,30 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, dy, sv.mod + 5 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
     dm = ws.dgated;
   }
-  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st)); }
+  // input gradient first: the activation backward then also rewrites the activation
+  // output that the weight-gradient GEMM of the down projection reads
+  BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
+  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
+    BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a,
+                              c.linear_bias ? (float*)grads->b_up : nullptr, ws.colsum_ws, T, m.F, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.F, T, dm, d, ws.a, m.F, grads->w_down, m.F, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
-  if (c.linear_bias)
+  // bias gradients of the down and output projections are column sums of the two
+  // gradients the norm backward below touches anyway (not so when a gate sits between)
+  const bool fused_sums = c.linear_bias && !m.ada;
+  if (c.linear_bias && !fused_sums)
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dm, d, T, d, (float*)grads->b_down, ws.colsum_ws, st)); }
-  BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
-  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (2.0 * m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, T, m.F, st)); }
 
   // ---- up = h2 W_up^T + b_up,  h2 = N2(x1)
   NormArgs n2 = norm_args(c, m, 2, w, sv.mod, ws.tok_seq);
-  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(n2, sv.x1, ws.h, nullptr, 0, st)); }
+  BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.UP, ws.dup, m.UP, w->w_up, d, ws.dh, d, none, nullptr, 0, st));
+  { ProfScope _p(PROF_NORM, 5.0 * T * m.d * (double)m.es, st);
+    BM_RETURN_IF(norm_backward(n2, sv.x1, sv.stats2, ws.dh, dy, ws.dx1, ws.h, (float*)grads->norm2_g,
+                               (float*)grads->norm2_b, fused_sums ? (float*)grads->b_down : nullptr,
+                               fused_sums ? (float*)grads->b_o : nullptr, ws.dmod, cu_dev, S,
+                               ws.norm_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, m.UP, d, T, ws.dup, m.UP, ws.h, d, grads->w_up, d, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
-  if (c.linear_bias)
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dup, m.UP, T, m.UP, (float*)grads->b_up, ws.colsum_ws, st)); }
-  BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.UP, ws.dup, m.UP, w->w_up, d, ws.dh, d, none, nullptr, 0, st));
-  { ProfScope _p(PROF_NORM, 4.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_backward(n2, sv.x1, sv.stats2, ws.dh, dy, ws.dx1, (float*)grads->norm2_g,
-                             (float*)grads->norm2_b, ws.dmod, cu_dev, S, ws.norm_ws, st)); }
 
   // ---- x1 = x + [g1 *] attn,  attn = o W_o^T + b_o
   const void* dattn = ws.dx1;
@@ -379,7 +385,7 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.QD, T, dattn, d, sv.o, m.QD, grads->w_o, m.QD, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
-  if (c.linear_bias)
+  if (c.linear_bias && !fused_sums)
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dattn, d, T, d, (float*)grads->b_o, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.QD, d, dattn, d, w->w_o, m.QD, ws.d_o, m.QD, none, nullptr, 0, st));
 
@@ -400,14 +406,15 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
 
   // ---- qkv = h W_qkv^T + b_qkv,  h = N1(x)
   NormArgs n1 = norm_args(c, m, 1, w, sv.mod, ws.tok_seq);
-  { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(n1, x, ws.h, nullptr, 0, st)); }
-  BM_RETURN_IF(gemm(GEMM_TN, dt, m.QKV, d, T, ws.dqkv, m.QKV, ws.h, d, grads->w_qkv, d, none,
-                    ws.gemm_ws, ws.gemm_ws_bytes, st));
   if (c.linear_bias)
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dqkv, m.QKV, T, m.QKV, (float*)grads->b_qkv, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.QKV, ws.dqkv, m.QKV, w->w_qkv, d, ws.dh, d, none, nullptr, 0, st));
-  { ProfScope _p(PROF_NORM, 4.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_backward(n1, x, sv.stats1, ws.dh, ws.dx1, dx, (float*)grads->norm1_g,
-                             (float*)grads->norm1_b, ws.dmod, cu_dev, S, ws.norm_ws, st)); }
+  { ProfScope _p(PROF_NORM, 5.0 * T * m.d * (double)m.es, st);
+    BM_RETURN_IF(norm_backward(n1, x, sv.stats1, ws.dh, ws.dx1, dx, ws.h, (float*)grads->norm1_g,
+                               (float*)grads->norm1_b, nullptr, nullptr, ws.dmod, cu_dev, S,
+                               ws.norm_ws, st)); }
+  BM_RETURN_IF(gemm(GEMM_TN, dt, m.QKV, d, T, ws.dqkv, m.QKV, ws.h, d, grads->w_qkv, d, none,
+                    ws.gemm_ws, ws.gemm_ws_bytes, st));
 
   // ---- adaLN: mod = silu(cond) W_ada^T + b_ada
   if (m.ada) {

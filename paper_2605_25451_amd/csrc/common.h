@@ -186,16 +186,17 @@ size_t norm_backward_scratch_bytes(int T, int d);
 // dx = dres + dN/dx(dh);  dgamma/dbeta fp32 += (LayerNorm/RMSNorm)
 // adaLN: dmod[:, shift_off..] = segsum(dh), dmod[:, scale_off..] = segsum(dh * xhat) (overwrite, fp32)
 bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, const void* dh,
-                        const void* dres, void* dx, float* dgamma, float* dbeta, float* dmod,
-                        const int32_t* cu_dev, int S, void* scratch, hipStream_t st);
+                        const void* dres, void* dx, void* h_out, float* dgamma, float* dbeta,
+                        float* dsum_res, float* dsum_out, float* dmod, const int32_t* cu_dev, int S,
+                        void* scratch, hipStream_t st);
 
 // RoPE in place on the first n_heads heads of each row of qkv; sign=+1 fwd, -1 bwd
 bm_status rope_inplace(int dtype, void* qkv, int ld, int T, int n_heads, int dh, float base,
                        const int32_t* cu_dev, const int32_t* tok_seq, float sign, hipStream_t st);
 
 bm_status act_forward(int dtype, int act, const void* up, void* a, int T, int F, hipStream_t st);
-bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, int T, int F,
-                       hipStream_t st);
+bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, void* a_out,
+                       float* bias_grad, void* scratch, int T, int F, hipStream_t st);
 
 // out[n] += sum_t a[t, n]   (fp32 accumulate, deterministic two-stage)
 size_t colsum_scratch_bytes(int T, int N);

@@ -139,21 +139,34 @@ bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, 
 
 // ------------------------------------------------------------------ norm backward
 // Each wavefront walks rows with a grid stride; every lane owns the same
-// columns on every row, so the gamma/beta column sums accumulate in registers
-// and leave the kernel as one partial row per workgroup.
+// columns on every row, so column sums accumulate in registers and leave the
+// kernel as NP partial rows per workgroup: gamma (and beta) gradients, and with
+// SUMS also the column sums of the residual gradient read here and of the
+// gradient written here (the bias gradients of the two neighbouring linear
+// layers, whose output gradients these are).  With h_out the normalised row is
+// written again for the weight-gradient GEMM that follows.
 constexpr int NORM_BWD_MAX_BLOCKS = 512;
 
-template <typename T, int KIND, int NV>
+template <int KIND, bool SUMS> struct NormBwdParts {
+  static constexpr int NP = (KIND == BM_NORM_LAYERNORM ? 2 : KIND == BM_NORM_RMSNORM ? 1 : 0) + (SUMS ? 2 : 0);
+};
+
+template <typename T, int KIND, int NV, bool SUMS>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(
     const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
-    const T* __restrict__ dres, T* __restrict__ dx, const T* __restrict__ gamma,
-    const float* __restrict__ mod, int ld_mod, int scale_off, const int32_t* __restrict__ tok_seq,
-    float* __restrict__ partial /* [gridDim.x][2][d] */, int rows, int d) {
+    const T* __restrict__ dres, T* __restrict__ dx, T* __restrict__ h_out,
+    const T* __restrict__ gamma, const T* __restrict__ beta,
+    const float* __restrict__ mod, int ld_mod, int shift_off, int scale_off,
+    const int32_t* __restrict__ tok_seq, float* __restrict__ partial /* [gridDim.x][NP][d] */,
+    int rows, int d) {
   constexpr int VEC = Elt<T>::VEC;
+  constexpr int NP = NormBwdParts<KIND, SUMS>::NP;
+  constexpr int NS = SUMS ? NV : 1;
   extern __shared__ float sm[];   // [d]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float gam[NV][VEC];
   float acc_g[NV][VEC], acc_b[NV][VEC];
+  float acc_r[NS][VEC], acc_o[NS][VEC];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     int col = (i * WAVE + lane) * VEC;
@@ -161,12 +174,16 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
     for (int e = 0; e < VEC; ++e) { acc_g[i][e] = 0.f; acc_b[i][e] = 0.f; gam[i][e] = 1.f; }
     if (KIND != BM_NORM_ADALN && col < d) load16(gamma + col, gam[i]);
   }
+#pragma unroll
+  for (int i = 0; i < NS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { acc_r[i][e] = 0.f; acc_o[i][e] = 0.f; }
   const float inv_d = 1.0f / (float)d;
   for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
     const size_t off = (size_t)row * d;
     const float mean = stats[row], rstd = stats[rows + row];
     const float* mrow = nullptr;
-    if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod + scale_off;
+    if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod;
     float xv[NV][VEC], gv[NV][VEC];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -179,7 +196,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           float g;
-          if (KIND == BM_NORM_ADALN) g = dhv[e] * (1.0f + mrow[col + e]);
+          if (KIND == BM_NORM_ADALN) g = dhv[e] * (1.0f + mrow[scale_off + col + e]);
           else g = dhv[e] * gam[i][e];
           if (KIND == BM_NORM_RMSNORM) {
             s2 += g * xv[i][e];
@@ -212,12 +229,38 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
           out[e] = res[e] + v;
         }
         store16(dx + off + col, out);
+        if (SUMS) {
+          // sum what the consumer reads: the stored (rounded) gradient
+          float stored[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) stored[e] = Elt<T>::to_f(Elt<T>::from_f(out[e]));
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) { acc_r[SUMS ? i : 0][e] += res[e]; acc_o[SUMS ? i : 0][e] += stored[e]; }
+        }
+        if (h_out) {
+          float hv[VEC];
+          if (KIND == BM_NORM_LAYERNORM) {
+            float bt[VEC];
+            load16(beta + col, bt);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) hv[e] = xv[i][e] * gam[i][e] + bt[e];
+          } else if (KIND == BM_NORM_RMSNORM) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) hv[e] = xv[i][e] * rstd * gam[i][e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+              hv[e] = xv[i][e] * (1.0f + mrow[scale_off + col + e]) + mrow[shift_off + col + e];
+          }
+          store16(h_out + off + col, hv);
+        }
       }
     }
   }
-  if (KIND == BM_NORM_ADALN) return;   // shift/scale gradients are per-sequence sums (own kernel)
-  // combine the four wavefronts through LDS, one after the other (fixed order)
-  for (int which = 0; which < (KIND == BM_NORM_LAYERNORM ? 2 : 1); ++which) {
+  // combine the four wavefronts through LDS, one after the other (fixed order);
+  // adaLN shift/scale gradients are per-sequence sums and have their own kernel
+  for (int which = 0; which < NP; ++which) {
+    const int what = KIND == BM_NORM_ADALN ? which + 2 : (KIND == BM_NORM_RMSNORM && which > 0 ? which + 1 : which);
     for (int w = 0; w < 4; ++w) {
       if (wave == w) {
 #pragma unroll
@@ -226,7 +269,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
           if (col < d) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
-              float v = which == 0 ? acc_g[i][e] : acc_b[i][e];
+              float v = what == 0 ? acc_g[i][e] : what == 1 ? acc_b[i][e]
+                      : what == 2 ? acc_r[SUMS ? i : 0][e] : acc_o[SUMS ? i : 0][e];
               if (w == 0) sm[col + e] = v; else sm[col + e] += v;
             }
           }
@@ -234,7 +278,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
       }
       __syncthreads();
     }
-    float* prow = partial + ((size_t)blockIdx.x * 2 + which) * d;
+    float* prow = partial + ((size_t)blockIdx.x * NP + which) * d;
     for (int c = threadIdx.x; c < d; c += 256) prow[c] = sm[c];
     __syncthreads();
   }
@@ -268,6 +312,36 @@ __global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_kernel(
   }
 }
 
+// The same reduction for up to four destinations in one launch (blockIdx.y
+// selects one); they share nparts, stride and n.
+struct ReduceTargets { const float* partial[4]; float* out[4]; };
+__global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_multi_kernel(
+    ReduceTargets t, int nparts, int stride, int n) {
+  __shared__ float sm[PR_GROUPS][64];
+  const float* __restrict__ partial = t.partial[blockIdx.y];
+  float* __restrict__ out = t.out[blockIdx.y];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int g = threadIdx.x >> 6;
+  float s0 = 0.f, s1 = 0.f;
+  if (c < n) {
+    int p = g;
+    for (; p + PR_GROUPS < nparts; p += 2 * PR_GROUPS) {
+      s0 += partial[(size_t)p * stride + c];
+      s1 += partial[(size_t)(p + PR_GROUPS) * stride + c];
+    }
+    if (p < nparts) s0 += partial[(size_t)p * stride + c];
+  }
+  sm[g][threadIdx.x & 63] = s0 + s1;
+  __syncthreads();
+  if (g == 0 && c < n) {
+    const int l = threadIdx.x;
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < PR_GROUPS; ++i) v += sm[i][l];
+    out[c] += v;
+  }
+}
+
 // adaLN: dshift[s,:] = sum_{t in s} dh,  dscale[s,:] = sum_{t in s} dh * xhat
 template <typename T>
 __global__ __launch_bounds__(256) void adaln_seg_grads_kernel(
@@ -298,21 +372,22 @@ __global__ __launch_bounds__(256) void adaln_seg_grads_kernel(
 static int norm_bwd_blocks(int T) { int b = cdiv(T, 4); return b < NORM_BWD_MAX_BLOCKS ? b : NORM_BWD_MAX_BLOCKS; }
 
 size_t norm_backward_scratch_bytes(int T, int d) {
-  return (size_t)norm_bwd_blocks(T) * 2 * d * sizeof(float);
+  return (size_t)norm_bwd_blocks(T) * 4 * d * sizeof(float);
 }
 
-template <typename T, int KIND>
+template <typename T, int KIND, bool SUMS>
 static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float* stats,
-                                   const void* dh, const void* dres, void* dx, float* partial,
-                                   hipStream_t st) {
+                                   const void* dh, const void* dres, void* dx, void* h_out,
+                                   float* partial, hipStream_t st) {
   constexpr int VEC = Elt<T>::VEC;
   int nv = cdiv(a.d, WAVE * VEC);
   dim3 grid(norm_bwd_blocks(a.T)), block(256);
   size_t lds = (size_t)a.d * sizeof(float);
 #define BM_LAUNCH_NV(NVV)                                                                        \
-  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV>), grid, block, lds, st, (const T*)x, stats,  \
-                     (const T*)dh, (const T*)dres, (T*)dx, (const T*)a.gamma, a.mod, a.ld_mod,   \
-                     a.scale_off, a.tok_seq, partial, a.T, a.d)
+  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS>), grid, block, lds, st, (const T*)x,   \
+                     stats, (const T*)dh, (const T*)dres, (T*)dx, (T*)h_out, (const T*)a.gamma,  \
+                     (const T*)a.beta, a.mod, a.ld_mod, a.shift_off, a.scale_off, a.tok_seq,     \
+                     partial, a.T, a.d)
   if (nv <= 1) BM_LAUNCH_NV(1);
   else if (nv <= 2) BM_LAUNCH_NV(2);
   else if (nv <= 4) BM_LAUNCH_NV(4);
@@ -324,20 +399,27 @@ static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float
   return BM_OK;
 }
 
+// dsum_res / dsum_out (both or neither): fp32 vectors that receive += the column
+// sums of dres and of dx.
 bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, const void* dh,
-                        const void* dres, void* dx, float* dgamma, float* dbeta, float* dmod,
-                        const int32_t* cu_dev, int S, void* scratch, hipStream_t st) {
+                        const void* dres, void* dx, void* h_out, float* dgamma, float* dbeta,
+                        float* dsum_res, float* dsum_out, float* dmod, const int32_t* cu_dev, int S,
+                        void* scratch, hipStream_t st) {
   if (a.T == 0) return BM_OK;
   float* partial = (float*)scratch;
+  const bool sums = dsum_res != nullptr;
+  if (sums != (dsum_out != nullptr)) { set_error("norm_backward: one column-sum target without the other"); return BM_ERR_INVALID_ARG; }
   bm_status rc;
-#define BM_KIND(TT)                                                                              \
+#define BM_KIND2(TT, SS)                                                                         \
   switch (a.kind) {                                                                              \
-    case BM_NORM_LAYERNORM: rc = norm_bwd_dispatch<TT, BM_NORM_LAYERNORM>(a, x, stats, dh, dres, dx, partial, st); break; \
-    case BM_NORM_RMSNORM: rc = norm_bwd_dispatch<TT, BM_NORM_RMSNORM>(a, x, stats, dh, dres, dx, partial, st); break;     \
-    default: rc = norm_bwd_dispatch<TT, BM_NORM_ADALN>(a, x, stats, dh, dres, dx, partial, st); break; \
+    case BM_NORM_LAYERNORM: rc = norm_bwd_dispatch<TT, BM_NORM_LAYERNORM, SS>(a, x, stats, dh, dres, dx, h_out, partial, st); break; \
+    case BM_NORM_RMSNORM: rc = norm_bwd_dispatch<TT, BM_NORM_RMSNORM, SS>(a, x, stats, dh, dres, dx, h_out, partial, st); break;     \
+    default: rc = norm_bwd_dispatch<TT, BM_NORM_ADALN, SS>(a, x, stats, dh, dres, dx, h_out, partial, st); break; \
   }
+#define BM_KIND(TT) if (sums) { BM_KIND2(TT, true) } else { BM_KIND2(TT, false) }
   if (a.dtype == BM_DTYPE_BF16) { BM_KIND(bf16_t) } else { BM_KIND(float) }
 #undef BM_KIND
+#undef BM_KIND2
   BM_RETURN_IF(rc);
   const int nb = norm_bwd_blocks(a.T);
   if (a.kind == BM_NORM_ADALN) {
@@ -351,13 +433,17 @@ bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, co
                          stats, (const float*)dh, cu_dev, dmod, a.ld_mod, a.shift_off, a.scale_off,
                          a.T, a.d);
     BM_CHECK_LAUNCH("adaln_seg_grads");
-    return BM_OK;
   }
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(64 * PR_GROUPS), 0, st, partial, nb,
-                     2 * a.d, a.d, dgamma);
-  if (a.kind == BM_NORM_LAYERNORM)
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(a.d, 64)), dim3(64 * PR_GROUPS), 0, st,
-                       partial + a.d, nb, 2 * a.d, a.d, dbeta);
+  ReduceTargets t;
+  int np = 0;
+  float* outs[4] = {nullptr, nullptr, nullptr, nullptr};
+  if (a.kind != BM_NORM_ADALN) outs[np++] = dgamma;
+  if (a.kind == BM_NORM_LAYERNORM) outs[np++] = dbeta;
+  if (sums) { outs[np++] = dsum_res; outs[np++] = dsum_out; }
+  if (np == 0) return BM_OK;
+  for (int i = 0; i < 4; ++i) { t.partial[i] = partial + (size_t)(i < np ? i : 0) * a.d; t.out[i] = outs[i < np ? i : 0]; }
+  hipLaunchKernelGGL(partial_reduce_multi_kernel, dim3(cdiv(a.d, 64), np), dim3(64 * PR_GROUPS), 0, st,
+                     t, nb, np * a.d, a.d);
   BM_CHECK_LAUNCH("norm_bwd_reduce");
   return BM_OK;
 }
@@ -452,33 +538,68 @@ __global__ void act_fwd_kernel(const T* __restrict__ up, T* __restrict__ a, int 
   store16(a + t * F + c, out);
 }
 
-template <typename T, int ACT>
-__global__ void act_bwd_kernel(const T* __restrict__ up, const T* __restrict__ da,
-                               T* __restrict__ dup, int rows, int F) {
+// Backward of the activation over a (column span, row chunk) grid: writes the
+// gradient of the pre-activation, optionally the activation output again (the
+// weight-gradient GEMM of the down projection reads it) and, with COLSUM, one
+// partial column sum of the written gradient per row chunk (bias gradient).
+template <typename T, int ACT, bool COLSUM>
+__global__ __launch_bounds__(256) void act_bwd_kernel(const T* __restrict__ up, const T* __restrict__ da,
+                                                      T* __restrict__ dup, T* __restrict__ a_out,
+                                                      float* __restrict__ partial, int rows, int F) {
   constexpr int VEC = Elt<T>::VEC;
-  const int per_row = F / VEC;
-  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= (long)rows * per_row) return;
-  const long t = gid / per_row;
-  const int c = (int)(gid % per_row) * VEC;
-  float d[VEC];
-  load16(da + t * F + c, d);
-  if (ACT == BM_ACT_GELU) {
-    float z[VEC], out[VEC];
-    load16(up + t * F + c, z);
+  __shared__ float sm[COLSUM ? 4 : 1][WAVE * VEC];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c = (blockIdx.x * WAVE + lane) * VEC;
+  const int chunks = gridDim.y;
+  const int per = (rows + chunks - 1) / chunks;
+  const int r0 = blockIdx.y * per;
+  const int r1 = min(rows, r0 + per);
+  float acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) out[e] = d[e] * gelu_grad_f(z[e]);
-    store16(dup + t * F + c, out);
-  } else {
-    float g[VEC], u[VEC], dg[VEC], du[VEC];
-    load16(up + t * 2 * F + c, g); load16(up + t * 2 * F + F + c, u);
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (c < F) {
+    for (long t = r0 + wave; t < r1; t += 4) {
+      float d[VEC];
+      load16(da + t * F + c, d);
+      if (ACT == BM_ACT_GELU) {
+        float z[VEC], out[VEC], act[VEC];
+        load16(up + t * F + c, z);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      float s = sigmoid_f(g[e]);
-      dg[e] = d[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
-      du[e] = d[e] * g[e] * s;
+        for (int e = 0; e < VEC; ++e) {
+          float cdf = 0.5f * (1.0f + erff(z[e] * 0.70710678118654752f));
+          float pdf = expf(-0.5f * z[e] * z[e]) * 0.39894228040143268f;
+          out[e] = d[e] * (cdf + z[e] * pdf);
+          act[e] = gelu_f(z[e]);
+          if (COLSUM) acc[e] += Elt<T>::to_f(Elt<T>::from_f(out[e]));
+        }
+        store16(dup + t * F + c, out);
+        if (a_out) store16(a_out + t * F + c, act);
+      } else {
+        float g[VEC], u[VEC], dg[VEC], du[VEC], act[VEC];
+        load16(up + t * 2 * F + c, g); load16(up + t * 2 * F + F + c, u);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          float sg = sigmoid_f(g[e]);
+          dg[e] = d[e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
+          du[e] = d[e] * g[e] * sg;
+          act[e] = g[e] * sg * u[e];
+        }
+        store16(dup + t * 2 * F + c, dg); store16(dup + t * 2 * F + F + c, du);
+        if (a_out) store16(a_out + t * F + c, act);
+      }
     }
-    store16(dup + t * 2 * F + c, dg); store16(dup + t * 2 * F + F + c, du);
+  }
+  if (COLSUM) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sm[wave][lane * VEC + e] = acc[e];
+    __syncthreads();
+    if (wave == 0 && c < F) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        int i = lane * VEC + e;
+        partial[(size_t)blockIdx.y * F + c + e] = sm[0][i] + sm[1][i] + sm[2][i] + sm[3][i];
+      }
+    }
   }
 }
 
@@ -496,17 +617,35 @@ bm_status act_forward(int dtype, int act, const void* up, void* a, int T, int F,
   return BM_OK;
 }
 
-bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, int T, int F,
-                       hipStream_t st) {
+static void colsum_plan(int T, int N, int vec, int* spans, int* chunks);
+
+// a_out (nullable): the activation output, written again.  bias_grad (nullable,
+// GELU only): fp32 [F] that receives += the column sums of dup; scratch then
+// needs colsum_scratch_bytes(T, F).
+bm_status act_backward(int dtype, int act, const void* up, const void* da, void* dup, void* a_out,
+                       float* bias_grad, void* scratch, int T, int F, hipStream_t st) {
   if (T == 0) return BM_OK;
   const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
   if (F % vec) { set_error("activation: mlp_hidden %d not a multiple of %d", F, vec); return BM_ERR_UNSUPPORTED; }
-  long n = (long)T * (F / vec);
-  dim3 grid(cdiv(n, 256)), block(256);
-#define BM_L(TT, AA) hipLaunchKernelGGL((act_bwd_kernel<TT, AA>), grid, block, 0, st, (const TT*)up, (const TT*)da, (TT*)dup, T, F)
-  if (dtype == BM_DTYPE_BF16) { if (act == BM_ACT_GELU) BM_L(bf16_t, BM_ACT_GELU); else BM_L(bf16_t, BM_ACT_SWIGLU); }
-  else { if (act == BM_ACT_GELU) BM_L(float, BM_ACT_GELU); else BM_L(float, BM_ACT_SWIGLU); }
+  if (bias_grad && act != BM_ACT_GELU) { set_error("activation: bias gradient with a gated MLP"); return BM_ERR_UNSUPPORTED; }
+  int spans, chunks;
+  colsum_plan(T, F, vec, &spans, &chunks);
+  dim3 grid(spans, chunks), block(256);
+  float* partial = (float*)scratch;
+#define BM_L(TT, AA, CS) hipLaunchKernelGGL((act_bwd_kernel<TT, AA, CS>), grid, block, 0, st, (const TT*)up, (const TT*)da, (TT*)dup, (TT*)a_out, partial, T, F)
+  if (dtype == BM_DTYPE_BF16) {
+    if (act != BM_ACT_GELU) BM_L(bf16_t, BM_ACT_SWIGLU, false);
+    else if (bias_grad) BM_L(bf16_t, BM_ACT_GELU, true);
+    else BM_L(bf16_t, BM_ACT_GELU, false);
+  } else {
+    if (act != BM_ACT_GELU) BM_L(float, BM_ACT_SWIGLU, false);
+    else if (bias_grad) BM_L(float, BM_ACT_GELU, true);
+    else BM_L(float, BM_ACT_GELU, false);
+  }
 #undef BM_L
+  if (bias_grad)
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3(cdiv(F, 64)), dim3(64 * PR_GROUPS), 0, st, partial, chunks, F,
+                       F, bias_grad);
   BM_CHECK_LAUNCH("act_bwd");
   return BM_OK;
 }
