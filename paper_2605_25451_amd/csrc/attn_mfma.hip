@@ -460,7 +460,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 // dQ of one 128-row query tile of one q head: walks the key tiles, scores kept as
 // S^T[key, q] as in the forward kernel.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dq,
