@@ -21,7 +21,7 @@ BM_OK = 0
 BM_ERR_INVALID_ARG, BM_ERR_UNSUPPORTED, BM_ERR_WORKSPACE_TOO_SMALL, BM_ERR_HIP = -1, -2, -3, -4
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 OP_ENC_FWD, OP_ENC_BWD, OP_LLM_FWD, OP_LLM_BWD, OP_GEN_FWD, OP_GEN_BWD = range(6)
-ORDER_NESTED, ORDER_COMPUTE_EFFICIENT, ORDER_SEQUENTIAL = 0, 1, 2
+ORDER_NESTED, ORDER_COMPUTE_EFFICIENT, ORDER_SEQUENTIAL, ORDER_MEMORY_EFFICIENT = 0, 1, 2, 3
 
 PARAM_FIELDS = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b",
                 "w_up", "b_up", "w_down", "b_down", "w_ada", "b_ada")
@@ -66,6 +66,25 @@ class Unit(C.Structure):
     _fields_ = [("T", C.c_int32), ("S", C.c_int32), ("cu_dev", C.c_void_p), ("cu_host", C.c_void_p),
                 ("patches", C.c_void_p), ("gen_cu_dev", C.c_void_p), ("gen_cu_host", C.c_void_p),
                 ("latents", C.c_void_p), ("targets", C.c_void_p)]
+
+
+class PipeOp(C.Structure):
+    _fields_ = [("op", C.c_int32), ("index", C.c_int32), ("chunk", C.c_int32), ("column", C.c_int32)]
+
+
+class PipeReplayConfig(C.Structure):
+    _fields_ = [("order", C.c_int32), ("P", C.c_int32), ("V", C.c_int32), ("M", C.c_int32),
+                ("W", C.c_int32), ("has_generator", C.c_int32)] + \
+               [(n, C.POINTER(C.c_double)) for n in ("llm_fwd", "llm_bwd", "enc_fwd", "enc_bwd",
+                                                      "gen_fwd", "gen_bwd")] + \
+               [("p2p", C.c_double), ("act_llm", C.c_double),
+                ("act_enc", C.POINTER(C.c_double)), ("act_gen", C.POINTER(C.c_double))]
+
+
+class PipeReplayResult(C.Structure):
+    _fields_ = [("makespan", C.c_double), ("bubble", C.c_double)] + \
+               [(n, C.POINTER(C.c_double)) for n in ("busy", "peak", "peak_enc", "peak_gen", "peak_llm")]
+
 
 
 _lib = None
@@ -122,6 +141,12 @@ def lib() -> C.CDLL:
         for name in ("bm_block_sizes", "bm_block_forward", "bm_block_backward", "bm_gemm",
                      "bm_attention_forward", "bm_attention_backward", "bm_build_schedule",
                      "bm_check_schedule", "bm_profile_begin", "bm_profile_end"):
+            getattr(l, name).restype = C.c_int
+        ppo = C.POINTER(PipeOp)
+        l.bm_pipeline_llm_schedule.argtypes = [i32] * 4 + [ppo, pi32]
+        l.bm_pipeline_build_schedule.argtypes = [i32] * 7 + [ppo, pi32]
+        l.bm_pipeline_replay.argtypes = [C.POINTER(PipeReplayConfig), C.POINTER(PipeReplayResult)]
+        for name in ("bm_pipeline_llm_schedule", "bm_pipeline_build_schedule", "bm_pipeline_replay"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -268,6 +293,53 @@ def check_schedule(ops, M, unit_size, has_generator):
     peak = (C.c_int32 * 3)()
     _check(lib().bm_check_schedule(flat, len(ops), M, unit_size, int(has_generator), peak))
     return tuple(peak)
+
+
+# ---------------------------------------------------------------- multi-rank schedule and replay
+
+def _pipe_ops(fn, *args):
+    n = C.c_int32(0)
+    fn(*args, None, C.byref(n))
+    if n.value <= 0:
+        _check(BM_ERR_INVALID_ARG)
+    buf = (PipeOp * n.value)()
+    _check(fn(*args, buf, C.byref(n)))
+    return [(o.op, o.index, o.chunk, o.column) for o in buf[:n.value]]
+
+
+def pipeline_llm_schedule(P, V, M, rank):
+    """LLM ops of one rank: list of (opcode, microbatch, chunk, column)."""
+    return _pipe_ops(lib().bm_pipeline_llm_schedule, P, V, M, rank)
+
+
+def pipeline_build_schedule(order, P, V, M, W, has_generator, rank):
+    """Program of one rank: list of (opcode, index, chunk, column)."""
+    return _pipe_ops(lib().bm_pipeline_build_schedule, order, P, V, M, W, int(has_generator), rank)
+
+
+def pipeline_replay(order, P, V, M, W, has_generator, llm_fwd, llm_bwd, enc_fwd, enc_bwd,
+                    gen_fwd=None, gen_bwd=None, p2p=0.0, act_llm=0.0, act_enc=None, act_gen=None):
+    """Replays the rank programs with the given operator seconds; returns a dict with makespan,
+    bubble and per-rank busy / peak / peak_enc / peak_gen / peak_llm lists."""
+    def arr(v, n):
+        if v is None:
+            return None
+        if len(v) != n:
+            raise ValueError(f"expected {n} values, got {len(v)}")
+        return (C.c_double * n)(*[float(x) for x in v])
+    keep = [arr(llm_fwd, P * V), arr(llm_bwd, P * V), arr(enc_fwd, M), arr(enc_bwd, M), arr(gen_fwd, M),
+            arr(gen_bwd, M), arr(act_enc, M), arr(act_gen, M)]
+    cast = lambda a: C.cast(a, C.POINTER(C.c_double)) if a is not None else None
+    cfg = PipeReplayConfig(order, P, V, M, W, int(has_generator), cast(keep[0]), cast(keep[1]),
+                           cast(keep[2]), cast(keep[3]), cast(keep[4]), cast(keep[5]), float(p2p),
+                           float(act_llm), cast(keep[6]), cast(keep[7]))
+    outs = [(C.c_double * P)() for _ in range(5)]
+    res = PipeReplayResult(0.0, 0.0, *[cast(o) for o in outs])
+    _check(lib().bm_pipeline_replay(C.byref(cfg), C.byref(res)))
+    names = ("busy", "peak", "peak_enc", "peak_gen", "peak_llm")
+    out = {"makespan": res.makespan, "bubble": res.bubble}
+    out.update({n: list(o) for n, o in zip(names, outs)})
+    return out
 
 
 # ---------------------------------------------------------------- executor
