@@ -283,6 +283,12 @@ bm_status bm_executor_load_schedule(bm_executor* ex, const int32_t* ops, int32_t
 /* Runs the loaded op stream once on the stream. loss: dev float[M], overwritten per unit or
  * microbatch as described above.  No host synchronisation. */
 bm_status bm_executor_execute(bm_executor* ex, float* loss, void* hip_stream);
+/* The same run with a HIP event recorded on the stream around every op; synchronises with the
+ * last event and fills op_ms (host double[n_ops]: milliseconds of each op of the loaded stream)
+ * and, when not NULL, live_bytes (host double[n_ops]: live activation bytes after each op).
+ * A measuring tool: it feeds measured operator times to bm_pipeline_replay (Sec. 3.1). */
+bm_status bm_executor_execute_timed(bm_executor* ex, float* loss, double* op_ms /* host */,
+                                    double* live_bytes /* host or NULL */, void* hip_stream);
 /* High-water mark, over the last execute, of the bytes of saved activations and
  * inter-module feature/gradient buffers that were alive at the same time (weights,
  * gradients and scratch excluded), and its encoder-unit part. */

@@ -129,6 +129,8 @@ def lib() -> C.CDLL:
         l.bm_executor_create.argtypes = [pcfg, ppar, ppar, pmb, pun, vp, sz, i32, i32, C.POINTER(vp)]
         l.bm_executor_load_schedule.argtypes = [vp, pi32, i32]
         l.bm_executor_execute.argtypes = [vp, vp, vp]
+        l.bm_executor_execute_timed.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+        l.bm_executor_execute_timed.restype = C.c_int
         l.bm_executor_peak_activation_bytes.argtypes = [vp]
         l.bm_executor_peak_activation_bytes.restype = sz
         l.bm_executor_peak_encoder_bytes.argtypes = [vp]
@@ -365,6 +367,14 @@ def executor_load_schedule(ex, ops):
 
 def executor_execute(ex, loss, stream=None):
     _check(lib().bm_executor_execute(ex, _ptr(loss), _stream() if stream is None else stream))
+
+
+def executor_execute_timed(h, loss, n_ops, stream=None):
+    """Runs the loaded op stream with per-op event timing; returns (ms per op, live bytes after each op)."""
+    ms = (C.c_double * n_ops)()
+    live = (C.c_double * n_ops)()
+    _check(lib().bm_executor_execute_timed(h, _ptr(loss), ms, live, _stream() if stream is None else stream))
+    return list(ms), list(live)
 
 
 def executor_peak_activation_bytes(ex) -> int:

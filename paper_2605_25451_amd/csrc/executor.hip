@@ -443,15 +443,18 @@ extern "C" bm_status bm_executor_load_schedule(bm_executor* ex, const int32_t* o
   return BM_OK;
 }
 
-extern "C" bm_status bm_executor_execute(bm_executor* ex, float* loss, void* hip_stream) {
-  BM_ARG_CHECK(ex && loss, "executor: NULL executor or loss buffer");
-  BM_ARG_CHECK(!ex->ops.empty(), "executor: no schedule loaded");
-  hipStream_t st = (hipStream_t)hip_stream;
+namespace {
+
+// runs the loaded op stream; with `after_op` it is called once before the first op
+// (index -1) and once after every op
+template <typename F>
+bm_status run_ops(bm_executor* ex, float* loss, hipStream_t st, F&& after_op) {
   ex->live = ex->peak = ex->live_enc = ex->peak_enc = 0;
   std::fill(ex->enc_slot_of.begin(), ex->enc_slot_of.end(), -1);
   std::fill(ex->llm_slot_of.begin(), ex->llm_slot_of.end(), -1);
   std::fill(ex->enc_busy.begin(), ex->enc_busy.end(), 0);
   std::fill(ex->llm_busy.begin(), ex->llm_busy.end(), 0);
+  BM_RETURN_IF(after_op(-1));
   for (size_t i = 0; i < ex->ops.size() / 2; ++i) {
     const int code = ex->ops[2 * i], idx = ex->ops[2 * i + 1];
     bm_status rc = BM_OK;
@@ -465,8 +468,43 @@ extern "C" bm_status bm_executor_execute(bm_executor* ex, float* loss, void* hip
       default: set_error("executor: opcode %d", code); rc = BM_ERR_INVALID_ARG;
     }
     if (rc != BM_OK) return rc;
+    BM_RETURN_IF(after_op((int)i));
   }
   return BM_OK;
+}
+
+}  // namespace
+
+extern "C" bm_status bm_executor_execute(bm_executor* ex, float* loss, void* hip_stream) {
+  BM_ARG_CHECK(ex && loss, "executor: NULL executor or loss buffer");
+  BM_ARG_CHECK(!ex->ops.empty(), "executor: no schedule loaded");
+  return run_ops(ex, loss, (hipStream_t)hip_stream, [](int) { return BM_OK; });
+}
+
+extern "C" bm_status bm_executor_execute_timed(bm_executor* ex, float* loss, double* op_ms,
+                                               double* live_bytes, void* hip_stream) {
+  BM_ARG_CHECK(ex && loss && op_ms, "executor: NULL executor, loss buffer or op_ms");
+  BM_ARG_CHECK(!ex->ops.empty(), "executor: no schedule loaded");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t n = ex->ops.size() / 2;
+  std::vector<hipEvent_t> ev(n + 1, nullptr);
+  bm_status rc = BM_OK;
+  for (size_t i = 0; i <= n && rc == BM_OK; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) { set_error("executor: hipEventCreate failed"); rc = BM_ERR_HIP; }
+  if (rc == BM_OK)
+    rc = run_ops(ex, loss, st, [&](int i) {
+      if (hipEventRecord(ev[i + 1], st) != hipSuccess) { set_error("executor: hipEventRecord failed"); return BM_ERR_HIP; }
+      if (live_bytes && i >= 0) live_bytes[i] = (double)ex->live;
+      return BM_OK;
+    });
+  if (rc == BM_OK && hipEventSynchronize(ev[n]) != hipSuccess) { set_error("executor: hipEventSynchronize failed"); rc = BM_ERR_HIP; }
+  for (size_t i = 0; i < n && rc == BM_OK; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) { set_error("executor: hipEventElapsedTime failed"); rc = BM_ERR_HIP; }
+    op_ms[i] = ms;
+  }
+  for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e);
+  return rc;
 }
 
 extern "C" size_t bm_executor_peak_activation_bytes(const bm_executor* ex) { return ex ? ex->peak : 0; }

@@ -102,6 +102,12 @@ class StageOnDevice:
         self.loss.zero_()
         bm.executor_execute(self.ex, self.loss)
 
+    def run_timed(self, ops):
+        """Runs the op stream with per-op timing: (ms per op, live activation bytes after each op)."""
+        bm.executor_load_schedule(self.ex, ops)
+        self.loss.zero_()
+        return bm.executor_execute_timed(self.ex, self.loss, len(ops))
+
     def results(self):
         torch.cuda.synchronize()
         f = lambda t: t.detach().float().cpu().numpy().astype(np.float64)

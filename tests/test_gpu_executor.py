@@ -127,3 +127,29 @@ def test_executor_errors():
     import torch
     torch.cuda.synchronize()
     dev.destroy()
+
+
+def test_timed_execution_gives_the_same_results_and_sane_figures():
+    """bm_executor_execute_timed: same arithmetic as the plain run (bit-identical
+    gradients), one positive duration per op, live bytes back to zero at the end."""
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd.stage import StageOnDevice
+    stage = stage_fp32(True, 4, 1, seed=83)
+    dev = StageOnDevice(stage)
+    dev.create(3, 3)
+    ops = bm.build_schedule(bm.ORDER_NESTED, stage.M, 1, 3, 3, 1)
+    dev.zero_grads()
+    dev.run(ops)
+    loss0, grads0 = dev.results()
+    dev.zero_grads()
+    ms, live = dev.run_timed(ops)
+    loss1, grads1 = dev.results()
+    peak = dev.peak_bytes()
+    dev.destroy()
+    assert len(ms) == len(ops) and all(t > 0.0 for t in ms)
+    assert live[-1] == 0.0 and max(live) == float(peak[0])
+    assert np.array_equal(loss0, loss1)
+    for grp in ("enc", "llm", "gen"):
+        for g0, g1 in zip(grads0[grp], grads1[grp]):
+            for k in g0:
+                assert np.array_equal(g0[k], g1[k]), (grp, k)
