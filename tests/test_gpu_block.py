@@ -99,6 +99,32 @@ def test_full_width_gqa_decoder_bf16():
     compare(case, run_hip(case), run_oracle(case))
 
 
+def edge_cases():
+    f32 = synth.DTYPE_FP32
+    tiny = dict(hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=16, mlp_hidden=96, dtype=f32)
+    rng = np.random.default_rng(7)
+    many = [int(v) for v in rng.integers(1, 8, size=150)]            # 150 sequences of 1..7 tokens
+    out = []
+    out.append(synth.make_case(synth.scaled(synth.decoder_8b_gqa(), **tiny), [1], 50, name="one_token_fp32"))
+    out.append(synth.make_case(synth.scaled(synth.decoder_8b_gqa(), **tiny), many, 51, name="many_tiny_fp32"))
+    out.append(synth.make_case(synth.vit_large(), [1], 52, name="one_token_vit_bf16"))
+    out.append(synth.make_case(synth.vit_large(), many, 53, name="many_tiny_vit_bf16"))
+    out.append(synth.make_case(synth.scaled(synth.decoder_8b_gqa(), mlp_hidden=1024, hidden=512,
+                                            n_q_heads=4, n_kv_heads=1),
+                               [2049], 54, name="one_long_gqa_bf16"))
+    out.append(synth.make_case(synth.scaled(synth.decoder_7b(), mlp_hidden=1024, hidden=512,
+                                            n_q_heads=4, n_kv_heads=4),
+                               [77], 55, name="odd_T_decoder_bf16"))
+    out.append(synth.make_case(synth.dit_block(), [1, 3, 257], 56, name="dit_ragged_bf16"))
+    return out
+
+
+@pytest.mark.parametrize("case", edge_cases(), ids=lambda c: c.name)
+def test_edge_shapes_match_oracle(case):
+    """Degenerate packs: a single token, many tiny sequences, one long sequence, odd totals."""
+    compare(case, run_hip(case), run_oracle(case))
+
+
 def test_gradients_accumulate_and_runs_are_bit_identical():
     from paper_2605_25451_amd.runner import CaseOnDevice
     case = synth.make_case(synth.vit_large(), [200, 120], 48, name="vit_large_accumulate")
