@@ -17,7 +17,6 @@
 // tiles that a second kernel sums in a fixed order: no floating-point atomics.
 #include "common.h"
 
-
 #include <type_traits>
 
 namespace bm {
@@ -41,6 +40,7 @@ struct GemmParams {
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n, splits, k_per_split;
   int out_fp32;
+  int xcd_split;                // each k split owns 8/splits XCDs (splits in {2,4,8})
 };
 
 // ---- LDS layouts ---------------------------------------------------------
@@ -154,6 +154,29 @@ struct Stage {
 // XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give
 // each XCD a contiguous run of tiles, walked in column-major groups of GROUP_M
 // tile rows (operand reuse in that XCD's L2).
+__device__ inline void grouped_tile(int id, int tiles_m, int tiles_n, int* tm, int* tn) {
+  constexpr int GROUP_M = 8;
+  const int per_group = GROUP_M * tiles_n;
+  const int g = id / per_group;
+  const int first_m = g * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in = id % per_group;
+  *tm = first_m + in % gsize;
+  *tn = in / gsize;
+}
+
+// K split with XCD affinity: split s owns the 8/splits XCDs s*G .. s*G+G-1 and each of
+// them a contiguous run of that split's tiles, so an operand panel of one k range is
+// fetched by as few L2s as possible (HBM traffic of the weight gradient is dominated by
+// panels fetched once per XCD that touches them).
+__device__ inline void split_tile_of_block(int pid, int tiles, int splits, int tiles_m, int tiles_n,
+                                           int* split, int* tm, int* tn) {
+  const int G = 8 / splits;
+  const int xcd = pid & 7, local = pid >> 3;
+  *split = xcd / G;
+  grouped_tile((xcd % G) * (tiles / G) + local, tiles_m, tiles_n, tm, tn);
+}
+
 __device__ inline void tile_of_block(int pid, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
   constexpr int XCDS = 8, GROUP_M = 8;
   int id = pid;
@@ -180,9 +203,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   const int wm = wave / WN, wn = wave % WN;
 
   const int tiles = p.tiles_m * p.tiles_n;
-  const int split = blockIdx.x / tiles;
+  int split = blockIdx.x / tiles;
   int tm, tn;
-  tile_of_block(blockIdx.x % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
+  if (p.xcd_split) split_tile_of_block(blockIdx.x, tiles, p.splits, p.tiles_m, p.tiles_n, &split, &tm, &tn);
+  else tile_of_block(blockIdx.x % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int kbeg = split * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);
@@ -383,17 +407,24 @@ struct Plan { int bm, bn, tiles_m, tiles_n, splits, k_per_split; };
 
 constexpr int NUM_CU = 256;
 
-// Tile size and K split from a small cost model (microseconds): workgroups run in
-// waves over the free slots (one 256x256 workgroup per CU, two 128x128 ones), each
-// pays a fixed prologue/epilogue plus a per-slice time, and a K split of the weight
-// gradient pays for writing and re-reading its fp32 partial tiles.
+// Tile size and K split from a small cost model in microseconds, calibrated on the
+// weight-gradient shapes of the ViT-L and decoder blocks: workgroups run in rounds over
+// the free slots (one 256x256 workgroup per CU, two 128x128 ones), each pays a fixed
+// prologue/epilogue plus a per-slice time (1.85 us for a 256x256x64 slice, 1.25 us for a
+// 128x128x64 slice that shares its CU with another workgroup), and a K split of the
+// weight gradient pays for writing and re-reading its fp32 partial tiles.  Splits of 2, 4
+// or 8 can be pinned to XCDs (see split_tile_of_block), which measures 4-7 % faster.
+bool xcd_split_possible(int tiles, int splits) {
+  return (splits == 2 || splits == 4 || splits == 8) && tiles % (8 / splits) == 0;
+}
+
 Plan make_plan(int layout, int M, int N, int K) {
   Plan best{};
   double best_t = 1e30;
   const int slices = cdiv(K, BK);
   for (int big = 1; big >= 0; --big) {
     const int tile = big ? 256 : 128;
-    const double t_slice = big ? 1.0 : 0.55, t_fixed = big ? 8.0 : 3.0;
+    const double t_slice = big ? 1.85 : 1.25, t_fixed = big ? 8.0 : 4.0;
     const int slots = big ? NUM_CU : 2 * NUM_CU;
     const long tiles = (long)cdiv(M, tile) * cdiv(N, tile);
     const int max_split = layout == GEMM_TN ? (slices / 4 > 32 ? 32 : (slices / 4 < 1 ? 1 : slices / 4)) : 1;
@@ -401,9 +432,10 @@ Plan make_plan(int layout, int M, int N, int K) {
       const int per = cdiv(slices, sp);
       const int splits = cdiv(slices, per);
       if (splits != sp) continue;
-      const long waves = (tiles * splits + slots - 1) / slots;
-      double t = waves * (per * t_slice + t_fixed);
-      if (splits > 1) t += 3.0 + 2.0 * splits * (double)M * N * 4.0 / 3.0e6;
+      const long rounds = (tiles * splits + slots - 1) / slots;
+      double t = rounds * (per * t_slice + t_fixed);
+      if (splits > 1) t += 3.0 + 1.3 * splits * (double)M * N * 4.0 / 3.0e6;
+      if (xcd_split_possible((int)tiles, splits)) t *= 0.95;
       if (t < best_t * 0.97) {            // prefer the earlier candidate on near ties
         best_t = t;
         best.bm = best.bn = tile;
@@ -468,6 +500,9 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
   p.out_fp32 = epi.out_fp32;
+  {
+    p.xcd_split = xcd_split_possible(pl.tiles_m * pl.tiles_n, pl.splits) ? 1 : 0;
+  }
   if (pl.splits > 1 && (!scratch || scratch_bytes < (size_t)pl.splits * M * N * sizeof(float))) {
     set_error("gemm TN: split reduction needs %zu scratch bytes, got %zu",
               (size_t)pl.splits * M * N * sizeof(float), scratch_bytes);
