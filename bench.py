@@ -33,9 +33,9 @@ HBM_PEAK_GBS = 8000.0
 MIB = 1048576.0
 MEASURED_TRAFFIC_BYTES = {
     "config2_vit_large_bf16": {
-        "gemm_tn": (400.0 + 28.0 + 40.0 + 12.0) * MIB,
-        "gemm_nt": (160.3 + 72.0) * MIB,
-        "gemm_nn": (144.3 + 56.0) * MIB,
+        "gemm_tn": 360.6 * MIB,
+        "gemm_nt": 232.4 * MIB,
+        "gemm_nn": 200.3 * MIB,
     },
 }
 
