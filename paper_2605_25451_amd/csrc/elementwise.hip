@@ -151,8 +151,12 @@ template <int KIND, bool SUMS> struct NormBwdParts {
   static constexpr int NP = (KIND == BM_NORM_LAYERNORM ? 2 : KIND == BM_NORM_RMSNORM ? 1 : 0) + (SUMS ? 2 : 0);
 };
 
+// wavefronts per workgroup (eight were measured slower: 512 threads cap the registers
+// per lane at 128 and the column accumulators spill)
+template <int NV> struct NormBwdWaves { static constexpr int N = 4; };
+
 template <typename T, int KIND, int NV, bool SUMS>
-__global__ __launch_bounds__(256) void norm_bwd_kernel(
+__global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
     const T* __restrict__ dres, T* __restrict__ dx, T* __restrict__ h_out,
     const T* __restrict__ gamma, const T* __restrict__ beta,
@@ -162,6 +166,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
   constexpr int VEC = Elt<T>::VEC;
   constexpr int NP = NormBwdParts<KIND, SUMS>::NP;
   constexpr int NS = SUMS ? NV : 1;
+  constexpr int NW = NormBwdWaves<NV>::N;
   extern __shared__ float sm[];   // [d]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float gam[NV][VEC];
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { acc_r[i][e] = 0.f; acc_o[i][e] = 0.f; }
   const float inv_d = 1.0f / (float)d;
-  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+  for (int row = blockIdx.x * NW + wave; row < rows; row += gridDim.x * NW) {
     const size_t off = (size_t)row * d;
     const float mean = stats[row], rstd = stats[rows + row];
     const float* mrow = nullptr;
@@ -257,11 +262,11 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
       }
     }
   }
-  // combine the four wavefronts through LDS, one after the other (fixed order);
+  // combine the wavefronts through LDS, one after the other (fixed order);
   // adaLN shift/scale gradients are per-sequence sums and have their own kernel
   for (int which = 0; which < NP; ++which) {
     const int what = KIND == BM_NORM_ADALN ? which + 2 : (KIND == BM_NORM_RMSNORM && which > 0 ? which + 1 : which);
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       if (wave == w) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(
       __syncthreads();
     }
     float* prow = partial + ((size_t)blockIdx.x * NP + which) * d;
-    for (int c = threadIdx.x; c < d; c += 256) prow[c] = sm[c];
+    for (int c = threadIdx.x; c < d; c += NW * 64) prow[c] = sm[c];
     __syncthreads();
   }
 }
@@ -381,10 +386,10 @@ static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float
                                    float* partial, hipStream_t st) {
   constexpr int VEC = Elt<T>::VEC;
   int nv = cdiv(a.d, WAVE * VEC);
-  dim3 grid(norm_bwd_blocks(a.T)), block(256);
+  dim3 grid(norm_bwd_blocks(a.T));
   size_t lds = (size_t)a.d * sizeof(float);
 #define BM_LAUNCH_NV(NVV)                                                                        \
-  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS>), grid, block, lds, st, (const T*)x,   \
+  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS>), grid, dim3(NormBwdWaves<NVV>::N * 64), lds, st, (const T*)x,   \
                      stats, (const T*)dh, (const T*)dres, (T*)dx, (T*)h_out, (const T*)a.gamma,  \
                      (const T*)a.beta, a.mod, a.ld_mod, a.shift_off, a.scale_off, a.tok_seq,     \
                      partial, a.T, a.d)
@@ -507,11 +512,26 @@ bm_status rope_inplace(int dtype, void* qkv, int ld, int T, int n_heads, int dh,
 }
 
 // ------------------------------------------------------------------ activations
-__device__ inline float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
-__device__ inline float gelu_grad_f(float z) {
-  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
-  float pdf = expf(-0.5f * z * z) * 0.39894228040143268f;
-  return cdf + z * pdf;
+// Phi(z) = (1 + erf(z / sqrt 2)) / 2 and phi(z) = exp(-z^2/2) / sqrt(2 pi) from ONE
+// exponential: erfc(x) = (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0
+// (Abramowitz & Stegun 7.1.26, absolute error below 1.5e-7, i.e. fp32 rounding level),
+// and exp(-x^2) with x = |z| / sqrt 2 is the exponential of the density.
+__device__ inline void normal_cdf_pdf(float z, float* cdf, float* pdf) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
+  float poly = fmaf(t, 1.061405429f, -1.453152027f);
+  poly = fmaf(t, poly, 1.421413741f);
+  poly = fmaf(t, poly, -0.284496736f);
+  poly = fmaf(t, poly, 0.254829592f);
+  const float half_erfc = 0.5f * t * poly * e;
+  *cdf = z >= 0.f ? 1.0f - half_erfc : half_erfc;
+  *pdf = e * 0.39894228040143268f;
+}
+__device__ inline float gelu_f(float z) {
+  float cdf, pdf;
+  normal_cdf_pdf(z, &cdf, &pdf);
+  return z * cdf;
 }
 __device__ inline float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
 
@@ -558,34 +578,53 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const T* __restrict__ up, 
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   if (c < F) {
-    for (long t = r0 + wave; t < r1; t += 4) {
-      float d[VEC];
-      load16(da + t * F + c, d);
-      if (ACT == BM_ACT_GELU) {
-        float z[VEC], out[VEC], act[VEC];
-        load16(up + t * F + c, z);
+    // two rows per trip: all loads of both rows are issued before any arithmetic
+    for (long t = r0 + wave; t < r1; t += 8) {
+      constexpr int NIN = ACT == BM_ACT_GELU ? 1 : 2;
+      float d[2][VEC], in[2][NIN][VEC];
+      const bool two = t + 4 < r1;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          float cdf = 0.5f * (1.0f + erff(z[e] * 0.70710678118654752f));
-          float pdf = expf(-0.5f * z[e] * z[e]) * 0.39894228040143268f;
-          out[e] = d[e] * (cdf + z[e] * pdf);
-          act[e] = gelu_f(z[e]);
-          if (COLSUM) acc[e] += Elt<T>::to_f(Elt<T>::from_f(out[e]));
+      for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !two) break;
+        const long tt = t + 4 * h;
+        load16(da + tt * F + c, d[h]);
+        if (ACT == BM_ACT_GELU) {
+          load16(up + tt * F + c, in[h][0]);
+        } else {
+          load16(up + tt * 2 * F + c, in[h][0]);
+          load16(up + tt * 2 * F + F + c, in[h][NIN - 1]);
         }
-        store16(dup + t * F + c, out);
-        if (a_out) store16(a_out + t * F + c, act);
-      } else {
-        float g[VEC], u[VEC], dg[VEC], du[VEC], act[VEC];
-        load16(up + t * 2 * F + c, g); load16(up + t * 2 * F + F + c, u);
+      }
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          float sg = sigmoid_f(g[e]);
-          dg[e] = d[e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
-          du[e] = d[e] * g[e] * sg;
-          act[e] = g[e] * sg * u[e];
+      for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !two) break;
+        const long tt = t + 4 * h;
+        if (ACT == BM_ACT_GELU) {
+          float out[VEC], act[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const float z = in[h][0][e];
+            float cdf, pdf;
+            normal_cdf_pdf(z, &cdf, &pdf);
+            out[e] = d[h][e] * (cdf + z * pdf);
+            act[e] = z * cdf;
+            if (COLSUM) acc[e] += Elt<T>::to_f(Elt<T>::from_f(out[e]));
+          }
+          store16(dup + tt * F + c, out);
+          if (a_out) store16(a_out + tt * F + c, act);
+        } else {
+          float dg[VEC], du[VEC], act[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const float g = in[h][0][e], u = in[h][NIN - 1][e];
+            float sg = sigmoid_f(g);
+            dg[e] = d[h][e] * u * sg * (1.0f + g * (1.0f - sg));
+            du[e] = d[h][e] * g * sg;
+            act[e] = g * sg * u;
+          }
+          store16(dup + tt * 2 * F + c, dg); store16(dup + tt * 2 * F + F + c, du);
+          if (a_out) store16(a_out + tt * F + c, act);
         }
-        store16(dup + t * 2 * F + c, dg); store16(dup + t * 2 * F + F + c, du);
-        if (a_out) store16(a_out + t * F + c, act);
       }
     }
   }
