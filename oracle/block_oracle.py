@@ -201,6 +201,84 @@ NORM_LAYERNORM, NORM_RMSNORM, NORM_ADALN = 0, 1, 2
 ACT_GELU, ACT_SWIGLU = 0, 1
 
 
+# ---------------------------------------------------------------------------
+# mixture-of-experts FFN (the paper's LLM backbone is a mixture-of-experts model,
+# Sec. 4.1, and Sec. 3.3 names expert imbalance as a source of uneven operator
+# times; it gives no arithmetic).  Reading: router logits = h W_r^T (no bias),
+# probabilities = softmax over the experts, the k most probable experts are
+# chosen (ties: lower expert index), their probabilities renormalised to sum 1
+# are the gates, every expert is a SwiGLU FFN, no token is dropped, no
+# auxiliary loss.
+# ---------------------------------------------------------------------------
+
+def moe_route(logits, k):
+    """(idx [T,k] by descending probability, gate [T,k], probs [T,E])."""
+    z = logits - logits.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    probs = e / e.sum(axis=1, keepdims=True)
+    T, E = probs.shape
+    # descending probability, ties to the lower expert index (stable sort of the negated row)
+    idx = np.argsort(-probs, axis=1, kind="stable")[:, :k]
+    sel = np.take_along_axis(probs, idx, axis=1)
+    gate = sel / sel.sum(axis=1, keepdims=True)
+    return idx, gate, probs
+
+
+def moe_ffn_fwd(h, p, E, k, F):
+    """out[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(h[t]);  returns (out, cache).
+    Expert by expert: the tokens (and their choice slot j) that picked expert e."""
+    T, d = h.shape
+    logits = h @ p["w_router"].T
+    idx, gate, probs = moe_route(logits, k)
+    w_up = p["w_up"].reshape(E, 2 * F, d)
+    w_down = p["w_down"].reshape(E, d, F)
+    ys = np.zeros((T, k, d))
+    ups = np.zeros((T, k, 2 * F))
+    acts = np.zeros((T, k, F))
+    for e in range(E):
+        t, j = np.nonzero(idx == e)
+        if t.size == 0:
+            continue
+        up = h[t] @ w_up[e].T
+        a = silu(up[:, :F]) * up[:, F:]
+        ups[t, j], acts[t, j] = up, a
+        ys[t, j] = a @ w_down[e].T
+    out = (gate[:, :, None] * ys).sum(axis=1)
+    return out, dict(idx=idx, gate=gate, probs=probs, ys=ys, ups=ups, acts=acts)
+
+
+def moe_ffn_bwd(dm, h, p, mc, E, k, F):
+    """Gradients of moe_ffn_fwd: (dh, {"w_router", "w_up", "w_down"})."""
+    T, d = h.shape
+    idx, gate, probs, ys, ups, acts = (mc[n] for n in ("idx", "gate", "probs", "ys", "ups", "acts"))
+    w_up = p["w_up"].reshape(E, 2 * F, d)
+    w_down = p["w_down"].reshape(E, d, F)
+    g_up = np.zeros_like(w_up); g_down = np.zeros_like(w_down)
+    dh = np.zeros_like(h)
+    dgate = np.einsum("td,tkd->tk", dm, ys)
+    for e in range(E):
+        t, j = np.nonzero(idx == e)
+        if t.size == 0:
+            continue
+        dy = gate[t, j][:, None] * dm[t]
+        g_down[e] = dy.T @ acts[t, j]
+        da = dy @ w_down[e]
+        gt, lin = ups[t, j, :F], ups[t, j, F:]
+        dup = np.concatenate([da * lin * silu_grad(gt), da * silu(gt)], axis=1)
+        g_up[e] = dup.T @ h[t]
+        np.add.at(dh, t, dup @ w_up[e])
+    # gates = selected probabilities / their sum; probabilities = softmax(logits)
+    sel = np.take_along_axis(probs, idx, axis=1)
+    ssum = sel.sum(axis=1, keepdims=True)
+    dsel = (dgate - (dgate * gate).sum(axis=1, keepdims=True)) / ssum
+    dprobs = np.zeros_like(probs)
+    np.put_along_axis(dprobs, idx, dsel, axis=1)
+    dlogits = probs * (dprobs - (probs * dprobs).sum(axis=1, keepdims=True))
+    g_router = dlogits.T @ h
+    dh += dlogits @ p["w_router"]
+    return dh, {"w_router": g_router, "w_up": g_up.reshape(E * 2 * F, d), "w_down": g_down.reshape(E * d, F)}
+
+
 def block_forward(cfg, params, x, cu_seqlens, cond=None):
     """Forward of one block.  ``cfg`` needs the fields hidden, n_q_heads,
     n_kv_heads, head_dim, mlp_hidden, norm, act, mask, rope, rope_base,
@@ -251,16 +329,21 @@ def block_forward(cfg, params, x, cu_seqlens, cond=None):
     else:
         xhat2, c["n2"] = layernorm_fwd(x1, None, None, cfg.norm_eps)
         h2 = xhat2 * (1.0 + sc2[sid]) + sh2[sid]
-    up = h2 @ p["w_up"].T
-    if "b_up" in p:
-        up = up + p["b_up"]
-    if cfg.act == ACT_GELU:
-        a = gelu(up)
+    E = getattr(cfg, "n_experts", 0)
+    if E > 0:
+        m, c["moe"] = moe_ffn_fwd(h2, p, E, cfg.top_k, F)
+        up = a = None
     else:
-        a = silu(up[:, :F]) * up[:, F:]
-    m = a @ p["w_down"].T
-    if "b_down" in p:
-        m = m + p["b_down"]
+        up = h2 @ p["w_up"].T
+        if "b_up" in p:
+            up = up + p["b_up"]
+        if cfg.act == ACT_GELU:
+            a = gelu(up)
+        else:
+            a = silu(up[:, :F]) * up[:, F:]
+        m = a @ p["w_down"].T
+        if "b_down" in p:
+            m = m + p["b_down"]
     y = x1 + (g2[sid] * m if cfg.norm == NORM_ADALN else m)
 
     c.update(x=x, h=h, q=q, k=k, v=v, o=o, attn=attn, x1=x1, h2=h2, up=up, a=a, m=m)
@@ -289,20 +372,25 @@ def block_backward(cfg, params, cache, dy):
         dm = dy * g2[sid]
     else:
         dm = dy
-    g["w_down"] = dm.T @ c["a"]
-    if "b_down" in p:
-        g["b_down"] = dm.sum(axis=0)
-    da = dm @ p["w_down"]
-    up = c["up"]
-    if cfg.act == ACT_GELU:
-        dup = da * gelu_grad(up)
+    E = getattr(cfg, "n_experts", 0)
+    if E > 0:
+        dh2, gm = moe_ffn_bwd(dm, c["h2"], p, c["moe"], E, cfg.top_k, F)
+        g.update(gm)
     else:
-        gate, lin = up[:, :F], up[:, F:]
-        dup = np.concatenate([da * lin * silu_grad(gate), da * silu(gate)], axis=1)
-    g["w_up"] = dup.T @ c["h2"]
-    if "b_up" in p:
-        g["b_up"] = dup.sum(axis=0)
-    dh2 = dup @ p["w_up"]
+        g["w_down"] = dm.T @ c["a"]
+        if "b_down" in p:
+            g["b_down"] = dm.sum(axis=0)
+        da = dm @ p["w_down"]
+        up = c["up"]
+        if cfg.act == ACT_GELU:
+            dup = da * gelu_grad(up)
+        else:
+            gate, lin = up[:, :F], up[:, F:]
+            dup = np.concatenate([da * lin * silu_grad(gate), da * silu(gate)], axis=1)
+        g["w_up"] = dup.T @ c["h2"]
+        if "b_up" in p:
+            g["b_up"] = dup.sum(axis=0)
+        dh2 = dup @ p["w_up"]
     if cfg.norm == NORM_LAYERNORM:
         dxn, g["norm2_g"], g["norm2_b"] = layernorm_bwd(dh2, p["norm2_g"], c["n2"])
     elif cfg.norm == NORM_RMSNORM:

@@ -26,6 +26,7 @@ PARAM_NAMES = (
     "norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
     "norm2_g", "norm2_b", "w_up", "b_up", "w_down", "b_down",
     "w_ada", "b_ada",
+    "w_router",
 )
 
 NORM_LAYERNORM, NORM_RMSNORM, NORM_ADALN = 0, 1, 2
@@ -50,6 +51,9 @@ class BlockConfig:
     norm_eps: float = 1e-5
     linear_bias: int = 1
     dtype: int = DTYPE_BF16
+    n_experts: int = 0          # > 0: mixture-of-experts FFN, mlp_hidden is the width of ONE expert
+    top_k: int = 0
+    router_std: float = 0.02    # std of the router matrix (drawn apart from the other weights)
 
     @property
     def qkv_dim(self) -> int:
@@ -71,8 +75,11 @@ class BlockConfig:
             s["norm1_g"] = (d,); s["norm2_g"] = (d,)
         s["w_qkv"] = (self.qkv_dim, d)
         s["w_o"] = (d, qd)
-        s["w_up"] = (self.up_dim, d)
-        s["w_down"] = (d, f)
+        e = max(self.n_experts, 1)
+        s["w_up"] = (e * self.up_dim, d)        # expert-major; per expert gate rows first, then linear rows
+        s["w_down"] = (e * d, f)                # expert-major; per expert a [d, f] matrix
+        if self.n_experts > 0:
+            s["w_router"] = (self.n_experts, d)
         if self.linear_bias:
             s["b_qkv"] = (self.qkv_dim,); s["b_o"] = (d,)
             s["b_up"] = (self.up_dim,); s["b_down"] = (d,)
@@ -103,6 +110,17 @@ def decoder_8b_gqa(dtype: int = DTYPE_BF16) -> BlockConfig:
     return BlockConfig(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, mlp_hidden=14336,
                        norm=NORM_RMSNORM, act=ACT_SWIGLU, mask=MASK_CAUSAL,
                        rope=1, rope_base=500000.0, norm_eps=1e-6, linear_bias=0, dtype=dtype)
+
+
+def decoder_moe(dtype: int = DTYPE_BF16) -> BlockConfig:
+    """Decoder block with a mixture-of-experts FFN in the shape of the paper's backbone family
+    (Sec. 4.1 names a 30B-A3B model): hidden 2048, 16 q / 4 kv heads of 128 (the library keeps
+    hidden = heads x head size), 128 experts of width 768, 8 active per token, normalised
+    top-k gates."""
+    return BlockConfig(hidden=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, mlp_hidden=768,
+                       norm=NORM_RMSNORM, act=ACT_SWIGLU, mask=MASK_CAUSAL,
+                       rope=1, rope_base=1000000.0, norm_eps=1e-6, linear_bias=0, dtype=dtype,
+                       n_experts=128, top_k=8, router_std=0.02)
 
 
 def dit_block(dtype: int = DTYPE_BF16) -> BlockConfig:
@@ -259,7 +277,8 @@ def draw_params(rng, cfg: BlockConfig, std: float = 0.02) -> Dict[str, np.ndarra
     out = {}
     for name, shape in cfg.param_shapes().items():
         mean = 1.0 if name in ("norm1_g", "norm2_g") else 0.0
-        out[name] = to_storage(_normal(rng, shape, std, mean), cfg.dtype)
+        sd = cfg.router_std if name == "w_router" else std
+        out[name] = to_storage(_normal(rng, shape, sd, mean), cfg.dtype)
     return out
 
 

@@ -24,7 +24,10 @@ def tiny_cases():
     gqa = synth.scaled(synth.decoder_8b_gqa(), **{**TINY, "n_kv_heads": 2})
     dit = synth.scaled(synth.dit_block(), **TINY)
     vit_causal = synth.scaled(vit, mask=synth.MASK_CAUSAL)
+    moe = synth.scaled(synth.decoder_moe(), **{**TINY, "n_kv_heads": 2, "mlp_hidden": 12},
+                       n_experts=4, top_k=2, router_std=0.6)
     return {
+        "moe": synth.make_case(moe, [5, 4], 15, weight_std=0.3),
         "vit": synth.make_case(vit, [3, 5], 10, weight_std=0.3),
         "vit_causal": synth.make_case(vit_causal, [4, 3], 11, weight_std=0.3),
         "decoder": synth.make_case(dec, [5, 2, 4], 12, weight_std=0.3),
