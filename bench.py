@@ -2,7 +2,7 @@
 """Benchmark of the hot path: forward + backward of one packed variable-length
 transformer block on one MI355X, through the C-ABI library.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit|moe]
   python bench.py --workload config5 --batch 8|16|32 [--unit-size 1] [--steps K]
   python bench.py --workload pipeline [--steps K]
 
@@ -40,13 +40,28 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def moe_case(seed=5, total=8192):
+    """Decoder block with the mixture-of-experts FFN (128 experts of width 768, 8 per token,
+    hidden 2048) over config-3-style documents."""
+    import numpy as np
+    from paper_2605_25451_amd import synth
+    rng = np.random.default_rng(seed)
+    docs = synth.documents_interleaved(rng, total)
+    return synth.make_case(synth.decoder_moe(), [d.length for d in docs], seed, rng=rng, docs=docs,
+                           name="moe_decoder_bf16")
+
+
 def algorithmic_flops(cfg, cu):
     """(gemm_fwd, attn_fwd) flops of one block over the packed batch."""
     import numpy as np
     T = int(cu[-1])
     d, F = cfg.hidden, cfg.mlp_hidden
     qd = cfg.n_q_heads * cfg.head_dim
-    gemm = 2.0 * T * d * cfg.qkv_dim + 2.0 * T * qd * d + 2.0 * T * d * cfg.up_dim + 2.0 * T * F * d
+    gemm = 2.0 * T * d * cfg.qkv_dim + 2.0 * T * qd * d
+    if getattr(cfg, "n_experts", 0) > 0:      # router + k active experts per token
+        gemm += 2.0 * T * d * cfg.n_experts + cfg.top_k * (2.0 * T * d * cfg.up_dim + 2.0 * T * F * d)
+    else:
+        gemm += 2.0 * T * d * cfg.up_dim + 2.0 * T * F * d
     if cfg.norm == 2:
         gemm += 2.0 * (len(cu) - 1) * d * 6 * d
     L = np.diff(cu).astype(np.float64)
@@ -87,6 +102,8 @@ def make_workload(name):
         return synth.config4()
     if name == "dit":
         return synth.dit_case()
+    if name == "moe":
+        return moe_case()
     raise SystemExit(f"unknown workload {name}")
 
 

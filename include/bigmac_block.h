@@ -75,6 +75,13 @@ typedef struct {
   int32_t dtype;        /* BM_DTYPE_*                                                      */
   int32_t deterministic;/* reserved; every kernel here is free of floating-point atomics,
                            so results are run-to-run bit-identical either way             */
+  int32_t n_experts;    /* 0: dense FFN.  > 0 (<= 256): mixture-of-experts FFN (the paper's
+                           LLM backbone, Sec. 4.1): router logits h W_r^T, softmax over the
+                           experts, the top_k most probable experts (ties: lower index) with
+                           their probabilities renormalised to sum 1 as gates, every expert a
+                           SwiGLU FFN of width mlp_hidden, no token dropped.  Needs
+                           act = SwiGLU, linear_bias = 0, a norm other than adaLN.            */
+  int32_t top_k;        /* 1..min(8, n_experts)                                             */
 } bm_block_desc;
 
 /* Parameters (storage dtype) -- and, with the same field meaning, their
@@ -85,9 +92,10 @@ typedef struct {
   void *w_qkv,  *b_qkv;      /* [(Hq+2Hkv)dh,d], [(Hq+2Hkv)dh]                             */
   void *w_o,    *b_o;        /* [d, Hq*dh], [d]                                            */
   void *norm2_g, *norm2_b;
-  void *w_up,   *b_up;       /* [F,d] or [2F,d];  [F] or [2F]                              */
-  void *w_down, *b_down;     /* [d,F], [d]                                                 */
+  void *w_up,   *b_up;       /* [F,d] or [2F,d];  [F] or [2F]; with experts [E,2F,d]       */
+  void *w_down, *b_down;     /* [d,F], [d]; with experts [E,d,F]                           */
   void *w_ada,  *b_ada;      /* [6d,d], [6d]    (adaLN only)                               */
+  void *w_router;            /* [E,d]           (mixture of experts only)                  */
 } bm_block_params;
 
 /* Last error text of the calling thread ("" if none). Never NULL. */

@@ -24,7 +24,7 @@ OP_ENC_FWD, OP_ENC_BWD, OP_LLM_FWD, OP_LLM_BWD, OP_GEN_FWD, OP_GEN_BWD = range(6
 ORDER_NESTED, ORDER_COMPUTE_EFFICIENT, ORDER_SEQUENTIAL, ORDER_MEMORY_EFFICIENT = 0, 1, 2, 3
 
 PARAM_FIELDS = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b",
-                "w_up", "b_up", "w_down", "b_down", "w_ada", "b_ada")
+                "w_up", "b_up", "w_down", "b_down", "w_ada", "b_ada", "w_router")
 
 
 class BmError(RuntimeError):
@@ -38,7 +38,8 @@ class BlockDesc(C.Structure):
                 ("head_dim", C.c_int32), ("mlp_hidden", C.c_int32), ("norm", C.c_int32),
                 ("act", C.c_int32), ("mask", C.c_int32), ("rope", C.c_int32),
                 ("rope_base", C.c_float), ("norm_eps", C.c_float), ("linear_bias", C.c_int32),
-                ("dtype", C.c_int32), ("deterministic", C.c_int32)]
+                ("dtype", C.c_int32), ("deterministic", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32)]
 
 
 class BlockParams(C.Structure):
@@ -178,7 +179,8 @@ def make_desc(cfg) -> BlockDesc:
     """From any object with the BlockDesc field names (e.g. synth.BlockConfig)."""
     return BlockDesc(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.mlp_hidden,
                      cfg.norm, cfg.act, cfg.mask, cfg.rope, cfg.rope_base, cfg.norm_eps,
-                     cfg.linear_bias, cfg.dtype, getattr(cfg, "deterministic", 1))
+                     cfg.linear_bias, cfg.dtype, getattr(cfg, "deterministic", 1),
+                     getattr(cfg, "n_experts", 0), getattr(cfg, "top_k", 0))
 
 
 def make_params(tensors: Dict[str, object]) -> BlockParams:

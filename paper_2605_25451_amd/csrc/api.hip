@@ -62,6 +62,23 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
   return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
 }
 
+bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
+                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st) {
+  if (M <= 0 || N <= 0) return BM_OK;
+  const int rows = layout == GEMM_TN ? K : M;
+  if (rows % MOE_PAD) { set_error("grouped gemm: %d rows are not a multiple of %d", rows, MOE_PAD); return BM_ERR_INVALID_ARG; }
+  if (layout == GEMM_TN ? (!g.group_rows || g.n_groups < 1) : !g.tile_group) {
+    set_error("grouped gemm: group tables are NULL");
+    return BM_ERR_INVALID_ARG;
+  }
+  // algorithmic work: the rows that carry tokens, not the padded capacity
+  const double rows_used = g.routed_rows > 0 ? (double)g.routed_rows : (double)rows;
+  ProfScope prof(PROF_GEMM_NT + layout, layout == GEMM_TN ? 2.0 * M * N * rows_used : 2.0 * rows_used * N * K, st);
+  if (gemm_mfma_grouped_supported(layout, dtype, M, N, K, lda, ldb, ldc))
+    return gemm_mfma_grouped(layout, M, N, K, A, lda, B, ldb, C, ldc, g, st);
+  return gemm_generic_grouped(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, g, st);
+}
+
 }  // namespace bm
 
 using namespace bm;

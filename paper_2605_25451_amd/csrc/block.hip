@@ -17,6 +17,7 @@ struct Dims {
   int T, S, d, Hq, Hkv, dh, F, QKV, UP, QD;
   size_t es;   // element size
   bool ada;
+  int E, k, cap;   // mixture of experts: experts, choices per token, padded row capacity (0 = dense)
 };
 
 Dims make_dims(const bm_block_desc& c, int T, int S) {
@@ -28,12 +29,16 @@ Dims make_dims(const bm_block_desc& c, int T, int S) {
   m.UP = m.F * (c.act == BM_ACT_SWIGLU ? 2 : 1);
   m.es = elt_size(c.dtype);
   m.ada = c.norm == BM_NORM_ADALN;
+  m.E = c.n_experts; m.k = c.top_k;
+  m.cap = m.E > 0 ? moe_row_capacity(T, m.E, m.k) : 0;
   return m;
 }
 
 struct Saved {
   float *stats1, *stats2, *lse, *mod;
   char *qkv, *o, *x1, *up, *attn, *m;
+  MoeTables moe;      // routing tables of the forward pass
+  char* moe_y;        // [cap, d] expert outputs in the expert-sorted layout
   size_t bytes;
 };
 
@@ -47,7 +52,21 @@ Saved layout_saved(const Dims& m, void* base) {
   s.qkv = a.take<char>(T * m.QKV * m.es);
   s.o = a.take<char>(T * m.QD * m.es);
   s.x1 = a.take<char>(T * m.d * m.es);
-  s.up = a.take<char>(T * m.UP * m.es);
+  // dense: [T, UP]; experts: [cap, 2F] pre-activations in the expert-sorted layout
+  s.up = a.take<char>((m.E > 0 ? (size_t)m.cap : T) * m.UP * m.es);
+  s.moe_y = nullptr;
+  if (m.E > 0) {
+    s.moe.cap = m.cap;
+    s.moe.probs = a.take<float>(T * m.E * sizeof(float));
+    s.moe.idx = a.take<int32_t>(T * m.k * sizeof(int32_t));
+    s.moe.gate = a.take<float>(T * m.k * sizeof(float));
+    s.moe.slot = a.take<int32_t>(T * m.k * sizeof(int32_t));
+    s.moe.row_token = a.take<int32_t>((size_t)m.cap * sizeof(int32_t));
+    s.moe.row_gate = a.take<float>((size_t)m.cap * sizeof(float));
+    s.moe.tile_group = a.take<int32_t>((size_t)(m.cap / MOE_PAD) * sizeof(int32_t));
+    s.moe.expert_rows = a.take<int32_t>((size_t)(m.E + 1) * sizeof(int32_t));
+    s.moe_y = a.take<char>((size_t)m.cap * m.d * m.es);
+  }
   s.mod = nullptr; s.attn = nullptr; s.m = nullptr;
   if (m.ada) {
     s.mod = a.take<float>((size_t)m.S * 6 * m.d * sizeof(float));
@@ -61,6 +80,8 @@ Saved layout_saved(const Dims& m, void* base) {
 struct FwdScratch {
   int32_t* tok_seq;
   char *h, *a, *sc;
+  float* logits;          // experts: [T, E]
+  char *xp, *moe_ws;      // experts: [cap, d] routed inputs; layout scratch
   size_t bytes;
 };
 
@@ -70,8 +91,14 @@ FwdScratch layout_fwd(const Dims& m, void* base) {
   const size_t T = m.T;
   s.tok_seq = a.take<int32_t>(T * sizeof(int32_t));
   s.h = a.take<char>(T * m.d * m.es);
-  s.a = a.take<char>(T * m.F * m.es);
+  s.a = a.take<char>((m.E > 0 ? (size_t)m.cap : T) * m.F * m.es);
   s.sc = m.ada ? a.take<char>((size_t)m.S * m.d * m.es) : nullptr;
+  s.logits = nullptr; s.xp = nullptr; s.moe_ws = nullptr;
+  if (m.E > 0) {
+    s.logits = a.take<float>(T * m.E * sizeof(float));
+    s.xp = a.take<char>((size_t)m.cap * m.d * m.es);
+    s.moe_ws = a.take<char>(moe_layout_scratch_bytes(m.T, m.E));
+  }
   s.bytes = a.off;
   return s;
 }
@@ -83,13 +110,20 @@ struct BwdScratch {
   size_t attn_ws_bytes, gemm_ws_bytes;
   float *dmod, *dsc;
   char *dmod_e, *sc;
+  char *dyp, *xp, *dlogits, *dh2e;   // experts: routed output grads [cap,d], routed inputs [cap,d],
+                                     // router logit grads [T,E], expert part of the norm-2 output grad [T,d]
   size_t bytes;
 };
 
 size_t max_gemm_tn_scratch(const Dims& m, int dtype) {
   size_t b = 0, v;
-  v = gemm_scratch_bytes(GEMM_TN, m.d, m.F, m.T, dtype); b = v > b ? v : b;
-  v = gemm_scratch_bytes(GEMM_TN, m.UP, m.d, m.T, dtype); b = v > b ? v : b;
+  if (m.E > 0) {
+    v = gemm_scratch_bytes(GEMM_TN, m.E, m.d, m.T, dtype); b = v > b ? v : b;
+    v = gemm_scratch_bytes(GEMM_NN, m.T, m.d, m.E, dtype); b = v > b ? v : b;
+  } else {
+    v = gemm_scratch_bytes(GEMM_TN, m.d, m.F, m.T, dtype); b = v > b ? v : b;
+    v = gemm_scratch_bytes(GEMM_TN, m.UP, m.d, m.T, dtype); b = v > b ? v : b;
+  }
   v = gemm_scratch_bytes(GEMM_TN, m.d, m.QD, m.T, dtype); b = v > b ? v : b;
   v = gemm_scratch_bytes(GEMM_TN, m.QKV, m.d, m.T, dtype); b = v > b ? v : b;
   if (m.ada) {
@@ -104,9 +138,10 @@ BwdScratch layout_bwd(const Dims& m, int dtype, void* base) {
   BwdScratch s;
   const size_t T = m.T;
   s.tok_seq = a.take<int32_t>(T * sizeof(int32_t));
-  s.a = a.take<char>(T * m.F * m.es);
-  s.dup = a.take<char>(T * m.UP * m.es);
-  s.da = a.take<char>(T * m.F * m.es);
+  const size_t R = m.E > 0 ? (size_t)m.cap : T;     // rows of the FFN activations
+  s.a = a.take<char>(R * m.F * m.es);
+  s.dup = a.take<char>(R * m.UP * m.es);
+  s.da = a.take<char>(R * m.F * m.es);
   s.h = a.take<char>(T * m.d * m.es);
   s.dh = a.take<char>(T * m.d * m.es);
   s.dx1 = a.take<char>(T * m.d * m.es);
@@ -120,6 +155,13 @@ BwdScratch layout_bwd(const Dims& m, int dtype, void* base) {
   s.colsum_ws = a.take<char>(colsum_scratch_bytes(m.T, widest));
   s.gemm_ws_bytes = max_gemm_tn_scratch(m, dtype);
   s.gemm_ws = a.take<char>(s.gemm_ws_bytes);
+  s.dyp = nullptr; s.xp = nullptr; s.dlogits = nullptr; s.dh2e = nullptr;
+  if (m.E > 0) {
+    s.dyp = a.take<char>((size_t)m.cap * m.d * m.es);
+    s.xp = a.take<char>((size_t)m.cap * m.d * m.es);
+    s.dlogits = a.take<char>(T * m.E * m.es);
+    s.dh2e = a.take<char>(T * m.d * m.es);
+  }
   s.dgated = nullptr; s.dmod = nullptr; s.dsc = nullptr; s.dmod_e = nullptr; s.sc = nullptr;
   if (m.ada) {
     s.dgated = a.take<char>(T * m.d * m.es);
@@ -156,6 +198,14 @@ bm_status check_desc(const bm_block_desc* c) {
   if (c->rope && (c->head_dim / 2) % vec) {
     set_error("desc: RoPE needs head_dim/2 to be a multiple of %d", vec);
     return BM_ERR_UNSUPPORTED;
+  }
+  BM_ARG_CHECK(c->n_experts >= 0, "desc: n_experts %d", c->n_experts);
+  if (c->n_experts > 0) {
+    BM_RETURN_IF(moe_check(c->n_experts, c->top_k, c->hidden, c->dtype));
+    if (c->act != BM_ACT_SWIGLU || c->linear_bias || c->norm == BM_NORM_ADALN) {
+      set_error("desc: experts need act = SwiGLU, linear_bias = 0 and a norm other than adaLN");
+      return BM_ERR_UNSUPPORTED;
+    }
   }
   switch (c->head_dim) {
     case 8: case 16: case 32: case 64: case 72: case 128: break;
@@ -194,6 +244,7 @@ bm_status check_params(const bm_block_desc& c, const bm_block_params* p, const c
   NEED(b_qkv, c.linear_bias); NEED(b_o, c.linear_bias); NEED(b_up, c.linear_bias);
   NEED(b_down, c.linear_bias);
   NEED(w_ada, ada); NEED(b_ada, ada);
+  NEED(w_router, c.n_experts > 0);
 #undef NEED
   return BM_OK;
 }
@@ -295,6 +346,30 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
   }
   // MLP half
   { ProfScope _p(PROF_NORM, 2.0 * T * m.d * (double)m.es, st); BM_RETURN_IF(norm_forward(norm_args(c, m, 2, w, sv.mod, ws.tok_seq), sv.x1, ws.h, sv.stats2, 1, st)); }
+  if (m.E > 0) {
+    // mixture of experts: route, sort the routed rows by expert, run the expert FFNs as
+    // grouped GEMMs over the sorted rows, and sum each token's k gated outputs
+    {
+      GemmEpilogue e; e.out_fp32 = 1;
+      BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.E, m.d, ws.h, m.d, w->w_router, m.d, ws.logits, m.E, e,
+                        nullptr, 0, st));
+    }
+    GemmGroups g;
+    g.tile_group = sv.moe.tile_group; g.routed_rows = (long)T * m.k;
+    {
+      ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
+      BM_RETURN_IF(moe_route(ws.logits, T, m.E, m.k, sv.moe.probs, sv.moe.idx, sv.moe.gate, st));
+      BM_RETURN_IF(moe_layout(sv.moe, T, m.E, m.k, ws.moe_ws, st));
+      BM_RETURN_IF(moe_gather(dt, ws.h, sv.moe, 0, ws.xp, m.d, T, st));
+    }
+    g.b_stride = (long)m.UP * m.d;
+    BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.UP, m.d, ws.xp, m.d, w->w_up, m.d, sv.up, m.UP, g, st));
+    { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, m.cap, m.F, st)); }
+    g.b_stride = (long)m.d * m.F;
+    BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.d, m.F, ws.a, m.F, w->w_down, m.F, sv.moe_y, m.d, g, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(moe_combine(dt, sv.moe_y, sv.moe, 1, sv.x1, y, T, m.k, m.d, st)); }
+    return BM_OK;
+  }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_up : nullptr;
     BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.UP, m.d, ws.h, m.d, w->w_up, m.d, sv.up, m.UP, e,
@@ -351,6 +426,42 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, dy, sv.mod + 5 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
     dm = ws.dgated;
   }
+  const bool fused_sums = c.linear_bias && !m.ada;
+  if (m.E > 0) {
+    // ---- mixture of experts (dm = dy: no gate sits on this branch)
+    GemmGroups g;
+    g.tile_group = sv.moe.tile_group; g.group_rows = sv.moe.expert_rows; g.n_groups = m.E;
+    g.routed_rows = (long)T * m.k;
+    {
+      ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
+      BM_RETURN_IF(moe_gather(dt, dm, sv.moe, 1, ws.dyp, d, T, st));            // gate * dy of the row's token
+      BM_RETURN_IF(moe_router_backward(dt, dm, sv.moe_y, sv.moe, ws.dlogits, T, m.E, m.k, d, st));
+    }
+    g.b_stride = (long)d * m.F;
+    BM_RETURN_IF(gemm_grouped(GEMM_NN, dt, m.cap, m.F, d, ws.dyp, d, w->w_down, m.F, ws.da, m.F, g, st));
+    { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
+      BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a, nullptr, ws.colsum_ws, m.cap, m.F, st)); }
+    g.c_stride = (long)d * m.F;
+    BM_RETURN_IF(gemm_grouped(GEMM_TN, dt, d, m.F, m.cap, ws.dyp, d, ws.a, m.F, grads->w_down, m.F, g, st));
+    g.b_stride = (long)m.UP * d;
+    char* dxp = ws.dyp;                                  // the routed output gradient is spent
+    BM_RETURN_IF(gemm_grouped(GEMM_NN, dt, m.cap, d, m.UP, ws.dup, m.UP, w->w_up, d, dxp, d, g, st));
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(moe_combine(dt, dxp, sv.moe, 0, nullptr, ws.dh2e, T, m.k, d, st)); }
+    {
+      GemmEpilogue e; e.residual = ws.dh2e;              // + the router's path
+      BM_RETURN_IF(gemm(GEMM_NN, dt, T, d, m.E, ws.dlogits, m.E, w->w_router, d, ws.dh, d, e, ws.gemm_ws,
+                        ws.gemm_ws_bytes, st));
+    }
+    NormArgs n2 = norm_args(c, m, 2, w, sv.mod, ws.tok_seq);
+    { ProfScope _p(PROF_NORM, 5.0 * T * m.d * (double)m.es, st);
+      BM_RETURN_IF(norm_backward(n2, sv.x1, sv.stats2, ws.dh, dy, ws.dx1, ws.h, (float*)grads->norm2_g,
+                                 (float*)grads->norm2_b, nullptr, nullptr, ws.dmod, cu_dev, S, ws.norm_ws, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(moe_gather(dt, ws.h, sv.moe, 0, ws.xp, d, T, st)); }
+    g.c_stride = (long)m.UP * d;
+    BM_RETURN_IF(gemm_grouped(GEMM_TN, dt, m.UP, d, m.cap, ws.dup, m.UP, ws.xp, d, grads->w_up, d, g, st));
+    BM_RETURN_IF(gemm(GEMM_TN, dt, m.E, d, T, ws.dlogits, m.E, ws.h, d, grads->w_router, d, none, ws.gemm_ws,
+                      ws.gemm_ws_bytes, st));
+  } else {
   // input gradient first: the activation backward then also rewrites the activation
   // output that the weight-gradient GEMM of the down projection reads
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
@@ -361,7 +472,6 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
                     ws.gemm_ws_bytes, st));
   // bias gradients of the down and output projections are column sums of the two
   // gradients the norm backward below touches anyway (not so when a gate sits between)
-  const bool fused_sums = c.linear_bias && !m.ada;
   if (c.linear_bias && !fused_sums)
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dm, d, T, d, (float*)grads->b_down, ws.colsum_ws, st)); }
 
@@ -375,6 +485,8 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
                                ws.norm_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_TN, dt, m.UP, d, T, ws.dup, m.UP, ws.h, d, grads->w_up, d, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
+
+  }
 
   // ---- x1 = x + [g1 *] attn,  attn = o W_o^T + b_o
   const void* dattn = ws.dx1;

@@ -133,6 +133,57 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
                int ldb, void* C, int ldc, const GemmEpilogue& epi, void* scratch,
                size_t scratch_bytes, hipStream_t st);
 
+// Grouped GEMM for the mixture-of-experts FFN: the rows of the activation matrices are
+// sorted by expert and every expert's segment is padded to MOE_PAD rows.
+//   NT / NN: row block t (MOE_PAD rows) of A and C belongs to group tile_group[t] (-1: no
+//            group, the block is skipped); the B matrix of group g starts at B + g*b_stride.
+//   TN:      group g contracts over rows [group_rows[g], group_rows[g+1]) of A and B and
+//            accumulates into the fp32 matrix at C + g*c_stride.
+// M (NT/NN) resp. K (TN) is the padded row capacity, a multiple of MOE_PAD.
+constexpr int MOE_PAD = 128;
+struct GemmGroups {
+  const int32_t* tile_group = nullptr;   // dev [rows / MOE_PAD]     (NT, NN)
+  const int32_t* group_rows = nullptr;   // dev [n_groups + 1]       (TN)
+  int n_groups = 0;
+  long b_stride = 0;                     // elements between the B matrices of two groups (NT, NN)
+  long c_stride = 0;                     // elements between the C matrices of two groups (TN)
+  long routed_rows = 0;                  // rows that carry tokens (profiling: algorithmic flops)
+};
+bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
+                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st);
+bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc);
+bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int lda, const void* B,
+                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st);
+bm_status gemm_generic_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
+                               const void* B, int ldb, void* C, int ldc, const GemmGroups& g,
+                               hipStream_t st);
+
+// ---------------------------------------------------------------- mixture of experts
+// Device tables of one routed batch (all caller memory, see moe.hip for the layout).
+struct MoeTables {
+  int cap = 0;                 // padded row capacity, moe_row_capacity(T, E, k)
+  float* probs = nullptr;      // [T, E] router probabilities
+  int32_t* idx = nullptr;      // [T, k] chosen experts, by descending probability
+  float* gate = nullptr;       // [T, k] normalised gates
+  int32_t* slot = nullptr;     // [T, k] row of each choice in the expert-sorted layout
+  int32_t* row_token = nullptr;   // [cap] token of a row, -1 for padding
+  float* row_gate = nullptr;      // [cap] gate of a row
+  int32_t* tile_group = nullptr;  // [cap / MOE_PAD] expert of a row block, -1 past the end
+  int32_t* expert_rows = nullptr; // [E + 1] padded segment offsets
+};
+int moe_row_capacity(int T, int E, int k);
+size_t moe_layout_scratch_bytes(int T, int E);
+bm_status moe_check(int E, int k, int d, int dtype);
+bm_status moe_route(const float* logits, int T, int E, int k, float* probs, int32_t* idx, float* gate,
+                    hipStream_t st);
+bm_status moe_layout(const MoeTables& m, int T, int E, int k, void* scratch, hipStream_t st);
+bm_status moe_gather(int dtype, const void* src, const MoeTables& m, int use_gate, void* dst, int d, int T,
+                     hipStream_t st);
+bm_status moe_combine(int dtype, const void* rows, const MoeTables& m, int use_gate, const void* res,
+                      void* out, int T, int k, int d, hipStream_t st);
+bm_status moe_router_backward(int dtype, const void* dm, const void* y_rows, const MoeTables& m,
+                              void* dlogits, int T, int E, int k, int d, hipStream_t st);
+
 // generic (any shape, fp32 FMA) and MFMA (bf16) back ends
 size_t gemm_generic_scratch_bytes(int M, int N, int K);
 bm_status gemm_generic(int layout, int dtype, int M, int N, int K, const void* A, int lda,

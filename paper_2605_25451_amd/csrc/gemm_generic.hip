@@ -23,11 +23,23 @@ template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     int M, int N, int K, const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
     void* __restrict__ Cv, int ldc, const T* __restrict__ bias, const T* __restrict__ residual,
-    int out_fp32, int k_per_split, float* __restrict__ partial) {
+    int out_fp32, int k_per_split, float* __restrict__ partial, GemmGroups grp) {
   __shared__ float As[GK][GT + 4];
   __shared__ float Bs[GK][GT + 4];
   const int tid = threadIdx.x;
   const int m0 = blockIdx.y * GT, n0 = blockIdx.x * GT;
+  int kbeg = blockIdx.z * k_per_split;
+  int kfin = min(K, kbeg + k_per_split);
+  if (grp.group_rows) {              // grouped weight gradient: blockIdx.z is the group
+    kbeg = min(grp.group_rows[blockIdx.z], K);
+    kfin = min(grp.group_rows[blockIdx.z + 1], K);
+    if (kbeg >= kfin) return;
+    Cv = (float*)Cv + (long)blockIdx.z * grp.c_stride;
+  } else if (grp.tile_group) {       // grouped forward / input gradient: B of this row block's group
+    const int g = grp.tile_group[m0 / MOE_PAD];
+    if (g < 0) return;
+    B += (long)g * grp.b_stride;
+  }
   const int ty = tid >> 4, tx = tid & 15;
   float acc[4][4];
 #pragma unroll
@@ -35,8 +47,6 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-  const int kbeg = blockIdx.z * k_per_split;
-  const int kfin = min(K, kbeg + k_per_split);
   for (int k0 = kbeg; k0 < kfin; k0 += GK) {
     // A slice -> As[k][m]
     if (LAYOUT == GEMM_TN) {
@@ -150,7 +160,7 @@ bm_status launch(int layout, int M, int N, int K, const void* A, int lda, const 
 #define BM_L(LAY)                                                                               \
   hipLaunchKernelGGL((gemm_generic_kernel<T, LAY>), grid, block, 0, st, M, N, K, (const T*)A,   \
                      lda, (const T*)B, ldb, C, ldc, (const T*)epi.bias, (const T*)epi.residual, \
-                     epi.out_fp32, per, partial)
+                     epi.out_fp32, per, partial, GemmGroups{})
   if (layout == GEMM_NT) BM_L(GEMM_NT);
   else if (layout == GEMM_NN) BM_L(GEMM_NN);
   else BM_L(GEMM_TN);
@@ -169,7 +179,33 @@ bm_status launch(int layout, int M, int N, int K, const void* A, int lda, const 
   return BM_OK;
 }
 
+template <typename T>
+bm_status launch_grouped(int layout, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+                         void* C, int ldc, const GemmGroups& g, hipStream_t st) {
+  dim3 grid(cdiv(N, GT), cdiv(M, GT), layout == GEMM_TN ? g.n_groups : 1), block(256);
+#define BM_L(LAY)                                                                               \
+  hipLaunchKernelGGL((gemm_generic_kernel<T, LAY>), grid, block, 0, st, M, N, K, (const T*)A,   \
+                     lda, (const T*)B, ldb, C, ldc, (const T*)nullptr, (const T*)nullptr, 0, K, \
+                     (float*)nullptr, g)
+  if (layout == GEMM_NT) BM_L(GEMM_NT);
+  else if (layout == GEMM_NN) BM_L(GEMM_NN);
+  else BM_L(GEMM_TN);
+#undef BM_L
+  BM_CHECK_LAUNCH("gemm_generic_grouped");
+  return BM_OK;
+}
+
 }  // namespace
+
+bm_status gemm_generic_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
+                               const void* B, int ldb, void* C, int ldc, const GemmGroups& g,
+                               hipStream_t st) {
+  if (M == 0 || N == 0) return BM_OK;
+  GemmGroups gg = g;
+  if (layout == GEMM_TN) gg.tile_group = nullptr; else gg.group_rows = nullptr;
+  if (dtype == BM_DTYPE_BF16) return launch_grouped<bf16_t>(layout, M, N, K, A, lda, B, ldb, C, ldc, gg, st);
+  return launch_grouped<float>(layout, M, N, K, A, lda, B, ldb, C, ldc, gg, st);
+}
 
 size_t gemm_generic_scratch_bytes(int M, int N, int K) {
   const int s = generic_splits(M, N, K);

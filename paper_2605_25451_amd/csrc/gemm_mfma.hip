@@ -41,6 +41,11 @@ struct GemmParams {
   int tiles_m, tiles_n, splits, k_per_split;
   int out_fp32;
   int xcd_split;                // each k split owns 8/splits XCDs (splits in {2,4,8})
+  // grouped problems (see GemmGroups); all null / zero otherwise
+  const int32_t* tile_group;
+  const int32_t* group_rows;
+  long b_group_stride, c_group_stride;
+  int grid_groups;              // host: workgroups = tiles * splits * grid_groups (>= 1)
 };
 
 // ---- LDS layouts ---------------------------------------------------------
@@ -208,8 +213,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   if (p.xcd_split) split_tile_of_block(blockIdx.x, tiles, p.splits, p.tiles_m, p.tiles_n, &split, &tm, &tn);
   else tile_of_block(blockIdx.x % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
-  const int kbeg = split * p.k_per_split;
-  const int kend = min(p.K, kbeg + p.k_per_split);
+  int kbeg = split * p.k_per_split;
+  int kend = min(p.K, kbeg + p.k_per_split);
+  const bf16_t* Bmat = p.B;
+  long c_off = 0;
+  if (p.group_rows) {
+    // grouped weight gradient: `split` is the group; its rows are the k range (all
+    // wavefronts take the same exit: the values are workgroup-uniform)
+    kbeg = min(p.group_rows[split], p.K);
+    kend = min(p.group_rows[split + 1], p.K);
+    if (kbeg >= kend) return;
+    c_off = (long)split * p.c_group_stride;
+    split = 0;
+  } else if (p.tile_group) {
+    const int g = p.tile_group[m0 / MOE_PAD];
+    if (g < 0) return;
+    Bmat += (long)g * p.b_group_stride;
+  }
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -230,7 +250,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   sb.init(p.ldb, p.N - n0, tid);
   // slice base pointers (wave-uniform): first row of the tile at k = kbeg
   const bf16_t* a_base = A_TR ? p.A + (size_t)kbeg * p.lda + m0 : p.A + (size_t)m0 * p.lda + kbeg;
-  const bf16_t* b_base = B_TR ? p.B + (size_t)kbeg * p.ldb + n0 : p.B + (size_t)n0 * p.ldb + kbeg;
+  const bf16_t* b_base = B_TR ? Bmat + (size_t)kbeg * p.ldb + n0 : Bmat + (size_t)n0 * p.ldb + kbeg;
   const size_t a_step = A_TR ? (size_t)BK * p.lda : (size_t)BK;
   const size_t b_step = B_TR ? (size_t)BK * p.ldb : (size_t)BK;
   sa.load(a_base, p.lda, kend - kbeg, tid);
@@ -358,7 +378,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
           if (ACCUM_F32) {
             // weight gradient: fp32, added to C (or parked as this split's partial tile)
             float* c = p.splits > 1 ? p.partial + ((size_t)split * p.M + gm) * p.N + gn
-                                    : (float*)p.C + idx;
+                                    : (float*)p.C + c_off + idx;
             f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
             if (p.splits == 1) {
               c0 = *reinterpret_cast<const f32x4*>(c);
@@ -458,7 +478,7 @@ bm_status launch_k(const GemmParams& p, hipStream_t st) {
     BM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_done = true;
   }
-  dim3 grid(p.tiles_m * p.tiles_n * p.splits), block(WM * WN * 64);
+  dim3 grid(p.tiles_m * p.tiles_n * p.splits * p.grid_groups), block(WM * WN * 64);
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);
   BM_CHECK_LAUNCH("gemm_mfma");
   return BM_OK;
@@ -500,6 +520,8 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
   p.out_fp32 = epi.out_fp32;
+  p.tile_group = nullptr; p.group_rows = nullptr; p.b_group_stride = 0; p.c_group_stride = 0;
+  p.grid_groups = 1;
   {
     p.xcd_split = xcd_split_possible(pl.tiles_m * pl.tiles_n, pl.splits) ? 1 : 0;
   }
@@ -524,6 +546,36 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
     BM_CHECK_LAUNCH("splitk_reduce");
   }
   return BM_OK;
+}
+
+bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc) {
+  if (dtype != BM_DTYPE_BF16) return false;
+  if (N < 64 || lda % 8 || ldb % 8) return false;
+  if (layout == GEMM_TN) return M >= 64 && M % 8 == 0 && N % 8 == 0 && ldc % 4 == 0 && K % MOE_PAD == 0;
+  return K >= 64 && K % 8 == 0 && N % 8 == 0 && ldc % 8 == 0 && M % MOE_PAD == 0;
+}
+
+// 128x128 tiles: a row tile is one MOE_PAD block, so it never straddles two groups.
+bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int lda, const void* B,
+                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st) {
+  static_assert(MOE_PAD == 128, "the grouped path uses 128-row tiles");
+  GemmParams p;
+  p.A = (const bf16_t*)A; p.B = (const bf16_t*)B; p.C = C;
+  p.bias = nullptr; p.residual = nullptr; p.partial = nullptr;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.tiles_m = cdiv(M, 128); p.tiles_n = cdiv(N, 128); p.splits = 1; p.k_per_split = cdiv(K, BK) * BK;
+  p.out_fp32 = 0; p.xcd_split = 0;
+  p.tile_group = layout == GEMM_TN ? nullptr : g.tile_group;
+  p.group_rows = layout == GEMM_TN ? g.group_rows : nullptr;
+  p.b_group_stride = g.b_stride; p.c_group_stride = g.c_stride;
+  p.grid_groups = layout == GEMM_TN ? g.n_groups : 1;
+  if ((layout == GEMM_TN ? p.group_rows == nullptr || g.n_groups < 1 : p.tile_group == nullptr)) {
+    set_error("grouped gemm: group tables are NULL");
+    return BM_ERR_INVALID_ARG;
+  }
+  if (layout == GEMM_NT) return launch<128, 128, 2, 2, false, false, false>(p, st);
+  if (layout == GEMM_NN) return launch<128, 128, 2, 2, false, true, false>(p, st);
+  return launch_k<128, 128, 2, 2, true, true, true, false>(p, st);   // k ranges are whole slices
 }
 
 }  // namespace bm
