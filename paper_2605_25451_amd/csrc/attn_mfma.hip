@@ -335,13 +335,20 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dk,
-    bf16_t* __restrict__ dv, int ldd, int Ttot, int Hkv, int group, float scale, float scale_log2) {
+    bf16_t* __restrict__ dv, int ldd, int Ttot, int Hkv, int group, float scale, float scale_log2,
+    int gsplit, float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
   __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
   int seq, kt, nkt, tile_id, hk;
-  tile_and_head(Hkv, &tile_id, &hk);
+  // with gsplit > 1 a workgroup takes group/gsplit of the q heads that share this kv head
+  // and leaves an fp32 partial; the (kv head, q-head part) pair plays the head's role
+  int hk_gs;
+  tile_and_head(Hkv * gsplit, &tile_id, &hk_gs);
+  hk = hk_gs / gsplit;
+  const int gs = hk_gs % gsplit;
+  const int gpart = group / gsplit;
   if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
   kt = nkt - 1 - kt;                                   // early key tiles see the most queries
   const int lo = cu[seq], L = cu[seq + 1] - lo;
@@ -368,11 +375,11 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 
   const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
   const int nqt = (L - qstart + BK_Q - 1) / BK_Q;
-  const int iters = nqt * group;
+  const int iters = nqt * gpart;
   TileStage<BK_Q, DH, 256> sq, sd;
   float st_l = 0.f, st_d = 0.f;
   auto fetch = [&](int it) {
-    const int hq = hk * group + it / nqt;
+    const int hq = hk * group + gs * gpart + it / nqt;
     const int q0 = qstart + (it % nqt) * BK_Q;
     sq.load(q + (size_t)lo * ld + hq * DH, ld, q0, L, tid);
     sd.load(d_o + (size_t)lo * ldo + hq * DH, ldo, q0, L, tid);
@@ -436,7 +443,21 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
       }
     }
   }
-  if (kpos < L) {
+  if (kpos < L && gsplit > 1) {
+    const size_t plane = (size_t)Ttot * Hkv * DH;
+    float* pk = part + ((size_t)gs * 2 + 0) * plane + (size_t)(lo + kpos) * (Hkv * DH) + hk * DH;
+    float* pv = part + ((size_t)gs * 2 + 1) * plane + (size_t)(lo + kpos) * (Hkv * DH) + hk * DH;
+#pragma unroll
+    for (int j = 0; j < HeadDim<DH>::NB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH) {
+          *reinterpret_cast<f32x4*>(pk + j * 32 + g * 8 + half * 4) =
+              f32x4{dkacc[j][g * 4] * scale, dkacc[j][g * 4 + 1] * scale, dkacc[j][g * 4 + 2] * scale, dkacc[j][g * 4 + 3] * scale};
+          *reinterpret_cast<f32x4*>(pv + j * 32 + g * 8 + half * 4) =
+              f32x4{dvacc[j][g * 4], dvacc[j][g * 4 + 1], dvacc[j][g * 4 + 2], dvacc[j][g * 4 + 3]};
+        }
+  } else if (kpos < L) {
     bf16_t* pk = dk + (size_t)(lo + kpos) * ldd + hk * DH;
     bf16_t* pv = dv + (size_t)(lo + kpos) * ldd + hk * DH;
 #pragma unroll
@@ -558,6 +579,36 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
   }
 }
 
+// dk, dv = sum over the q-head parts of the fp32 partials, in part order
+__global__ void fa_dkdv_reduce_kernel(const float* __restrict__ part, int gsplit, int Ttot, int W /* Hkv*dh */,
+                                      bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int ldd) {
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const long plane = (long)Ttot * W;
+  if (i >= plane) return;
+  const int t = (int)(i / W), c = (int)(i % W);
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < gsplit; ++g) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(part + ((size_t)g * 2 + which) * plane + i);
+      s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+    }
+    bf16x4 w = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
+    *reinterpret_cast<bf16x4*>((which == 0 ? dk : dv) + (size_t)t * ldd + c) = w;
+  }
+}
+
+// q-head parts per kv head in the dK/dV kernel: more workgroups when few key tiles x kv
+// heads would leave most CUs idle (grouped-query attention over a short pack)
+int dkdv_group_split(int tiles, int Hkv, int group) {
+  const long wgs = (long)tiles * Hkv;
+  int want = (int)((1024 + wgs - 1) / wgs);
+  int gsplit = 1;
+  for (int s = 1; s <= group; ++s)
+    if (group % s == 0 && s <= want) gsplit = s;
+  return gsplit;
+}
+
 template <int DH>
 bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const float* lse, void* dq,
                      void* dk, void* dv, int ldd, float* delta, hipStream_t st) {
@@ -567,17 +618,25 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const long n = (long)a.T * a.Hq;
   hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
                      (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
-  dim3 gkv(count_tiles(a.cu_host, a.S, BK_KEYS) * a.Hkv), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
+  const int ktiles = count_tiles(a.cu_host, a.S, BK_KEYS);
+  const int gsplit = dkdv_group_split(ktiles, a.Hkv, a.Hq / a.Hkv);
+  float* part = delta + align_up((size_t)a.Hq * a.T, 64);      // after the delta plane
+  dim3 gkv(ktiles * a.Hkv * gsplit), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
 #define BM_L(C)                                                                                  \
   hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,      \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
                      lse, delta, a.cu_dev, a.S, (bf16_t*)dk, (bf16_t*)dv, ldd, a.T, a.Hkv,       \
-                     a.Hq / a.Hkv, scale, sl2);                                                  \
+                     a.Hq / a.Hkv, scale, sl2, gsplit, part);                                    \
   hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,        \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
                      lse, delta, a.cu_dev, a.S, (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2)
   if (a.causal) { BM_L(true); } else { BM_L(false); }
 #undef BM_L
+  if (gsplit > 1) {
+    const long n4 = (long)a.T * a.Hkv * a.dh / 4;
+    hipLaunchKernelGGL(fa_dkdv_reduce_kernel, dim3(cdiv(n4, 256)), dim3(256), 0, st, part, gsplit, a.T,
+                       a.Hkv * a.dh, (bf16_t*)dk, (bf16_t*)dv, ldd);
+  }
   BM_CHECK_LAUNCH("fa_bwd");
   return BM_OK;
 }
@@ -594,8 +653,12 @@ bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStre
   return fwd_launch<64>(a, o, lse, st);
 }
 
-size_t attention_backward_mfma_scratch_bytes(int Hq, int, int, int T) {
-  return align_up((size_t)Hq * T * sizeof(float), 256);
+size_t attention_backward_mfma_scratch_bytes(int Hq, int Hkv, int dh, int T) {
+  // the delta plane, then room for the fp32 dK/dV partials of the largest q-head split
+  const size_t delta = align_up((size_t)Hq * T, 64) * sizeof(float);
+  const int group = Hq / Hkv;
+  const size_t part = group > 1 ? (size_t)group * 2 * T * Hkv * dh * sizeof(float) : 0;
+  return align_up(delta + part, 256);
 }
 
 bm_status attention_backward_mfma(const AttnArgs& a, const void* o, const void* d_o, const float* lse,

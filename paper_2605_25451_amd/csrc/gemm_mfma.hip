@@ -575,7 +575,13 @@ bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int 
   }
   if (layout == GEMM_NT) return launch<128, 128, 2, 2, false, false, false>(p, st);
   if (layout == GEMM_NN) return launch<128, 128, 2, 2, false, true, false>(p, st);
-  return launch_k<128, 128, 2, 2, true, true, true, false>(p, st);   // k ranges are whole slices
+  // weight gradient: rows are the contraction index, so the output tile is free; a group's
+  // k range is short (a few slices), which makes the per-tile fixed cost count: large tiles
+  if (M >= 256 && N >= 256) {
+    p.tiles_m = cdiv(M, 256); p.tiles_n = cdiv(N, 256);
+    return launch_k<256, 256, 2, 2, true, true, true, false>(p, st);   // k ranges are whole slices
+  }
+  return launch_k<128, 128, 2, 2, true, true, true, false>(p, st);
 }
 
 }  // namespace bm
