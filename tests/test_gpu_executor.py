@@ -153,3 +153,18 @@ def test_timed_execution_gives_the_same_results_and_sane_figures():
         for g0, g1 in zip(grads0[grp], grads1[grp]):
             for k in g0:
                 assert np.array_equal(g0[k], g1[k]), (grp, k)
+
+
+def test_stage_with_mixture_of_experts_llm_blocks_fp32():
+    """The paper's backbone is a mixture-of-experts model (Sec. 4.1): the same executor over LLM
+    blocks with routed FFNs.  fp32 check path (router margins far above rounding)."""
+    from paper_2605_25451_amd import binding as bm
+    f32 = synth.DTYPE_FP32
+    enc = synth.scaled(synth.vit_tiny(f32), hidden=64, n_q_heads=4, n_kv_heads=4, head_dim=16, mlp_hidden=96)
+    llm = synth.scaled(synth.decoder_moe(f32), hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32,
+                       mlp_hidden=64, n_experts=6, top_k=2, router_std=0.2)
+    g = synth.scaled(synth.dit_block(f32), hidden=64, n_q_heads=4, n_kv_heads=4, head_dim=16, mlp_hidden=96)
+    stage = synth.make_stage(enc, llm, g, 2, 2, 2, 4, 1, 256, 90, image_range=(16, 48), text_range=(8, 32),
+                             tokens_per_image=8, proj_std=0.1)
+    loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
+    compare((loss, grads), eo.run_stage(stage), 1e-4)
