@@ -22,6 +22,9 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+PAPER_CONTEXT = ("the paper reports 1.08x-1.9x end-to-end training speedups of its nested schedule over "
+                 "prior systems on 128 H800 GPUs (Sec. 4.2) and no per-block time, TFLOP/s or bandwidth: "
+                 "context only, not comparable with a single-GPU block measurement")
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
@@ -356,6 +359,7 @@ def main():
         "roofline": roofline,
         "breakdown": breakdown,
         "measured_peaks": measured_peaks(),
+        "paper_context": PAPER_CONTEXT,
     }
     if args.copy_calibration:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
