@@ -241,3 +241,164 @@ def replay(order: str, P: int, V: int, M: int, W: int, has_generator: bool,
     return {"makespan": makespan, "busy": busy, "peak": peak, "peak_enc": peak_enc,
             "peak_gen": peak_gen, "peak_llm": peak_llm,
             "bubble": 1.0 - sum(busy) / (P * makespan) if makespan > 0 else 0.0}
+
+
+# ---------------------------------------------------------------------------
+# communication operators and the deadlock check (Sec. 3.1 "Communication
+# operator", Sec. 3.2; the executor-interface figure names insert_comm_ops and
+# deadlock_check without defining them)
+#
+# Reading.  Every cross-rank data dependency of a compute op becomes a RECV
+# placed right before it and every tensor another rank consumes a SEND placed
+# right after it.  A message is identified by (what, microbatch, edge):
+#   ACT   forward activation into pipeline position `edge`      (edge-1 -> edge)
+#   GRAD  gradient w.r.t. the input of pipeline position `edge` (edge -> edge-1)
+#   FEAT  encoder features of a microbatch to the entry rank 0  (owner m mod P -> 0)
+#   FGRAD input-embedding gradient back to the encoder owner    (0 -> m mod P)
+#   OUT   LLM output of a microbatch to its generator owner     (P-1 -> m mod P)
+#   OGRAD generator-input gradient back to the exit rank        (m mod P -> P-1)
+# Edges whose two ends sit on one rank need no message.  Sends are posted
+# asynchronously and never block; a RECV blocks until its SEND was posted
+# (the executor waits on receive handles before consuming, Sec. 3.2).
+# ---------------------------------------------------------------------------
+
+def comm_rank_schedule(order: str, P: int, V: int, M: int, W: int, has_generator: bool,
+                       rank: int) -> List[tuple]:
+    """Rank program with communication operators.  Compute ops stay (kind, index, chunk);
+    comm ops are ("SEND" | "RECV", peer, what, microbatch, edge)."""
+    r = rank
+    last = P * V - 1
+    fused = order == MEMORY_EFFICIENT
+    out: List[tuple] = []
+    for op in build_rank_schedule(order, P, V, M, W, has_generator, r):
+        kind, i, c = op
+        pre: List[tuple] = []
+        post: List[tuple] = []
+        if kind in "FB":
+            pos = c * P + r
+            if kind == "F":
+                if pos > 0 and (pos - 1) % P != r:
+                    pre.append(("RECV", (pos - 1) % P, "ACT", i, pos))
+                if pos == 0 and not fused and i % P != r:
+                    pre.append(("RECV", i % P, "FEAT", i, 0))
+                if pos < last and (pos + 1) % P != r:
+                    post.append(("SEND", (pos + 1) % P, "ACT", i, pos + 1))
+                if pos == last and has_generator and not fused and i % P != r:
+                    post.append(("SEND", i % P, "OUT", i, last))
+            else:
+                if pos < last and (pos + 1) % P != r:
+                    pre.append(("RECV", (pos + 1) % P, "GRAD", i, pos + 1))
+                if pos == last and has_generator and not fused and i % P != r:
+                    pre.append(("RECV", i % P, "OGRAD", i, last))
+                if pos > 0 and (pos - 1) % P != r:
+                    post.append(("SEND", (pos - 1) % P, "GRAD", i, pos))
+                if pos == 0 and not fused and i % P != r:
+                    post.append(("SEND", i % P, "FGRAD", i, 0))
+        else:
+            m = i * P + r
+            if kind == "E" and r != 0:
+                post.append(("SEND", 0, "FEAT", m, 0))
+            if kind == "e" and r != 0:
+                pre.append(("RECV", 0, "FGRAD", m, 0))
+            if kind == "G" and r != P - 1:
+                pre.append(("RECV", P - 1, "OUT", m, last))
+            if kind == "H" and r != P - 1:
+                post.append(("SEND", P - 1, "OGRAD", m, last))
+        out += pre + [op] + post
+    return out
+
+
+def check_comm(order: str, P: int, V: int, M: int, W: int, has_generator: bool) -> Dict[str, object]:
+    """Runs the P rank programs with eager sends and blocking receives.
+
+    A compute op also waits for the tensors its own rank produces for it; an op placed
+    before its local producer therefore shows up as a deadlock.
+    Returns {"deadlock": bool, "messages": total sends, "unmatched": sends without a
+    receive plus receives without a send, "fifo": whether, for every ordered pair of
+    ranks, messages are received in the order they were sent (what a transport that
+    matches by order alone needs), "max_inflight": largest number of posted but not
+    yet received messages on one ordered pair}."""
+    progs = [comm_rank_schedule(order, P, V, M, W, has_generator, r) for r in range(P)]
+    sends = {}
+    recvs = {}
+    for r, prog in enumerate(progs):
+        for op in prog:
+            if op[0] == "SEND":
+                sends[(r, op[1]) + op[2:]] = sends.get((r, op[1]) + op[2:], 0) + 1
+            elif op[0] == "RECV":
+                recvs[(op[1], r) + op[2:]] = recvs.get((op[1], r) + op[2:], 0) + 1
+    unmatched = sum(abs(sends.get(k, 0) - recvs.get(k, 0)) for k in set(sends) | set(recvs))
+    unmatched += sum(v - 1 for v in sends.values() if v > 1)
+
+    last = P * V - 1
+    fused = order == MEMORY_EFFICIENT
+
+    def local_inputs(r: int, op: tuple) -> List[tuple]:
+        """Tensors a compute op consumes that its own rank produces (no message exists for
+        them, so the producer must simply have run already)."""
+        kind, i, c = op
+        need: List[tuple] = []
+        if kind == "F":
+            p_ = c * P + r
+            if p_ > 0 and (p_ - 1) % P == r:
+                need.append(("F", i, c - 1))
+            if p_ == 0 and not fused and i % P == r:
+                need.append(("E", i // P, 0))
+        elif kind == "B":
+            p_ = c * P + r
+            need.append(("F", i, c))
+            if p_ < last and (p_ + 1) % P == r:
+                need.append(("B", i, c + 1))
+            if p_ == last and has_generator and not fused and i % P == r:
+                need.append(("H", i // P, 0))
+        elif kind == "e":
+            need.append(("E", i, 0))
+            if r == 0:
+                need.append(("B", i * P, 0))
+        elif kind == "G" and r == P - 1:
+            need.append(("F", i * P + r, V - 1))
+        elif kind == "H":
+            need.append(("G", i, 0))
+        return need
+
+    posted = set()
+    ran = [set() for _ in range(P)]
+    pos = [0] * P
+    inflight: Dict[Tuple[int, int], int] = {}
+    max_inflight = 0
+    sent_order: Dict[Tuple[int, int], list] = {}
+    recv_order: Dict[Tuple[int, int], list] = {}
+    remaining = sum(len(p) for p in progs)
+    deadlock = False
+    while remaining:
+        progressed = False
+        for r in range(P):
+            while pos[r] < len(progs[r]):
+                op = progs[r][pos[r]]
+                if op[0] == "SEND":
+                    key = (r, op[1]) + op[2:]
+                    posted.add(key)
+                    pair = (r, op[1])
+                    inflight[pair] = inflight.get(pair, 0) + 1
+                    max_inflight = max(max_inflight, inflight[pair])
+                    sent_order.setdefault(pair, []).append(op[2:])
+                elif op[0] == "RECV":
+                    key = (op[1], r) + op[2:]
+                    if key not in posted:
+                        break
+                    pair = (op[1], r)
+                    inflight[pair] -= 1
+                    recv_order.setdefault(pair, []).append(op[2:])
+                else:
+                    if any(n not in ran[r] for n in local_inputs(r, op)):
+                        break                      # consumes a tensor its own rank has not produced yet
+                    ran[r].add(op)
+                pos[r] += 1
+                remaining -= 1
+                progressed = True
+        if not progressed:
+            deadlock = True
+            break
+    fifo = (not deadlock) and all(sent_order.get(k, []) == recv_order.get(k, []) for k in set(sent_order) | set(recv_order))
+    return {"deadlock": deadlock, "messages": sum(sends.values()), "unmatched": unmatched, "fifo": fifo,
+            "max_inflight": max_inflight}

@@ -190,3 +190,75 @@ def test_transfer_latency_and_heterogeneous_stage_times():
     # rank0: F0 [0,1] F1 [1,2]; rank1: F0 [1.5,4.5] B0 [4.5,9.5] F1 [9.5,12.5] B1 [12.5,17.5];
     # rank0: B0 [10,12] B1 [18,20]
     assert r["makespan"] == 20.0 and r["busy"] == [6.0, 16.0]
+
+
+# ------------------------------------------------------------------ communication operators
+
+def fmt_comm(op):
+    if op[0] == "SEND":
+        return f"S:{op[2]}{op[3]}@{op[4]}>{op[1]}"
+    if op[0] == "RECV":
+        return f"R:{op[2]}{op[3]}@{op[4]}<{op[1]}"
+    return fmt(op)
+
+
+def test_comm_hand_expansion():
+    n = 0
+    for line in gold_lines("comm"):
+        m = re.match(r"comm (\w+) P=(\d+) V=(\d+) M=(\d+) W=(\d+) gen=(\d) rank=(\d+): (.*)", line)
+        order, P, V, M, W, gen, rank = m.group(1), *map(int, m.groups()[1:7])
+        got = " ".join(fmt_comm(o) for o in po.comm_rank_schedule(order, P, V, M, W, bool(gen), rank))
+        assert got == m.group(8), line
+        n += 1
+    assert n == 2
+
+
+@pytest.mark.parametrize("P,V,M", GRID)
+@pytest.mark.parametrize("gen", [False, True])
+def test_comm_ops_wrap_the_compute_program_and_match_up(P, V, M, gen):
+    for order in (po.NESTED, po.COMPUTE_EFFICIENT, po.MEMORY_EFFICIENT):
+        for r in range(P):
+            prog = po.comm_rank_schedule(order, P, V, M, 3, gen, r)
+            assert [op for op in prog if op[0] not in ("SEND", "RECV")] == \
+                po.build_rank_schedule(order, P, V, M, 3, gen, r)
+            assert all(op[1] != r for op in prog if op[0] in ("SEND", "RECV"))      # never to itself
+        res = po.check_comm(order, P, V, M, 3, gen)
+        assert res["unmatched"] == 0
+        # one activation and one gradient per microbatch and pipeline edge, plus the
+        # encoder and generator handoffs of the microbatches another rank owns
+        edges = (P * V - 1) if P > 1 else 0
+        want = 2 * M * edges
+        if order != po.MEMORY_EFFICIENT and P > 1:
+            want += 2 * (M - M // P) * (2 if gen else 1)
+        assert res["messages"] == want
+        needs_w3 = order == po.NESTED and V >= 2 and P >= 3 and M // P > 3
+        assert res["deadlock"] is False or not needs_w3
+
+
+@pytest.mark.parametrize("P,V,M,W,expect", [(4, 2, 16, 2, True), (4, 2, 16, 3, False), (4, 1, 16, 1, True),
+                                            (4, 1, 16, 2, False), (3, 3, 9, 2, True), (3, 3, 9, 3, False),
+                                            (8, 2, 32, 3, False), (2, 2, 8, 2, False)])
+def test_deadlock_check_agrees_with_the_replay(P, V, M, W, expect):
+    for gen in (False, True):
+        assert po.check_comm(po.NESTED, P, V, M, W, gen)["deadlock"] is expect
+        z = [0.0] * M
+        try:
+            po.replay(po.NESTED, P, V, M, W, gen, [1.0] * (P * V), [1.0] * (P * V), z, z, z, z)
+            stuck = False
+        except RuntimeError:
+            stuck = True
+        assert stuck is expect
+
+
+def test_llm_only_traffic_is_in_order_per_pair_and_nested_traffic_is_not():
+    # a transport that matches messages by order alone is enough for the plain pipeline; the
+    # nested programs interleave handoff messages differently on the two ends of a pair, which
+    # is why every operator carries (what, microbatch, chunk) metadata (Sec. 3.1)
+    for P, V, M in [(2, 1, 8), (4, 1, 16), (4, 2, 16), (8, 2, 32), (3, 3, 9)]:
+        assert po.check_comm(po.MEMORY_EFFICIENT, P, V, M, 3, False)["fifo"] is True
+        assert po.check_comm(po.NESTED, P, V, M, 3, True)["fifo"] is False
+
+
+def test_a_program_that_runs_a_consumer_before_its_local_producer_is_reported():
+    # W = 1: rank 0 would forward a microbatch of unit 1 before its own encoder forward
+    assert po.check_comm(po.NESTED, 2, 1, 8, 1, False)["deadlock"] is True
