@@ -82,6 +82,50 @@ typedef struct {
  * no rank can advance (e.g. W too small for the LLM schedule).  Output arrays may be NULL. */
 bm_status bm_pipeline_replay(const bm_pipe_replay_config* cfg, bm_pipe_replay_result* res);
 
+/* ---- communication operators and the deadlock check (Sec. 3.1 "Communication operator",
+ *      Sec. 3.2; the executor-interface figure names insert_comm_ops and deadlock_check) ----
+ *
+ * Every cross-rank data dependency of a compute op becomes a receive placed right before it,
+ * every tensor another rank consumes a send placed right after it.  A message is identified
+ * by (what, microbatch, edge); edges whose two ends sit on one rank need no message. */
+enum { BM_OP_SEND = 6, BM_OP_RECV = 7 };
+enum {
+  BM_MSG_ACT = 0,    /* forward activation into pipeline position `edge`       (edge-1 -> edge)  */
+  BM_MSG_GRAD = 1,   /* gradient of the input of pipeline position `edge`      (edge -> edge-1)  */
+  BM_MSG_FEAT = 2,   /* encoder features of a microbatch to the entry rank     (m mod P -> 0)    */
+  BM_MSG_FGRAD = 3,  /* input-embedding gradient back to the encoder owner     (0 -> m mod P)    */
+  BM_MSG_OUT = 4,    /* LLM output of a microbatch to its generator owner      (P-1 -> m mod P)  */
+  BM_MSG_OGRAD = 5   /* generator-input gradient back to the exit rank         (m mod P -> P-1)  */
+};
+
+typedef struct {
+  int32_t op;      /* BM_OP_* (compute) or BM_OP_SEND / BM_OP_RECV                          */
+  int32_t index;   /* compute: microbatch or unit;  message: microbatch                     */
+  int32_t chunk;   /* compute: model chunk;         message: edge (a pipeline position)     */
+  int32_t peer;    /* message: the other rank; -1 for compute ops                           */
+  int32_t what;    /* message: BM_MSG_*;       -1 for compute ops                           */
+} bm_pipe_xop;
+
+/* Program of one rank with its communication operators: at most 3 ops per compute op. */
+bm_status bm_pipeline_comm_schedule(int32_t order, int32_t P, int32_t V, int32_t M, int32_t W,
+                                    int32_t has_generator, int32_t rank,
+                                    bm_pipe_xop* ops, int32_t* n_ops);
+
+typedef struct {
+  int32_t deadlock;      /* 1: some rank can never advance (also: a compute op placed before the
+                            op of its own rank that produces its input)                       */
+  int32_t unmatched;     /* sends without a receive + receives without a send + duplicates    */
+  int32_t fifo;          /* 1: on every ordered pair of ranks messages are received in the order
+                            they were sent (enough for a transport that matches by order)     */
+  int32_t max_inflight;  /* most messages posted but not yet received on one ordered pair     */
+  int64_t messages;      /* sends over all ranks                                              */
+} bm_pipe_comm_report;
+
+/* Runs the P programs with sends that never block and receives that block until their send
+ * was posted (the executor waits on receive handles before consuming, Sec. 3.2). */
+bm_status bm_pipeline_check_comm(int32_t order, int32_t P, int32_t V, int32_t M, int32_t W,
+                                 int32_t has_generator, bm_pipe_comm_report* report);
+
 #ifdef __cplusplus
 }
 #endif

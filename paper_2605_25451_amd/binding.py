@@ -73,6 +73,16 @@ class PipeOp(C.Structure):
     _fields_ = [("op", C.c_int32), ("index", C.c_int32), ("chunk", C.c_int32), ("column", C.c_int32)]
 
 
+class PipeXOp(C.Structure):
+    _fields_ = [("op", C.c_int32), ("index", C.c_int32), ("chunk", C.c_int32), ("peer", C.c_int32),
+                ("what", C.c_int32)]
+
+
+class PipeCommReport(C.Structure):
+    _fields_ = [("deadlock", C.c_int32), ("unmatched", C.c_int32), ("fifo", C.c_int32),
+                ("max_inflight", C.c_int32), ("messages", C.c_int64)]
+
+
 class PipeReplayConfig(C.Structure):
     _fields_ = [("order", C.c_int32), ("P", C.c_int32), ("V", C.c_int32), ("M", C.c_int32),
                 ("W", C.c_int32), ("has_generator", C.c_int32)] + \
@@ -149,7 +159,10 @@ def lib() -> C.CDLL:
         l.bm_pipeline_llm_schedule.argtypes = [i32] * 4 + [ppo, pi32]
         l.bm_pipeline_build_schedule.argtypes = [i32] * 7 + [ppo, pi32]
         l.bm_pipeline_replay.argtypes = [C.POINTER(PipeReplayConfig), C.POINTER(PipeReplayResult)]
-        for name in ("bm_pipeline_llm_schedule", "bm_pipeline_build_schedule", "bm_pipeline_replay"):
+        l.bm_pipeline_comm_schedule.argtypes = [i32] * 7 + [C.POINTER(PipeXOp), pi32]
+        l.bm_pipeline_check_comm.argtypes = [i32] * 6 + [C.POINTER(PipeCommReport)]
+        for name in ("bm_pipeline_llm_schedule", "bm_pipeline_build_schedule", "bm_pipeline_replay",
+                     "bm_pipeline_comm_schedule", "bm_pipeline_check_comm"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -319,6 +332,31 @@ def pipeline_llm_schedule(P, V, M, rank):
 def pipeline_build_schedule(order, P, V, M, W, has_generator, rank):
     """Program of one rank: list of (opcode, index, chunk, column)."""
     return _pipe_ops(lib().bm_pipeline_build_schedule, order, P, V, M, W, int(has_generator), rank)
+
+
+OP_SEND, OP_RECV = 6, 7
+MSG_NAMES = ("ACT", "GRAD", "FEAT", "FGRAD", "OUT", "OGRAD")
+
+
+def pipeline_comm_schedule(order, P, V, M, W, has_generator, rank):
+    """Program of one rank with communication operators: list of (opcode, index, chunk, peer, what);
+    peer and what are -1 for compute ops."""
+    fn = lib().bm_pipeline_comm_schedule
+    n = C.c_int32(0)
+    fn(order, P, V, M, W, int(has_generator), rank, None, C.byref(n))
+    if n.value <= 0:
+        _check(BM_ERR_INVALID_ARG)
+    buf = (PipeXOp * n.value)()
+    _check(fn(order, P, V, M, W, int(has_generator), rank, buf, C.byref(n)))
+    return [(o.op, o.index, o.chunk, o.peer, o.what) for o in buf[:n.value]]
+
+
+def pipeline_check_comm(order, P, V, M, W, has_generator):
+    """Deadlock / matching report of the P rank programs (see bm_pipeline_check_comm)."""
+    rep = PipeCommReport()
+    _check(lib().bm_pipeline_check_comm(order, P, V, M, W, int(has_generator), C.byref(rep)))
+    return {"deadlock": bool(rep.deadlock), "unmatched": rep.unmatched, "fifo": bool(rep.fifo),
+            "max_inflight": rep.max_inflight, "messages": rep.messages}
 
 
 def pipeline_replay(order, P, V, M, W, has_generator, llm_fwd, llm_bwd, enc_fwd, enc_bwd,

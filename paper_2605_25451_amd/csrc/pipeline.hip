@@ -112,6 +112,54 @@ struct Finish {
   double& at_unit(int rank, int kind, int u) { return unit[((size_t)rank * 4 + kind) * s.U() + u]; }
 };
 
+// ---- communication operators ----------------------------------------------------------------
+bm_pipe_xop compute_xop(const bm_pipe_op& op) { return {op.op, op.index, op.chunk, -1, -1}; }
+bm_pipe_xop message(int dir, int peer, int what, int mb, int edge) { return {dir, mb, edge, peer, what}; }
+
+void build_comm_program(const Shape& s, int order, int W, bool gen, int rank, std::vector<bm_pipe_xop>& out) {
+  std::vector<bm_pipe_op> prog;
+  build_program(s, order, W, gen, rank, prog);
+  out.clear();
+  const int P = s.P, r = rank, last = s.P * s.V - 1;
+  const bool fused = order == BM_ORDER_MEMORY_EFFICIENT;
+  for (const bm_pipe_op& op : prog) {
+    bm_pipe_xop pre[2], post[2];
+    int npre = 0, npost = 0;
+    const int i = op.index;
+    if (op.op == BM_OP_LLM_FWD || op.op == BM_OP_LLM_BWD) {
+      const int pos = op.chunk * P + r;
+      const int up = (pos + P - 1) % P, down = (pos + 1) % P;   // ranks of the neighbouring positions
+      if (op.op == BM_OP_LLM_FWD) {
+        if (pos > 0 && up != r) pre[npre++] = message(BM_OP_RECV, up, BM_MSG_ACT, i, pos);
+        if (pos == 0 && !fused && i % P != r) pre[npre++] = message(BM_OP_RECV, i % P, BM_MSG_FEAT, i, 0);
+        if (pos < last && down != r) post[npost++] = message(BM_OP_SEND, down, BM_MSG_ACT, i, pos + 1);
+        if (pos == last && gen && !fused && i % P != r) post[npost++] = message(BM_OP_SEND, i % P, BM_MSG_OUT, i, last);
+      } else {
+        if (pos < last && down != r) pre[npre++] = message(BM_OP_RECV, down, BM_MSG_GRAD, i, pos + 1);
+        if (pos == last && gen && !fused && i % P != r) pre[npre++] = message(BM_OP_RECV, i % P, BM_MSG_OGRAD, i, last);
+        if (pos > 0 && up != r) post[npost++] = message(BM_OP_SEND, up, BM_MSG_GRAD, i, pos);
+        if (pos == 0 && !fused && i % P != r) post[npost++] = message(BM_OP_SEND, i % P, BM_MSG_FGRAD, i, 0);
+      }
+    } else {
+      const int m = i * P + r;
+      if (op.op == BM_OP_ENC_FWD && r != 0) post[npost++] = message(BM_OP_SEND, 0, BM_MSG_FEAT, m, 0);
+      if (op.op == BM_OP_ENC_BWD && r != 0) pre[npre++] = message(BM_OP_RECV, 0, BM_MSG_FGRAD, m, 0);
+      if (op.op == BM_OP_GEN_FWD && r != P - 1) pre[npre++] = message(BM_OP_RECV, P - 1, BM_MSG_OUT, m, last);
+      if (op.op == BM_OP_GEN_BWD && r != P - 1) post[npost++] = message(BM_OP_SEND, P - 1, BM_MSG_OGRAD, m, last);
+    }
+    for (int k = 0; k < npre; ++k) out.push_back(pre[k]);
+    out.push_back(compute_xop(op));
+    for (int k = 0; k < npost; ++k) out.push_back(post[k]);
+  }
+}
+
+// dense index of a message (what, microbatch, edge): the key under which sends and receives meet
+struct MessageIndex {
+  int M, edges;
+  size_t size() const { return (size_t)6 * M * edges; }
+  size_t at(int what, int mb, int edge) const { return ((size_t)what * M + mb) * edges + edge; }
+};
+
 int unit_kind(int opcode) {
   switch (opcode) {
     case BM_OP_ENC_FWD: return 0;
@@ -143,6 +191,129 @@ extern "C" bm_status bm_pipeline_build_schedule(int32_t order, int32_t P, int32_
   std::vector<bm_pipe_op> prog;
   build_program(Shape{P, V, M}, order, W, has_generator != 0, rank, prog);
   return emit(prog, ops, n_ops);
+}
+
+extern "C" bm_status bm_pipeline_comm_schedule(int32_t order, int32_t P, int32_t V, int32_t M, int32_t W,
+                                               int32_t has_generator, int32_t rank, bm_pipe_xop* ops,
+                                               int32_t* n_ops) {
+  BM_RETURN_IF(check_shape(P, V, M, rank));
+  BM_ARG_CHECK(order == BM_ORDER_NESTED || order == BM_ORDER_COMPUTE_EFFICIENT ||
+               order == BM_ORDER_MEMORY_EFFICIENT, "pipeline: order %d", order);
+  BM_ARG_CHECK(order != BM_ORDER_NESTED || W >= 1, "pipeline: W=%d must be at least 1", W);
+  BM_ARG_CHECK(n_ops != nullptr, "pipeline: n_ops is NULL");
+  std::vector<bm_pipe_xop> prog;
+  build_comm_program(Shape{P, V, M}, order, W, has_generator != 0, rank, prog);
+  const int32_t cap = *n_ops;
+  *n_ops = (int32_t)prog.size();
+  BM_ARG_CHECK(ops != nullptr && cap >= (int32_t)prog.size(), "pipeline: %zu ops need more than the %d given",
+               prog.size(), cap);
+  for (size_t i = 0; i < prog.size(); ++i) ops[i] = prog[i];
+  return BM_OK;
+}
+
+extern "C" bm_status bm_pipeline_check_comm(int32_t order, int32_t P, int32_t V, int32_t M, int32_t W,
+                                            int32_t has_generator, bm_pipe_comm_report* report) {
+  BM_RETURN_IF(check_shape(P, V, M, 0));
+  BM_ARG_CHECK(order == BM_ORDER_NESTED || order == BM_ORDER_COMPUTE_EFFICIENT ||
+               order == BM_ORDER_MEMORY_EFFICIENT, "pipeline: order %d", order);
+  BM_ARG_CHECK(order != BM_ORDER_NESTED || W >= 1, "pipeline: W=%d must be at least 1", W);
+  BM_ARG_CHECK(report != nullptr, "pipeline: report is NULL");
+  const Shape s{P, V, M};
+  const bool gen = has_generator != 0, fused = order == BM_ORDER_MEMORY_EFFICIENT;
+  const int last = P * V - 1;
+  std::vector<std::vector<bm_pipe_xop>> prog(P);
+  for (int r = 0; r < P; ++r) build_comm_program(s, order, W, gen, r, prog[r]);
+
+  // matching: every message key is sent once and received once, between the same two ranks
+  const MessageIndex mi{M, P * V};
+  std::vector<int> n_send(mi.size(), 0), n_recv(mi.size(), 0), src(mi.size(), -1), dst(mi.size(), -1);
+  int unmatched = 0;
+  int64_t messages = 0;
+  for (int r = 0; r < P; ++r)
+    for (const bm_pipe_xop& op : prog[r]) {
+      if (op.op != BM_OP_SEND && op.op != BM_OP_RECV) continue;
+      const size_t k = mi.at(op.what, op.index, op.chunk);
+      if (op.op == BM_OP_SEND) {
+        ++messages;
+        if (n_send[k]++ > 0 || (dst[k] >= 0 && dst[k] != op.peer) || (src[k] >= 0 && src[k] != r)) ++unmatched;
+        src[k] = r; dst[k] = op.peer;
+      } else {
+        if (n_recv[k]++ > 0 || (src[k] >= 0 && src[k] != op.peer) || (dst[k] >= 0 && dst[k] != r)) ++unmatched;
+        src[k] = op.peer; dst[k] = r;
+      }
+    }
+  for (size_t k = 0; k < mi.size(); ++k) unmatched += n_send[k] > n_recv[k] ? n_send[k] - n_recv[k] : n_recv[k] - n_send[k];
+
+  // run: sends never block, a receive waits for its send, a compute op for its local producers
+  Finish ran(s);                                    // >= 0 marks a compute op that has run
+  std::vector<char> posted(mi.size(), 0);
+  std::vector<size_t> pc(P, 0);
+  std::vector<int> inflight((size_t)P * P, 0);
+  std::vector<std::vector<size_t>> sent_seq((size_t)P * P), recv_seq((size_t)P * P);
+  int max_inflight = 0;
+  size_t left = 0;
+  for (int r = 0; r < P; ++r) left += prog[r].size();
+  bool deadlock = false;
+  auto ran_llm = [&](int r, bool bwd, int mb, int c) { return ran.at_llm(r, bwd, mb, c) >= 0.0; };
+  auto ran_unit = [&](int r, int kind, int u) { return ran.at_unit(r, kind, u) >= 0.0; };
+  while (left > 0) {
+    bool moved = false;
+    for (int r = 0; r < P; ++r) {
+      while (pc[r] < prog[r].size()) {
+        const bm_pipe_xop& op = prog[r][pc[r]];
+        const int i = op.index, c = op.chunk;
+        if (op.op == BM_OP_SEND) {
+          posted[mi.at(op.what, i, c)] = 1;
+          const size_t pair = (size_t)r * P + op.peer;
+          max_inflight = ++inflight[pair] > max_inflight ? inflight[pair] : max_inflight;
+          sent_seq[pair].push_back(mi.at(op.what, i, c));
+        } else if (op.op == BM_OP_RECV) {
+          if (!posted[mi.at(op.what, i, c)]) break;
+          const size_t pair = (size_t)op.peer * P + r;
+          --inflight[pair];
+          recv_seq[pair].push_back(mi.at(op.what, i, c));
+        } else {
+          bool ok = true;
+          const int pos = c * P + r;
+          switch (op.op) {
+            case BM_OP_LLM_FWD:
+              if (pos > 0 && (pos - 1) % P == r) ok = ok && ran_llm(r, false, i, c - 1);
+              if (pos == 0 && !fused && i % P == r) ok = ok && ran_unit(r, 0, i / P);
+              break;
+            case BM_OP_LLM_BWD:
+              ok = ok && ran_llm(r, false, i, c);
+              if (pos < last && (pos + 1) % P == r) ok = ok && ran_llm(r, true, i, c + 1);
+              if (pos == last && gen && !fused && i % P == r) ok = ok && ran_unit(r, 3, i / P);
+              break;
+            case BM_OP_ENC_BWD:
+              ok = ok && ran_unit(r, 0, i);
+              if (r == 0) ok = ok && ran_llm(0, true, i * P, 0);
+              break;
+            case BM_OP_GEN_FWD:
+              if (r == P - 1) ok = ok && ran_llm(r, false, i * P + r, V - 1);
+              break;
+            case BM_OP_GEN_BWD: ok = ok && ran_unit(r, 2, i); break;
+            default: break;
+          }
+          if (!ok) break;
+          if (op.op == BM_OP_LLM_FWD || op.op == BM_OP_LLM_BWD) ran.at_llm(r, op.op == BM_OP_LLM_BWD, i, c) = 1.0;
+          else ran.at_unit(r, unit_kind(op.op), i) = 1.0;
+        }
+        ++pc[r];
+        --left;
+        moved = true;
+      }
+    }
+    if (!moved) { deadlock = true; break; }
+  }
+  bool fifo = !deadlock;
+  for (size_t pair = 0; pair < sent_seq.size() && fifo; ++pair) fifo = sent_seq[pair] == recv_seq[pair];
+  report->deadlock = deadlock ? 1 : 0;
+  report->unmatched = unmatched;
+  report->fifo = fifo ? 1 : 0;
+  report->max_inflight = max_inflight;
+  report->messages = messages;
+  return BM_OK;
 }
 
 extern "C" bm_status bm_pipeline_replay(const bm_pipe_replay_config* cfg, bm_pipe_replay_result* res) {

@@ -98,3 +98,28 @@ def test_paper_figure_configuration_properties():
     assert res[bm.ORDER_MEMORY_EFFICIENT]["peak_enc"][0] == 8.0          # first stage's in-flight depth
     # uneven encoder work stalls the coupled pipeline; the nested order hides it
     assert res[bm.ORDER_NESTED]["makespan"] < res[bm.ORDER_MEMORY_EFFICIENT]["makespan"]
+
+
+@pytest.mark.parametrize("P,V,M", GRID)
+@pytest.mark.parametrize("gen", [0, 1])
+def test_comm_programs_and_report_match_oracle(P, V, M, gen):
+    msg = {n: i for i, n in enumerate(bm.MSG_NAMES)}
+    for name, order in ORDERS.items():
+        for W in (1, 3):
+            for r in range(P):
+                got = bm.pipeline_comm_schedule(order, P, V, M, W, gen, r)
+                want = []
+                for op in po.comm_rank_schedule(name, P, V, M, W, bool(gen), r):
+                    if op[0] in ("SEND", "RECV"):
+                        want.append((bm.OP_SEND if op[0] == "SEND" else bm.OP_RECV, op[3], op[4], op[1], msg[op[2]]))
+                    else:
+                        want.append((CODE[op[0]], op[1], op[2], -1, -1))
+                assert got == want
+            assert bm.pipeline_check_comm(order, P, V, M, W, gen) == po.check_comm(name, P, V, M, W, bool(gen))
+
+
+def test_check_comm_reports_the_w2_deadlock_of_the_interleaved_schedule():
+    assert bm.pipeline_check_comm(bm.ORDER_NESTED, 4, 2, 16, 2, 0)["deadlock"] is True
+    rep = bm.pipeline_check_comm(bm.ORDER_NESTED, 4, 2, 64, 3, 1)
+    assert rep == {"deadlock": False, "unmatched": 0, "fifo": False, "max_inflight": rep["max_inflight"],
+                   "messages": 2 * 64 * 7 + 2 * 48 * 2}
