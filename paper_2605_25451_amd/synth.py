@@ -296,6 +296,46 @@ def make_case(cfg: BlockConfig, lens, seed: int, rng=None, docs=None, name: str 
     return BlockCase(cfg, cu, x, params, dy, cond, docs, name)
 
 
+@dataclass
+class TwoStreamCase:
+    """Inputs of a two-stream (text / image) adaLN block: per stream the packed tokens, the
+    per-sample offsets, the parameters and the upstream gradient; one conditioning row per
+    sample.  Stream 0 is text, stream 1 is image."""
+    cfg: BlockConfig
+    cu: List[np.ndarray]
+    x: List[np.ndarray]
+    params: List[Dict[str, np.ndarray]]
+    dy: List[np.ndarray]
+    cond: np.ndarray
+    qk_norm: int = 1
+    name: str = ""
+
+    @property
+    def S(self) -> int:
+        return len(self.cu[0]) - 1
+
+
+def make_two_stream_case(cfg: BlockConfig, text_lens, image_lens, seed: int, qk_norm: int = 1,
+                         name: str = "", weight_std: float = 0.02) -> TwoStreamCase:
+    """Draw order: per stream (text, image) x, parameters (block parameters, then the q and k
+    normalisation weights 1 + N(0, std) of length head_dim), dy; then cond."""
+    assert cfg.norm == NORM_ADALN and len(text_lens) == len(image_lens)
+    rng = np.random.default_rng(seed)
+    cu, x, params, dy = [], [], [], []
+    for lens in (text_lens, image_lens):
+        c = cu_from_lengths(lens)
+        T = int(c[-1])
+        cu.append(c)
+        x.append(to_storage(_normal(rng, (T, cfg.hidden)), cfg.dtype))
+        p = draw_params(rng, cfg, weight_std)
+        p["q_norm_g"] = to_storage(_normal(rng, (cfg.head_dim,), weight_std, 1.0), cfg.dtype)
+        p["k_norm_g"] = to_storage(_normal(rng, (cfg.head_dim,), weight_std, 1.0), cfg.dtype)
+        params.append(p)
+        dy.append(to_storage(_normal(rng, (T, cfg.hidden)), cfg.dtype))
+    cond = to_storage(_normal(rng, (len(text_lens), cfg.hidden)), cfg.dtype)
+    return TwoStreamCase(cfg, cu, x, params, dy, cond, qk_norm, name)
+
+
 def config1(seed: int = 0) -> BlockCase:
     """Tiny fp32 ViT block: two images of 16 and 24 patch tokens in one 40-token pack."""
     return make_case(vit_tiny(DTYPE_FP32), [16, 24], seed, name="config1_vit_tiny_fp32")
