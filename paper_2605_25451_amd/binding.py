@@ -1,7 +1,7 @@
 """Thin ctypes binding over the C-ABI library (argument marshalling only).
 
 Every function has the name and argument order of its C entry point in
-``include/bigmac_block.h``.  Tensors are torch device tensors used purely as
+``include/*.h``.  Tensors are torch device tensors used purely as
 device memory: the binding passes their ``data_ptr()`` and the current HIP
 stream.  There is no fallback: if the shared library is missing or a call
 fails, an exception is raised.
@@ -44,6 +44,14 @@ class BlockDesc(C.Structure):
 
 class BlockParams(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+class MmditDesc(C.Structure):
+    _fields_ = [("block", BlockDesc), ("qk_norm", C.c_int32), ("qk_norm_eps", C.c_float)]
+
+
+class MmditParams(C.Structure):
+    _fields_ = [("stream", BlockParams * 2), ("q_norm_g", C.c_void_p * 2), ("k_norm_g", C.c_void_p * 2)]
 
 
 class ExecutorConfig(C.Structure):
@@ -164,6 +172,13 @@ def lib() -> C.CDLL:
         for name in ("bm_pipeline_llm_schedule", "bm_pipeline_build_schedule", "bm_pipeline_replay",
                      "bm_pipeline_comm_schedule", "bm_pipeline_check_comm"):
             getattr(l, name).restype = C.c_int
+        pmd, pmp = C.POINTER(MmditDesc), C.POINTER(MmditParams)
+        l.bm_mmdit_sizes.argtypes = [pmd, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+        l.bm_mmdit_forward.argtypes = [pmd, pmp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        l.bm_mmdit_backward.argtypes = [pmd, pmp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, pmp,
+                                        vp, vp, sz, vp]
+        for name in ("bm_mmdit_sizes", "bm_mmdit_forward", "bm_mmdit_backward"):
+            getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
 
@@ -232,6 +247,46 @@ def block_backward(desc, w: BlockParams, x, dy, cu_seqlens_dev, cu_seqlens_host,
                                    _ptr(cu_seqlens_dev), cu_h.ctypes.data, S, T, max_seqlen,
                                    _ptr(cond), _ptr(saved), _ptr(dx), C.byref(grads), _ptr(dcond),
                                    _ptr(scratch), scratch_bytes,
+                                   _stream() if stream is None else stream))
+
+
+def make_mmdit_desc(cfg, qk_norm: int, qk_norm_eps: float = 1e-6) -> MmditDesc:
+    return MmditDesc(make_desc(cfg), int(qk_norm), float(qk_norm_eps))
+
+
+def make_mmdit_params(streams) -> MmditParams:
+    """streams: two dicts of tensors (text, image), block parameter names plus q_norm_g / k_norm_g."""
+    p = MmditParams()
+    for s in range(2):
+        p.stream[s] = make_params(streams[s])
+        p.q_norm_g[s] = _ptr(streams[s].get("q_norm_g"))
+        p.k_norm_g[s] = _ptr(streams[s].get("k_norm_g"))
+    return p
+
+
+def mmdit_sizes(desc: MmditDesc, T_text: int, T_img: int, S: int):
+    saved, scratch = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().bm_mmdit_sizes(C.byref(desc), T_text, T_img, S, C.byref(saved), C.byref(scratch)))
+    return saved.value, scratch.value
+
+
+def mmdit_forward(desc, w: MmditParams, x_text, x_img, cu_text_dev, cu_text_host, cu_img_dev, cu_img_host, S,
+                  cond, y_text, y_img, saved, scratch, scratch_bytes, stream=None):
+    ct, ci = _host_cu(cu_text_host), _host_cu(cu_img_host)
+    _check(lib().bm_mmdit_forward(C.byref(desc), C.byref(w), _ptr(x_text), _ptr(x_img), _ptr(cu_text_dev),
+                                  ct.ctypes.data, _ptr(cu_img_dev), ci.ctypes.data, S, _ptr(cond),
+                                  _ptr(y_text), _ptr(y_img), _ptr(saved), _ptr(scratch), scratch_bytes,
+                                  _stream() if stream is None else stream))
+
+
+def mmdit_backward(desc, w: MmditParams, x_text, x_img, dy_text, dy_img, cu_text_dev, cu_text_host,
+                   cu_img_dev, cu_img_host, S, cond, saved, dx_text, dx_img, grads: MmditParams, dcond,
+                   scratch, scratch_bytes, stream=None):
+    ct, ci = _host_cu(cu_text_host), _host_cu(cu_img_host)
+    _check(lib().bm_mmdit_backward(C.byref(desc), C.byref(w), _ptr(x_text), _ptr(x_img), _ptr(dy_text),
+                                   _ptr(dy_img), _ptr(cu_text_dev), ct.ctypes.data, _ptr(cu_img_dev),
+                                   ci.ctypes.data, S, _ptr(cond), _ptr(saved), _ptr(dx_text), _ptr(dx_img),
+                                   C.byref(grads), _ptr(dcond), _ptr(scratch), scratch_bytes,
                                    _stream() if stream is None else stream))
 
 

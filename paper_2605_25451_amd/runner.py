@@ -95,3 +95,57 @@ class CaseOnDevice:
         torch.cuda.synchronize()
         f = lambda t: None if t is None else t.detach().float().cpu().numpy().astype(np.float64)
         return f(self.y), f(self.dx), {k: f(v) for k, v in self.runner.grads.items()}, f(self.dcond)
+
+
+class TwoStreamOnDevice:
+    """A synth.TwoStreamCase resident in HBM: both streams' tokens, parameters, fp32 gradient
+    accumulators, outputs and workspaces, forwarded to bm_mmdit_forward / bm_mmdit_backward."""
+
+    def __init__(self, case: synth.TwoStreamCase, device="cuda:0", qk_norm_eps: float = 1e-6):
+        cfg = case.cfg
+        self.case = case
+        self.desc = bm.make_mmdit_desc(cfg, case.qk_norm, qk_norm_eps)
+        self.params = [{k: to_device(v, cfg.dtype, device) for k, v in p.items()} for p in case.params]
+        self.grads = [{k: torch.zeros(v.shape, dtype=torch.float32, device=device) for k, v in p.items()}
+                      for p in self.params]
+        self.w = bm.make_mmdit_params(self.params)
+        self.g = bm.make_mmdit_params(self.grads)
+        self.cu_host = [np.asarray(c, dtype=np.int32) for c in case.cu]
+        self.cu_dev = [torch.from_numpy(c).to(device) for c in self.cu_host]
+        self.S = case.S
+        self.x = [to_device(a, cfg.dtype, device) for a in case.x]
+        self.dy = [to_device(a, cfg.dtype, device) for a in case.dy]
+        self.cond = to_device(case.cond, cfg.dtype, device)
+        self.y = [torch.empty_like(a) for a in self.x]
+        self.dx = [torch.empty_like(a) for a in self.x]
+        self.dcond = torch.empty_like(self.cond)
+        saved, scratch = bm.mmdit_sizes(self.desc, int(self.cu_host[0][-1]), int(self.cu_host[1][-1]), self.S)
+        self.saved_bytes, self.scratch_bytes = saved, scratch
+        self.saved = torch.empty(saved, dtype=torch.uint8, device=device)
+        self.scratch = torch.empty(scratch, dtype=torch.uint8, device=device)
+
+    def zero_grads(self):
+        for gs in self.grads:
+            for g in gs.values():
+                g.zero_()
+
+    def forward(self):
+        bm.mmdit_forward(self.desc, self.w, self.x[0], self.x[1], self.cu_dev[0], self.cu_host[0], self.cu_dev[1],
+                         self.cu_host[1], self.S, self.cond, self.y[0], self.y[1], self.saved, self.scratch,
+                         self.scratch_bytes)
+
+    def backward(self):
+        bm.mmdit_backward(self.desc, self.w, self.x[0], self.x[1], self.dy[0], self.dy[1], self.cu_dev[0],
+                          self.cu_host[0], self.cu_dev[1], self.cu_host[1], self.S, self.cond, self.saved,
+                          self.dx[0], self.dx[1], self.g, self.dcond, self.scratch, self.scratch_bytes)
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+    def results(self):
+        """([y_text, y_img], [dx_text, dx_img], [grads_text, grads_img], dcond) as float64 numpy arrays."""
+        torch.cuda.synchronize()
+        f = lambda t: t.detach().float().cpu().numpy().astype(np.float64)
+        return ([f(t) for t in self.y], [f(t) for t in self.dx],
+                [{k: f(v) for k, v in gs.items()} for gs in self.grads], f(self.dcond))
