@@ -2,7 +2,7 @@
 """Benchmark of the hot path: forward + backward of one packed variable-length
 transformer block on one MI355X, through the C-ABI library.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit|moe]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit|moe|mmdit]
   python bench.py --workload config5 --batch 8|16|32 [--unit-size 1] [--steps K]
   python bench.py --workload pipeline [--steps K]
 
@@ -71,6 +71,63 @@ def algorithmic_flops(cfg, cu):
     pairs = (L * (L + 1) / 2).sum() if cfg.mask else (L * L).sum()
     attn = 4.0 * cfg.head_dim * cfg.n_q_heads * pairs
     return gemm, attn
+
+
+def mmdit_case(seed=6, n_samples=16, image_tokens=1024):
+    """Two-stream block at the shape of a 20 B-class multimodal diffusion transformer (hidden 3072,
+    24 heads of 128, MLP 12288; the paper states the size only): per sample one caption of
+    U[32, 256] text tokens and 1024 latent image tokens."""
+    import numpy as np
+    from paper_2605_25451_amd import synth
+    rng = np.random.default_rng(seed)
+    text = [int(v) for v in rng.integers(32, 257, size=n_samples)]
+    cfg = synth.scaled(synth.dit_block(), hidden=3072, n_q_heads=24, n_kv_heads=24, head_dim=128, mlp_hidden=12288)
+    return synth.make_two_stream_case(cfg, text, [image_tokens] * n_samples, seed, 1, "mmdit_20b_block_bf16")
+
+
+def mmdit_flops(cfg, cu_text, cu_img):
+    """(gemm_fwd, attn_fwd) flops of the two-stream block: per-stream projections, joint attention."""
+    import numpy as np
+    d, F, S = cfg.hidden, cfg.mlp_hidden, len(cu_text) - 1
+    T = int(cu_text[-1]) + int(cu_img[-1])
+    gemm = 2.0 * T * d * (3 * d + d + 2 * F) + 2 * 2.0 * S * d * 6 * d
+    L = (np.diff(cu_text) + np.diff(cu_img)).astype(np.float64)
+    attn = 4.0 * cfg.head_dim * cfg.n_q_heads * (L * L).sum()
+    return gemm, attn
+
+
+def mmdit_sub_case(case, n):
+    """The first n samples of a two-stream case (same parameters)."""
+    from paper_2605_25451_amd import synth
+    cu = [c[:n + 1] for c in case.cu]
+    return synth.TwoStreamCase(case.cfg, cu, [case.x[s][:cu[s][-1]] for s in range(2)], case.params,
+                               [case.dy[s][:cu[s][-1]] for s in range(2)], case.cond[:n], case.qk_norm,
+                               case.name + "_sub")
+
+
+def cpu_baseline_mmdit(case, budget_flops=2.0e12):
+    from oracle import mmdit_oracle as mo
+    n = 1
+    while n < case.S:
+        g, a = mmdit_flops(case.cfg, case.cu[0][:n + 1], case.cu[1][:n + 1])
+        if 3.0 * g + 3.5 * a >= budget_flops:
+            break
+        n += 1
+    sub = mmdit_sub_case(case, n)
+    t0 = time.perf_counter()
+    _, cache = mo.mmdit_forward(sub.cfg, sub.params, sub.x, sub.cu, sub.cond, bool(sub.qk_norm))
+    mo.mmdit_backward(sub.cfg, cache, sub.dy, bool(sub.qk_norm))
+    dt = time.perf_counter() - t0
+    g, a = mmdit_flops(sub.cfg, sub.cu[0], sub.cu[1])
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    T_sub, T = int(sub.cu[0][-1] + sub.cu[1][-1]), int(case.cu[0][-1] + case.cu[1][-1])
+    return {"value": (3.0 * g + 3.5 * a) / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"numpy fp64 oracle fwd+bwd on the first {n} samples ({T_sub} of {T} tokens) "
+                      f"of the same batch, {dt:.1f} s"}
 
 
 def measured_peaks():
@@ -289,9 +346,25 @@ def main():
         return run_stage_workload(args)
     if args.workload == "pipeline":
         return run_pipeline_workload(args)
-    case = make_workload(args.workload)
-    dev = CaseOnDevice(case)
-    gemm_f, attn_f = algorithmic_flops(case.cfg, case.cu_seqlens)
+    if args.workload == "mmdit":
+        import numpy as np
+        from paper_2605_25451_amd.runner import TwoStreamOnDevice
+        case = mmdit_case()
+        dev = TwoStreamOnDevice(case)
+        gemm_f, attn_f = mmdit_flops(case.cfg, case.cu[0], case.cu[1])
+        tokens, n_seq = int(case.cu[0][-1] + case.cu[1][-1]), case.S
+        max_seqlen = int(np.max(np.diff(case.cu[0]) + np.diff(case.cu[1])))
+        extra = {"text_tokens": int(case.cu[0][-1]), "image_tokens": int(case.cu[1][-1]),
+                 "step": "one two-stream block forward + backward (joint attention over [text ; image], "
+                         "q/k RMS norm, weight grads accumulated in fp32)"}
+        baseline = lambda: cpu_baseline_mmdit(case)
+    else:
+        case = make_workload(args.workload)
+        dev = CaseOnDevice(case)
+        gemm_f, attn_f = algorithmic_flops(case.cfg, case.cu_seqlens)
+        tokens, n_seq, max_seqlen = case.T, case.S, case.max_seqlen
+        extra = {"step": "one block forward + backward (weight grads accumulated in fp32)"}
+        baseline = lambda: cpu_baseline(case)
     step_flops = 3.0 * gemm_f + 3.5 * attn_f
 
     for _ in range(args.warmup):
@@ -346,16 +419,15 @@ def main():
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": case.name, "tokens": case.T, "sequences": case.S,
-                   "max_seqlen": case.max_seqlen, "hidden": case.cfg.hidden,
+        "config": {"workload": case.name, "tokens": tokens, "sequences": n_seq,
+                   "max_seqlen": max_seqlen, "hidden": case.cfg.hidden,
                    "heads": f"{case.cfg.n_q_heads}q/{case.cfg.n_kv_heads}kv x {case.cfg.head_dim}",
-                   "mlp_hidden": case.cfg.mlp_hidden,
-                   "step": "one block forward + backward (weight grads accumulated in fp32)",
+                   "mlp_hidden": case.cfg.mlp_hidden, **extra,
                    "flops_per_step": step_flops},
         "mfma_util_pct": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "gemm_tflops": gemm_work / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
         "attention_tflops": attn_work / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None,
-        "tokens_per_s": case.T / (ms_per_step * 1e-3),
+        "tokens_per_s": tokens / (ms_per_step * 1e-3),
         "roofline": roofline,
         "breakdown": breakdown,
         "measured_peaks": measured_peaks(),
@@ -368,7 +440,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(case)
+        out["cpu_baseline"] = baseline()
     print(json.dumps(out))
 
 
