@@ -109,7 +109,7 @@ struct BwdScratch {
   char *attn_ws, *norm_ws, *colsum_ws, *gemm_ws;
   size_t attn_ws_bytes, gemm_ws_bytes;
   float *dmod, *dsc;
-  char *dmod_e, *sc;
+  char *dmod_e, *dmod_t, *sc;
   char *dyp, *xp, *dlogits, *dh2e;   // experts: routed output grads [cap,d], routed inputs [cap,d],
                                      // router logit grads [T,E], expert part of the norm-2 output grad [T,d]
   size_t bytes;
@@ -128,7 +128,7 @@ size_t max_gemm_tn_scratch(const Dims& m, int dtype) {
   v = gemm_scratch_bytes(GEMM_TN, m.QKV, m.d, m.T, dtype); b = v > b ? v : b;
   if (m.ada) {
     v = gemm_scratch_bytes(GEMM_TN, 6 * m.d, m.d, m.S, dtype); b = v > b ? v : b;
-    v = gemm_scratch_bytes(GEMM_NN, m.S, m.d, 6 * m.d, dtype); b = v > b ? v : b;
+    v = gemm_scratch_bytes(GEMM_TN, (int)align_up(m.S, 8), m.d, 6 * m.d, dtype); b = v > b ? v : b;
   }
   return b;
 }
@@ -162,13 +162,15 @@ BwdScratch layout_bwd(const Dims& m, int dtype, void* base) {
     s.dlogits = a.take<char>(T * m.E * m.es);
     s.dh2e = a.take<char>(T * m.d * m.es);
   }
-  s.dgated = nullptr; s.dmod = nullptr; s.dsc = nullptr; s.dmod_e = nullptr; s.sc = nullptr;
+  s.dgated = nullptr; s.dmod = nullptr; s.dsc = nullptr; s.dmod_e = nullptr; s.dmod_t = nullptr; s.sc = nullptr;
   if (m.ada) {
     s.dgated = a.take<char>(T * m.d * m.es);
     s.dmod = a.take<float>((size_t)m.S * 6 * m.d * sizeof(float));
     s.dmod_e = a.take<char>((size_t)m.S * 6 * m.d * m.es);
     s.sc = a.take<char>((size_t)m.S * m.d * m.es);
-    s.dsc = a.take<float>((size_t)m.S * m.d * sizeof(float));
+    const size_t S8 = align_up(m.S, 8);
+    s.dmod_t = a.take<char>(S8 * 6 * m.d * m.es);
+    s.dsc = a.take<float>(S8 * m.d * sizeof(float));
   }
   s.bytes = a.off;
   return s;
@@ -422,8 +424,10 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   // ---- y = x1 + [g2 *] m,  m = a W_down^T + b_down
   const void* dm = dy;
   if (m.ada) {
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(segment_colsum(dt, dy, sv.m, d, d, cu_dev, S, ws.dmod + 5 * d, 6 * d, st)); }
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, dy, sv.mod + 5 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
+    // gate gradient (per-sequence sum of dy * m) and the gated upstream gradient in one pass over dy
+    { ProfScope _p(PROF_ELEMENTWISE, 3.0 * T * d * (double)m.es, st);
+      BM_RETURN_IF(segment_gate(dt, dy, sv.m, sv.mod + 5 * d, 6 * d, ws.dgated, cu_dev, S, d, ws.dmod + 5 * d, 6 * d,
+                                ws.norm_ws, st)); }
     dm = ws.dgated;
   }
   const bool fused_sums = c.linear_bias && !m.ada;
@@ -491,8 +495,9 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   // ---- x1 = x + [g1 *] attn,  attn = o W_o^T + b_o
   const void* dattn = ws.dx1;
   if (m.ada) {
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(segment_colsum(dt, ws.dx1, sv.attn, d, d, cu_dev, S, ws.dmod + 2 * d, 6 * d, st)); }
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(gate_mul(dt, ws.dx1, sv.mod + 2 * d, 6 * d, ws.tok_seq, nullptr, ws.dgated, T, d, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 3.0 * T * d * (double)m.es, st);
+      BM_RETURN_IF(segment_gate(dt, ws.dx1, sv.attn, sv.mod + 2 * d, 6 * d, ws.dgated, cu_dev, S, d, ws.dmod + 2 * d,
+                                6 * d, ws.norm_ws, st)); }
     dattn = ws.dgated;
   }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.QD, T, dattn, d, sv.o, m.QD, grads->w_o, m.QD, none, ws.gemm_ws,
@@ -536,8 +541,12 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
     BM_RETURN_IF(gemm(GEMM_TN, dt, 6 * d, d, S, ws.dmod_e, 6 * d, ws.sc, d, grads->w_ada, d, none,
                       ws.gemm_ws, ws.gemm_ws_bytes, st));
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, ws.dmod_e, 6 * d, S, 6 * d, (float*)grads->b_ada, ws.colsum_ws, st)); }
-    GemmEpilogue e; e.out_fp32 = 1;
-    BM_RETURN_IF(gemm(GEMM_NN, dt, S, d, 6 * d, ws.dmod_e, 6 * d, w->w_ada, d, ws.dsc, d, e, ws.gemm_ws,
+    // d silu(cond) = dmod W_ada: a few rows against a long reduction, so it runs as a weight-gradient
+    // style product on the transposed dmod (rows padded to 8), whose k range splits over the chip
+    const int S8 = (int)align_up(S, 8);
+    BM_RETURN_IF(cast_transpose_from_f32(dt, ws.dmod, ws.dmod_t, S, 6 * d, S8, st));
+    BM_RETURN_IF(fill_zero(ws.dsc, (size_t)S8 * d * sizeof(float), st));
+    BM_RETURN_IF(gemm(GEMM_TN, dt, S8, d, 6 * d, ws.dmod_t, S8, w->w_ada, d, ws.dsc, d, none, ws.gemm_ws,
                       ws.gemm_ws_bytes, st));
     BM_RETURN_IF(silu_backward_f32(dt, cond, ws.dsc, dcond, (long)S * d, st));
   }

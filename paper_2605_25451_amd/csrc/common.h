@@ -253,9 +253,12 @@ bm_status act_backward(int dtype, int act, const void* up, const void* da, void*
 size_t colsum_scratch_bytes(int T, int N);
 bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, float* out,
                             void* scratch, hipStream_t st);
-// out[s, n] = sum_{t in s} a[t,n] * b[t,n]    (fp32, overwrite; b optional)
-bm_status segment_colsum(int dtype, const void* a, const void* b, int ld, int N,
-                         const int32_t* cu_dev, int S, float* out, int ld_out, hipStream_t st);
+// out[s, n] = sum_{t in s} a[t,n] * b[t,n] (fp32, overwrite) and, when gated != nullptr,
+// gated[t, n] = a[t, n] * gate[s, n]; rows are N wide; scratch: segment_scratch_bytes()
+size_t segment_scratch_bytes();
+bm_status segment_gate(int dtype, const void* a, const void* b, const float* gate, int ld_gate, void* gated,
+                       const int32_t* cu_dev, int S, int N, float* out, int ld_out, void* scratch,
+                       hipStream_t st);
 // out[t, n] = (residual ? residual[t,n] : 0) + a[t, n] * gate[tok_seq[t], n]
 bm_status gate_mul(int dtype, const void* a, const float* gate, int ld_gate,
                    const int32_t* tok_seq, const void* residual, void* out, int T, int N,
@@ -266,6 +269,9 @@ bm_status silu_backward_f32(int dtype, const void* in, const float* g, void* out
                             hipStream_t st);
 // fp32 -> storage dtype
 bm_status cast_from_f32(int dtype, const float* in, void* out, long n, hipStream_t st);
+// fp32 [rows, cols] -> storage dtype [cols, ld_out], columns rows..ld_out-1 zero
+bm_status cast_transpose_from_f32(int dtype, const float* in, void* out, int rows, int cols, int ld_out,
+                                  hipStream_t st);
 
 }  // namespace bm
 

@@ -347,37 +347,142 @@ __global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_multi_kernel(
   }
 }
 
-// adaLN: dshift[s,:] = sum_{t in s} dh,  dscale[s,:] = sum_{t in s} dh * xhat
-template <typename T>
-__global__ __launch_bounds__(256) void adaln_seg_grads_kernel(
-    const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
-    const int32_t* __restrict__ cu, float* __restrict__ dmod, int ld_mod, int shift_off,
-    int scale_off, int rows, int d) {
-  __shared__ float sm[2][4][64];
-  const int s = blockIdx.x;
-  const int c = blockIdx.y * 64 + (threadIdx.x & 63);
-  const int rg = threadIdx.x >> 6;
-  float a_sh = 0.f, a_sc = 0.f;
-  if (c < d) {
-    for (int t = cu[s] + rg; t < cu[s + 1]; t += 4) {
-      float g = Elt<T>::to_f(dh[(size_t)t * d + c]);
-      float xh = (Elt<T>::to_f(x[(size_t)t * d + c]) - stats[t]) * stats[rows + t];
-      a_sh += g; a_sc += g * xh;
+// ------------------------------------------------------------------ per-sequence column sums
+// Sums over the rows of every sequence, for the adaLN parameter gradients.  A workgroup owns one
+// part (of `parts`) of one sequence's rows and 64 16-byte column chunks; its four wavefronts take
+// rows round-robin, are combined through LDS in a fixed order, and the parts of a sequence are
+// added in a fixed order by seg_reduce_kernel (parts == 1 writes the result directly).
+//   MODE 0 (gate):   sum0[s] = sum_t a*b;  optionally gated[t] = a[t] * gate[s]
+//   MODE 1 (adaLN):  sum0[s] = sum_t dh,  sum1[s] = sum_t dh * xhat   (xhat from x and the row statistics)
+struct SegArgs {
+  const void *a, *b;              // MODE 0: a, b.  MODE 1: dh, x
+  const float* stats;             // MODE 1: mean[rows], rstd[rows]
+  const float* gate; int ld_gate; // MODE 0: gate[s, :] (fp32), used when gated != nullptr
+  void* gated;
+  const int32_t* cu;
+  float* out; int ld_out, off0, off1;   // out[s, off_p + n]
+  float* partial;                 // [S*parts][planes][N] when parts > 1
+  int parts, rows, N;
+};
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void seg_sums_kernel(SegArgs p) {
+  constexpr int VEC = Elt<T>::VEC;
+  constexpr int P = MODE == 0 ? 1 : 2;
+  __shared__ float sm[P][4][WAVE * VEC];
+  const int s = blockIdx.x / p.parts, part = blockIdx.x % p.parts;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = (blockIdx.y * WAVE + lane) * VEC;
+  const bool live = col < p.N;
+  const int t0 = p.cu[s], t1 = p.cu[s + 1];
+  const int per = (t1 - t0 + p.parts - 1) / p.parts;
+  const int rb = t0 + part * per, re = min(t1, rb + per);
+  const T* a = (const T*)p.a;
+  const T* b = (const T*)p.b;
+  float acc[P][VEC], g[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { acc[0][e] = 0.f; acc[P - 1][e] = 0.f; g[e] = 0.f; }
+  if (MODE == 0 && p.gated && live) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) g[e] = p.gate[(size_t)s * p.ld_gate + col + e];
+  }
+  if (live) {
+    for (int t = rb + wave; t < re; t += 4) {
+      float va[VEC], vb[VEC];
+      load16(a + (size_t)t * p.N + col, va);
+      load16(b + (size_t)t * p.N + col, vb);
+      if (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[0][e] += va[e] * vb[e];
+        if (p.gated) {
+          float o[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) o[e] = va[e] * g[e];
+          store16((T*)p.gated + (size_t)t * p.N + col, o);
+        }
+      } else {
+        const float mean = p.stats[t], rstd = p.stats[p.rows + t];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          acc[0][e] += va[e];
+          acc[P - 1][e] += va[e] * ((vb[e] - mean) * rstd);
+        }
+      }
     }
   }
-  sm[0][rg][threadIdx.x & 63] = a_sh; sm[1][rg][threadIdx.x & 63] = a_sc;
+#pragma unroll
+  for (int q = 0; q < P; ++q)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sm[q][wave][lane * VEC + e] = acc[q][e];
   __syncthreads();
-  if (rg == 0 && c < d) {
-    int l = threadIdx.x;
-    dmod[(size_t)s * ld_mod + shift_off + c] = sm[0][0][l] + sm[0][1][l] + sm[0][2][l] + sm[0][3][l];
-    dmod[(size_t)s * ld_mod + scale_off + c] = sm[1][0][l] + sm[1][1][l] + sm[1][2][l] + sm[1][3][l];
+  if (wave == 0 && live) {
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+      float* dst = p.parts > 1 ? p.partial + ((size_t)blockIdx.x * P + q) * p.N + col
+                               : p.out + (size_t)s * p.ld_out + (q == 0 ? p.off0 : p.off1) + col;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const int c = lane * VEC + e;
+        dst[e] = sm[q][0][c] + sm[q][1][c] + sm[q][2][c] + sm[q][3][c];
+      }
+    }
   }
+}
+
+__global__ void seg_reduce_kernel(const float* __restrict__ partial, int S, int parts, int planes, int N,
+                                  float* __restrict__ out, int ld_out, int off0, int off1) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)S * planes * N) return;
+  const int n = (int)(i % N), q = (int)((i / N) % planes), s = (int)(i / ((long)N * planes));
+  float v = 0.f;
+  for (int r = 0; r < parts; ++r) v += partial[(((size_t)s * parts + r) * planes + q) * N + n];
+  out[(size_t)s * ld_out + (q == 0 ? off0 : off1) + n] = v;
+}
+
+// parts per sequence: enough workgroups to fill the chip, at most 16
+static int seg_parts(int S, int N, int vec) {
+  const long blocks = (long)S * cdiv(N, WAVE * vec);
+  if (blocks >= 1024) return 1;
+  const int r = cdiv(1024, blocks);
+  return r > 16 ? 16 : r;
+}
+
+// upper bound for any S: parts > 1 only while S * column blocks < 1024, and then
+// S * parts * N <= 2048 * 64 * VEC elements per plane
+size_t segment_scratch_bytes() { return (size_t)2048 * 512 * 2 * sizeof(float); }
+
+template <int MODE>
+static bm_status seg_launch(int dtype, SegArgs p, int S, void* scratch, hipStream_t st) {
+  if (S == 0) return BM_OK;
+  const int vec = dtype == BM_DTYPE_BF16 ? 8 : 4;
+  if (p.N % vec) { set_error("segment sums: width %d not a multiple of %d", p.N, vec); return BM_ERR_UNSUPPORTED; }
+  p.parts = scratch ? seg_parts(S, p.N, vec) : 1;
+  p.partial = (float*)scratch;
+  dim3 grid(S * p.parts, cdiv(p.N, WAVE * vec));
+  if (dtype == BM_DTYPE_BF16) hipLaunchKernelGGL((seg_sums_kernel<bf16_t, MODE>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((seg_sums_kernel<float, MODE>), grid, dim3(256), 0, st, p);
+  if (p.parts > 1) {
+    const int planes = MODE == 0 ? 1 : 2;
+    hipLaunchKernelGGL(seg_reduce_kernel, dim3(cdiv((long)S * planes * p.N, 256)), dim3(256), 0, st, p.partial, S,
+                       p.parts, planes, p.N, p.out, p.ld_out, p.off0, p.off1);
+  }
+  BM_CHECK_LAUNCH("segment sums");
+  return BM_OK;
+}
+
+bm_status segment_gate(int dtype, const void* a, const void* b, const float* gate, int ld_gate, void* gated,
+                       const int32_t* cu_dev, int S, int N, float* out, int ld_out, void* scratch,
+                       hipStream_t st) {
+  SegArgs p{};
+  p.a = a; p.b = b; p.gate = gate; p.ld_gate = ld_gate; p.gated = gated; p.cu = cu_dev;
+  p.out = out; p.ld_out = ld_out; p.off0 = 0; p.off1 = 0; p.N = N;
+  return seg_launch<0>(dtype, p, S, scratch, st);
 }
 
 static int norm_bwd_blocks(int T) { int b = cdiv(T, 4); return b < NORM_BWD_MAX_BLOCKS ? b : NORM_BWD_MAX_BLOCKS; }
 
 size_t norm_backward_scratch_bytes(int T, int d) {
-  return (size_t)norm_bwd_blocks(T) * 4 * d * sizeof(float);
+  return align_up((size_t)norm_bwd_blocks(T) * 4 * d * sizeof(float), 256) + segment_scratch_bytes();
 }
 
 template <typename T, int KIND, bool SUMS>
@@ -428,16 +533,11 @@ bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, co
   BM_RETURN_IF(rc);
   const int nb = norm_bwd_blocks(a.T);
   if (a.kind == BM_NORM_ADALN) {
-    dim3 grid(S, cdiv(a.d, 64));
-    if (a.dtype == BM_DTYPE_BF16)
-      hipLaunchKernelGGL(adaln_seg_grads_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)x,
-                         stats, (const bf16_t*)dh, cu_dev, dmod, a.ld_mod, a.shift_off, a.scale_off,
-                         a.T, a.d);
-    else
-      hipLaunchKernelGGL(adaln_seg_grads_kernel<float>, grid, dim3(256), 0, st, (const float*)x,
-                         stats, (const float*)dh, cu_dev, dmod, a.ld_mod, a.shift_off, a.scale_off,
-                         a.T, a.d);
-    BM_CHECK_LAUNCH("adaln_seg_grads");
+    SegArgs p{};
+    p.a = dh; p.b = x; p.stats = stats; p.cu = cu_dev; p.out = dmod; p.ld_out = a.ld_mod;
+    p.off0 = a.shift_off; p.off1 = a.scale_off; p.rows = a.T; p.N = a.d;
+    char* seg_ws = (char*)scratch + align_up((size_t)nb * 4 * a.d * sizeof(float), 256);
+    BM_RETURN_IF(seg_launch<1>(a.dtype, p, S, seg_ws, st));
   }
   ReduceTargets t;
   int np = 0;
@@ -764,46 +864,6 @@ bm_status colsum_accumulate(int dtype, const void* a, int lda, int T, int N, flo
   return BM_OK;
 }
 
-// ------------------------------------------------------------------ per-sequence column sums
-template <typename T>
-__global__ __launch_bounds__(256) void segment_colsum_kernel(const T* __restrict__ a,
-                                                             const T* __restrict__ b, int ld, int N,
-                                                             const int32_t* __restrict__ cu,
-                                                             float* __restrict__ out, int ld_out) {
-  __shared__ float sm[4][64];
-  const int s = blockIdx.x;
-  const int c = blockIdx.y * 64 + (threadIdx.x & 63);
-  const int rg = threadIdx.x >> 6;
-  float acc = 0.f;
-  if (c < N) {
-    for (int t = cu[s] + rg; t < cu[s + 1]; t += 4) {
-      float v = Elt<T>::to_f(a[(size_t)t * ld + c]);
-      if (b) v *= Elt<T>::to_f(b[(size_t)t * ld + c]);
-      acc += v;
-    }
-  }
-  sm[rg][threadIdx.x & 63] = acc;
-  __syncthreads();
-  if (rg == 0 && c < N) {
-    int l = threadIdx.x;
-    out[(size_t)s * ld_out + c] = sm[0][l] + sm[1][l] + sm[2][l] + sm[3][l];
-  }
-}
-
-bm_status segment_colsum(int dtype, const void* a, const void* b, int ld, int N,
-                         const int32_t* cu_dev, int S, float* out, int ld_out, hipStream_t st) {
-  if (S == 0) return BM_OK;
-  dim3 grid(S, cdiv(N, 64));
-  if (dtype == BM_DTYPE_BF16)
-    hipLaunchKernelGGL(segment_colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)a,
-                       (const bf16_t*)b, ld, N, cu_dev, out, ld_out);
-  else
-    hipLaunchKernelGGL(segment_colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)a,
-                       (const float*)b, ld, N, cu_dev, out, ld_out);
-  BM_CHECK_LAUNCH("segment_colsum");
-  return BM_OK;
-}
-
 // ------------------------------------------------------------------ small elementwise helpers
 template <typename T>
 __global__ void gate_mul_kernel(const T* __restrict__ a, const float* __restrict__ gate, int ld_gate,
@@ -866,6 +926,30 @@ template <typename T>
 __global__ void cast_from_f32_kernel(const float* __restrict__ in, T* __restrict__ out, long n) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = Elt<T>::from_f(in[i]);
+}
+
+// out[n, s] = in[s, n] for s < rows, 0 for rows <= s < ld_out
+template <typename T>
+__global__ void cast_transpose_from_f32_kernel(const float* __restrict__ in, T* __restrict__ out, int rows,
+                                               int cols, int ld_out) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)cols * ld_out) return;
+  const int n = (int)(i / ld_out), s = (int)(i % ld_out);
+  out[i] = Elt<T>::from_f(s < rows ? in[(size_t)s * cols + n] : 0.f);
+}
+
+bm_status cast_transpose_from_f32(int dtype, const float* in, void* out, int rows, int cols, int ld_out,
+                                  hipStream_t st) {
+  const long n = (long)cols * ld_out;
+  if (n == 0) return BM_OK;
+  if (dtype == BM_DTYPE_BF16)
+    hipLaunchKernelGGL(cast_transpose_from_f32_kernel<bf16_t>, dim3(cdiv(n, 256)), dim3(256), 0, st, in,
+                       (bf16_t*)out, rows, cols, ld_out);
+  else
+    hipLaunchKernelGGL(cast_transpose_from_f32_kernel<float>, dim3(cdiv(n, 256)), dim3(256), 0, st, in,
+                       (float*)out, rows, cols, ld_out);
+  BM_CHECK_LAUNCH("cast_transpose");
+  return BM_OK;
 }
 
 bm_status silu_forward(int dtype, const void* in, void* out, long n, hipStream_t st) {

@@ -497,9 +497,17 @@ bool gemm_mfma_supported(int layout, int dtype, int M, int N, int K, int lda, in
                          const GemmEpilogue& epi) {
   (void)epi;
   if (dtype != BM_DTYPE_BF16) return false;
-  if (M < 64 || N < 64 || K < 64) return false;          // tiny problems: generic kernel
   if (lda % 8 || ldb % 8) return false;                  // 16-byte rows
-  if (layout == GEMM_TN) return M % 8 == 0 && N % 8 == 0 && ldc % 4 == 0;   // rows are contiguous
+  if (N < 64) return false;                              // tiny problems: generic kernel
+  if (layout == GEMM_TN) {
+    // operands are [k][row]: rows come in chunks of 8, any k range of at least one chunk
+    // works (a short one is zero-filled); one of M and K may be small (the 8..32-row
+    // products of the adaLN modulation), not both
+    if (M % 8 || N % 8 || ldc % 4) return false;
+    return M >= 8 && K >= 8 && (M >= 64 || K >= 64);
+  }
+  // row-major A: rows past M are clamped to the last one and never stored, so few rows are fine
+  if (M < 1 || K < 64) return false;
   return K % 8 == 0 && N % 8 == 0 && ldc % 8 == 0;          // 16-byte row chunks of C
 }
 

@@ -109,7 +109,7 @@ struct MBwd {
   float* dmod[2];               // [S, 6d] per stream
   float* dsc[2];                // [S, d] per stream
   char *d_o_j, *dqkv_j;         // joint order
-  char *a, *dup, *da, *h, *dh, *dgated, *d_o, *dqkv, *dmod_e, *sc;   // per-stream temporaries, reused
+  char *a, *dup, *da, *h, *dh, *dgated, *d_o, *dqkv, *dmod_e, *dmod_t, *sc;   // per-stream temporaries, reused
   float* gain_part;             // per-workgroup partial sums of the q/k gain gradients
   char *attn_ws, *norm_ws, *colsum_ws, *gemm_ws;
   size_t attn_ws_bytes, gemm_ws_bytes;
@@ -128,7 +128,7 @@ size_t max_gemm_scratch(const MDims& m, int dtype) {
     v = gemm_scratch_bytes(GEMM_TN, m.QKV, m.d, T, dtype); b = v > b ? v : b;
   }
   v = gemm_scratch_bytes(GEMM_TN, 6 * m.d, m.d, m.S, dtype); b = v > b ? v : b;
-  v = gemm_scratch_bytes(GEMM_NN, m.S, m.d, 6 * m.d, dtype); b = v > b ? v : b;
+  v = gemm_scratch_bytes(GEMM_TN, (int)align_up(m.S, 8), m.d, 6 * m.d, dtype); b = v > b ? v : b;
   return b;
 }
 
@@ -139,7 +139,7 @@ MBwd layout_bwd(const MDims& m, int dtype, void* base) {
   for (int s = 0; s < 2; ++s) {
     w.dx1[s] = a.take<char>((size_t)m.Ts[s] * m.d * m.es);
     w.dmod[s] = a.take<float>((size_t)m.S * 6 * m.d * sizeof(float));
-    w.dsc[s] = a.take<float>((size_t)m.S * m.d * sizeof(float));
+    w.dsc[s] = a.take<float>(align_up(m.S, 8) * m.d * sizeof(float));
   }
   w.d_o_j = a.take<char>((size_t)m.T * m.QD * m.es);
   w.dqkv_j = a.take<char>((size_t)m.T * m.QKV * m.es);
@@ -153,6 +153,7 @@ MBwd layout_bwd(const MDims& m, int dtype, void* base) {
   w.d_o = a.take<char>(R * m.QD * m.es);
   w.dqkv = a.take<char>(R * m.QKV * m.es);
   w.dmod_e = a.take<char>((size_t)m.S * 6 * m.d * m.es);
+  w.dmod_t = a.take<char>(align_up(m.S, 8) * 6 * m.d * m.es);
   w.sc = a.take<char>((size_t)m.S * m.d * m.es);
   w.gain_part = a.take<float>((size_t)QKN_BLOCKS * 2 * m.dh * sizeof(float));
   w.attn_ws_bytes = attention_backward_scratch_bytes(m.H, m.H, m.dh, m.T);
@@ -608,9 +609,9 @@ extern "C" bm_status bm_mmdit_backward(const bm_mmdit_desc* desc, const bm_mmdit
     const int32_t* tok = ws.tb.tok_seq[s];
     float* dmod = ws.dmod[s];
     // y = x1 + g2 * m,  m = a W_down^T + b_down
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
-      BM_RETURN_IF(segment_colsum(dt, dy[s], q.m, d, d, cu_dev[s], S, dmod + 5 * d, 6 * d, st));
-      BM_RETURN_IF(gate_mul(dt, dy[s], q.mod + 5 * d, 6 * d, tok, nullptr, ws.dgated, T, d, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 3.0 * T * d * (double)m.es, st);
+      BM_RETURN_IF(segment_gate(dt, dy[s], q.m, q.mod + 5 * d, 6 * d, ws.dgated, cu_dev[s], S, d, dmod + 5 * d, 6 * d,
+                                ws.norm_ws, st)); }
     BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, ws.dgated, d, p.w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
     { ProfScope _p(PROF_ELEMENTWISE, (double)T * 4.0 * m.F * (double)m.es, st);
       BM_RETURN_IF(act_backward(dt, BM_ACT_GELU, q.up, ws.da, ws.dup, ws.a, (float*)g.b_up, ws.colsum_ws, T, m.F, st)); }
@@ -625,9 +626,9 @@ extern "C" bm_status bm_mmdit_backward(const bm_mmdit_desc* desc, const bm_mmdit
                                  nullptr, nullptr, nullptr, nullptr, dmod, cu_dev[s], S, ws.norm_ws, st)); }
     BM_RETURN_IF(gemm(GEMM_TN, dt, m.F, d, T, ws.dup, m.F, ws.h, d, g.w_up, d, none, ws.gemm_ws, ws.gemm_ws_bytes, st));
     // x1 = x + g1 * attn,  attn = o W_o^T + b_o
-    { ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
-      BM_RETURN_IF(segment_colsum(dt, ws.dx1[s], q.attn, d, d, cu_dev[s], S, dmod + 2 * d, 6 * d, st));
-      BM_RETURN_IF(gate_mul(dt, ws.dx1[s], q.mod + 2 * d, 6 * d, tok, nullptr, ws.dgated, T, d, st)); }
+    { ProfScope _p(PROF_ELEMENTWISE, 3.0 * T * d * (double)m.es, st);
+      BM_RETURN_IF(segment_gate(dt, ws.dx1[s], q.attn, q.mod + 2 * d, 6 * d, ws.dgated, cu_dev[s], S, d, dmod + 2 * d,
+                                6 * d, ws.norm_ws, st)); }
     BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.QD, T, ws.dgated, d, q.o, m.QD, g.w_o, m.QD, none, ws.gemm_ws,
                       ws.gemm_ws_bytes, st));
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
@@ -673,8 +674,12 @@ extern "C" bm_status bm_mmdit_backward(const bm_mmdit_desc* desc, const bm_mmdit
                       ws.gemm_ws_bytes, st));
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st);
       BM_RETURN_IF(colsum_accumulate(dt, ws.dmod_e, 6 * d, S, 6 * d, (float*)g.b_ada, ws.colsum_ws, st)); }
-    GemmEpilogue e; e.out_fp32 = 1;
-    BM_RETURN_IF(gemm(GEMM_NN, dt, S, d, 6 * d, ws.dmod_e, 6 * d, p.w_ada, d, ws.dsc[s], d, e, ws.gemm_ws,
+    // d silu(cond) = dmod W_ada as a weight-gradient style product on the transposed dmod
+    // (few rows, long reduction: the k range splits over the chip)
+    const int S8 = (int)align_up(S, 8);
+    BM_RETURN_IF(cast_transpose_from_f32(dt, dmod, ws.dmod_t, S, 6 * d, S8, st));
+    BM_RETURN_IF(fill_zero(ws.dsc[s], (size_t)S8 * d * sizeof(float), st));
+    BM_RETURN_IF(gemm(GEMM_TN, dt, S8, d, 6 * d, ws.dmod_t, S8, p.w_ada, d, ws.dsc[s], d, none, ws.gemm_ws,
                       ws.gemm_ws_bytes, st));
   }
   // both streams read the same conditioning rows

@@ -24,6 +24,10 @@ GEMM_SHAPES = [
     (2048, 1024, 1000 * 8), (40, 64, 24), (515, 640, 1096),
     # skinny outputs with a long contraction (k ranges split over workgroups)
     (32, 1152, 6912), (5, 200, 3001),
+    # few rows against wide weights (the per-sample modulation products): few output rows,
+    # and for the weight-gradient layout also a contraction of only a few rows
+    (16, 1152, 1152), (1, 64, 64), (33, 200, 136), (16, 512, 2048), (640, 384, 16), (8, 64, 64),
+    (64, 64, 8), (24, 3072, 4608),
 ]
 
 
