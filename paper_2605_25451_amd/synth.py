@@ -235,6 +235,25 @@ def cu_from_lengths(lens) -> np.ndarray:
     return cu
 
 
+def context_chunks(cu, C: int):
+    """Partition of every packed sequence into C contiguous position ranges (the token layout of a
+    context-parallel group of C ranks): chunk c of a sequence of length L holds its positions
+    [c*L // C, (c+1)*L // C).  Returns, per chunk, (rows, cu_c): the rows of the full pack that
+    the chunk holds, in order, and the offsets of the chunk's own packed layout (one entry per
+    sequence; a short sequence leaves some chunks empty)."""
+    cu = np.asarray(cu, dtype=np.int64)
+    out = []
+    for c in range(C):
+        rows, lens = [], []
+        for s in range(len(cu) - 1):
+            L = int(cu[s + 1] - cu[s])
+            a, b = c * L // C, (c + 1) * L // C
+            rows.append(np.arange(cu[s] + a, cu[s] + b, dtype=np.int64))
+            lens.append(b - a)
+        out.append((np.concatenate(rows) if rows else np.zeros(0, dtype=np.int64), cu_from_lengths(lens)))
+    return out
+
+
 # --------------------------------------------------------------------------
 # one block's inputs
 # --------------------------------------------------------------------------
