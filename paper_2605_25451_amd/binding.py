@@ -179,6 +179,17 @@ def lib() -> C.CDLL:
                                         vp, vp, sz, vp]
         for name in ("bm_mmdit_sizes", "bm_mmdit_forward", "bm_mmdit_backward"):
             getattr(l, name).restype = C.c_int
+        i64 = C.c_int64
+        l.bm_cp_attention_forward.argtypes = [i32] * 5 + [vp, i32, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+        l.bm_cp_attention_merge.argtypes = [i32] * 5 + [C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
+        l.bm_cp_attention_backward_scratch_bytes.argtypes = [i32] * 5
+        l.bm_cp_attention_backward_scratch_bytes.restype = sz
+        l.bm_cp_attention_backward.argtypes = ([i32] * 5 + [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, i32,
+                                                            vp, i32, vp, vp, i32, vp, sz, vp])
+        l.bm_cp_sum_parts.argtypes = [i32, i64, i32, C.POINTER(vp), vp, vp]
+        for name in ("bm_cp_attention_forward", "bm_cp_attention_merge", "bm_cp_attention_backward",
+                     "bm_cp_sum_parts"):
+            getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
 
@@ -322,6 +333,48 @@ def attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, c
                                        cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
                                        _ptr(dv), ld_dqkv, _ptr(scratch), scratch_bytes,
                                        _stream() if stream is None else stream))
+
+
+def _ptr_array(tensors):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def cp_attention_forward(dtype, mask, Hq, Hkv, dh, q, ld_q, k, v, ld_kv, cu_q_dev, cu_q_host, cu_k_dev,
+                         cu_k_host, S, o_part, lse_part, stream=None):
+    cq, ck = _host_cu(cu_q_host), _host_cu(cu_k_host)
+    _check(lib().bm_cp_attention_forward(dtype, mask, Hq, Hkv, dh, _ptr(q), ld_q, _ptr(k), _ptr(v), ld_kv,
+                                         _ptr(cu_q_dev), cq.ctypes.data, _ptr(cu_k_dev), ck.ctypes.data, S,
+                                         _ptr(o_part), _ptr(lse_part),
+                                         _stream() if stream is None else stream))
+
+
+def cp_attention_merge(dtype, Hq, dh, Tq, o_parts, lse_parts, o, lse, stream=None):
+    _check(lib().bm_cp_attention_merge(dtype, Hq, dh, Tq, len(o_parts), _ptr_array(o_parts),
+                                       _ptr_array(lse_parts), _ptr(o), _ptr(lse),
+                                       _stream() if stream is None else stream))
+
+
+def cp_attention_backward_scratch_bytes(Hq, Hkv, dh, Tq, Tk) -> int:
+    return lib().bm_cp_attention_backward_scratch_bytes(Hq, Hkv, dh, Tq, Tk)
+
+
+def cp_attention_backward(dtype, mask, Hq, Hkv, dh, q, ld_q, k, v, ld_kv, o, d_o, lse, cu_q_dev, cu_q_host,
+                          cu_k_dev, cu_k_host, S, dq_part, ld_dq, dk_part, dv_part, ld_dkv, scratch,
+                          scratch_bytes, stream=None):
+    cq, ck = _host_cu(cu_q_host), _host_cu(cu_k_host)
+    _check(lib().bm_cp_attention_backward(dtype, mask, Hq, Hkv, dh, _ptr(q), ld_q, _ptr(k), _ptr(v), ld_kv,
+                                          _ptr(o), _ptr(d_o), _ptr(lse), _ptr(cu_q_dev), cq.ctypes.data,
+                                          _ptr(cu_k_dev), ck.ctypes.data, S, _ptr(dq_part), ld_dq,
+                                          _ptr(dk_part), _ptr(dv_part), ld_dkv, _ptr(scratch), scratch_bytes,
+                                          _stream() if stream is None else stream))
+
+
+def cp_sum_parts(dtype, n, parts, out, stream=None):
+    _check(lib().bm_cp_sum_parts(dtype, n, len(parts), _ptr_array(parts), _ptr(out),
+                                 _stream() if stream is None else stream))
 
 
 def probe_mfma(blocks, iters, out, stream=None):

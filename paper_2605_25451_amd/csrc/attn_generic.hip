@@ -17,13 +17,14 @@ constexpr int BT = 32;    // rows of the streamed tile
 
 template <typename T, int DH, bool CAUSAL>
 __global__ __launch_bounds__(BQ) void attn_fwd_generic_kernel(
-    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld,
-    const int32_t* __restrict__ cu, T* __restrict__ o, int ldo, float* __restrict__ lse, int Ttot,
-    int group, float scale) {
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld, int ldk,
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk, T* __restrict__ o, int ldo,
+    float* __restrict__ lse, int Ttot, int group, float scale) {
   __shared__ float Ks[BT][DH];
   __shared__ float Vs[BT][DH];
   const int s = blockIdx.y, hq = blockIdx.z, hk = hq / group;
   const int lo = cu[s], L = cu[s + 1] - lo;
+  const int lok = cuk[s], Lk = cuk[s + 1] - lok;     // keys/values may be packed on their own
   const int q0 = blockIdx.x * BQ;
   if (q0 >= L) return;
   const int qi = q0 + threadIdx.x;
@@ -35,13 +36,13 @@ __global__ __launch_bounds__(BQ) void attn_fwd_generic_kernel(
     acc[c] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
-  const int kend = CAUSAL ? min(L, q0 + BQ) : L;
+  const int kend = CAUSAL ? min(Lk, q0 + BQ) : Lk;
   for (int k0 = 0; k0 < kend; k0 += BT) {
     for (int idx = threadIdx.x; idx < BT * DH; idx += BQ) {
       int r = idx / DH, c = idx % DH, kj = k0 + r;
-      bool ok = kj < L;
-      Ks[r][c] = ok ? Elt<T>::to_f(k[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
-      Vs[r][c] = ok ? Elt<T>::to_f(v[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
+      bool ok = kj < Lk;
+      Ks[r][c] = ok ? Elt<T>::to_f(k[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
+      Vs[r][c] = ok ? Elt<T>::to_f(v[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
     }
     __syncthreads();
     if (active) {
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(BQ) void attn_fwd_generic_kernel(
         float d = 0.f;
 #pragma unroll
         for (int c = 0; c < DH; ++c) d = fmaf(qr[c], Ks[j][c], d);
-        bool ok = kj < L && (!CAUSAL || kj <= qi);
+        bool ok = kj < Lk && (!CAUSAL || kj <= qi);
         sc[j] = ok ? d : -INFINITY;
         tmax = fmaxf(tmax, sc[j]);
       }
@@ -76,11 +77,11 @@ __global__ __launch_bounds__(BQ) void attn_fwd_generic_kernel(
     __syncthreads();
   }
   if (active) {
-    float inv = 1.0f / l;
+    float inv = l > 0.f ? 1.0f / l : 0.f;       // no visible key in this chunk: o = 0, lse = -inf
 #pragma unroll
     for (int c = 0; c < DH; ++c)
       o[(size_t)(lo + qi) * ldo + hq * DH + c] = Elt<T>::from_f(acc[c] * inv);
-    lse[(size_t)hq * Ttot + lo + qi] = m + logf(l);
+    lse[(size_t)hq * Ttot + lo + qi] = l > 0.f ? m + logf(l) : -INFINITY;
   }
 }
 
@@ -100,14 +101,15 @@ __global__ void attn_delta_kernel(const T* __restrict__ o, const T* __restrict__
 
 template <typename T, int DH, bool CAUSAL>
 __global__ __launch_bounds__(BQ) void attn_dq_generic_kernel(
-    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld,
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld, int ldk,
     const T* __restrict__ d_o, int ldo, const float* __restrict__ lse,
-    const float* __restrict__ delta, const int32_t* __restrict__ cu, T* __restrict__ dq, int ldd,
-    int Ttot, int group, float scale) {
+    const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
+    T* __restrict__ dq, int ldd, int Ttot, int group, float scale) {
   __shared__ float Ks[BT][DH];
   __shared__ float Vs[BT][DH];
   const int s = blockIdx.y, hq = blockIdx.z, hk = hq / group;
   const int lo = cu[s], L = cu[s + 1] - lo;
+  const int lok = cuk[s], Lk = cuk[s + 1] - lok;
   const int q0 = blockIdx.x * BQ;
   if (q0 >= L) return;
   const int qi = q0 + threadIdx.x;
@@ -121,19 +123,19 @@ __global__ __launch_bounds__(BQ) void attn_dq_generic_kernel(
   }
   const float my_lse = active ? lse[(size_t)hq * Ttot + lo + qi] : 0.f;
   const float my_delta = active ? delta[(size_t)hq * Ttot + lo + qi] : 0.f;
-  const int kend = CAUSAL ? min(L, q0 + BQ) : L;
+  const int kend = CAUSAL ? min(Lk, q0 + BQ) : Lk;
   for (int k0 = 0; k0 < kend; k0 += BT) {
     for (int idx = threadIdx.x; idx < BT * DH; idx += BQ) {
       int r = idx / DH, c = idx % DH, kj = k0 + r;
-      bool ok = kj < L;
-      Ks[r][c] = ok ? Elt<T>::to_f(k[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
-      Vs[r][c] = ok ? Elt<T>::to_f(v[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
+      bool ok = kj < Lk;
+      Ks[r][c] = ok ? Elt<T>::to_f(k[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
+      Vs[r][c] = ok ? Elt<T>::to_f(v[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
     }
     __syncthreads();
     if (active) {
       for (int j = 0; j < BT; ++j) {
         int kj = k0 + j;
-        if (kj >= L || (CAUSAL && kj > qi)) break;
+        if (kj >= Lk || (CAUSAL && kj > qi)) break;
         float sc = 0.f, dp = 0.f;
 #pragma unroll
         for (int c = 0; c < DH; ++c) {
@@ -158,24 +160,27 @@ __global__ __launch_bounds__(BQ) void attn_dq_generic_kernel(
 // tiles are walked in a fixed order, so dk/dv sums are reproducible.
 template <typename T, int DH, bool CAUSAL>
 __global__ __launch_bounds__(BQ) void attn_dkdv_generic_kernel(
-    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld,
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int ld, int ldk,
     const T* __restrict__ d_o, int ldo, const float* __restrict__ lse,
-    const float* __restrict__ delta, const int32_t* __restrict__ cu, T* __restrict__ dk,
-    T* __restrict__ dv, int ldd, int Ttot, int group, float scale) {
+    const float* __restrict__ delta, const int32_t* __restrict__ cuq, const int32_t* __restrict__ cuk,
+    T* __restrict__ dk, T* __restrict__ dv, int ldd, int Ttot, int group, float scale) {
+  // this thread's key row lives in the key/value packing (cuk, ldk); queries, dO, lse and
+  // delta (Ttot rows per head) in the queries' packing (cuq, ld)
   __shared__ float Qs[BT][DH];
   __shared__ float Ds[BT][DH];
   __shared__ float Ls[BT], Dl[BT];
   const int s = blockIdx.y, hk = blockIdx.z;
-  const int lo = cu[s], L = cu[s + 1] - lo;
+  const int lok = cuk[s], Lk = cuk[s + 1] - lok;
+  const int lo = cuq[s], L = cuq[s + 1] - lo;
   const int kb = blockIdx.x * BQ;
-  if (kb >= L) return;
+  if (kb >= Lk) return;
   const int kj = kb + threadIdx.x;
-  const bool active = kj < L;
+  const bool active = kj < Lk;
   float kr[DH], vr[DH], dkr[DH], dvr[DH];
 #pragma unroll
   for (int c = 0; c < DH; ++c) {
-    kr[c] = active ? Elt<T>::to_f(k[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
-    vr[c] = active ? Elt<T>::to_f(v[(size_t)(lo + kj) * ld + hk * DH + c]) : 0.f;
+    kr[c] = active ? Elt<T>::to_f(k[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
+    vr[c] = active ? Elt<T>::to_f(v[(size_t)(lok + kj) * ldk + hk * DH + c]) : 0.f;
     dkr[c] = 0.f; dvr[c] = 0.f;
   }
   const int qstart = CAUSAL ? (kb / BT) * BT : 0;
@@ -221,8 +226,8 @@ __global__ __launch_bounds__(BQ) void attn_dkdv_generic_kernel(
   if (active) {
 #pragma unroll
     for (int c = 0; c < DH; ++c) {
-      dk[(size_t)(lo + kj) * ldd + hk * DH + c] = Elt<T>::from_f(dkr[c]);
-      dv[(size_t)(lo + kj) * ldd + hk * DH + c] = Elt<T>::from_f(dvr[c]);
+      dk[(size_t)(lok + kj) * ldd + hk * DH + c] = Elt<T>::from_f(dkr[c]);
+      dv[(size_t)(lok + kj) * ldd + hk * DH + c] = Elt<T>::from_f(dvr[c]);
     }
   }
 }
@@ -231,8 +236,8 @@ template <typename T, int DH, bool CAUSAL>
 bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
   dim3 grid(cdiv(a.max_seqlen, BQ), a.S, a.Hq);
   hipLaunchKernelGGL((attn_fwd_generic_kernel<T, DH, CAUSAL>), grid, dim3(BQ), 0, st, (const T*)a.q,
-                     (const T*)a.k, (const T*)a.v, a.ld_qkv, a.cu_dev, (T*)o, a.Hq * a.dh, lse, a.T,
-                     a.Hq / a.Hkv, 1.0f / sqrtf((float)a.dh));
+                     (const T*)a.k, (const T*)a.v, a.ld_qkv, a.kv_ld(), a.cu_dev, a.kv_cu_dev(), (T*)o,
+                     a.Hq * a.dh, lse, a.T, a.Hq / a.Hkv, 1.0f / sqrtf((float)a.dh));
   BM_CHECK_LAUNCH("attn_fwd_generic");
   return BM_OK;
 }
@@ -243,15 +248,20 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const int ldo = a.Hq * a.dh;
   const float scale = 1.0f / sqrtf((float)a.dh);
   long n = (long)a.T * a.Hq;
-  hipLaunchKernelGGL((attn_delta_kernel<T, DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const T*)o,
-                     (const T*)d_o, ldo, delta, a.T, a.Hq);
-  hipLaunchKernelGGL((attn_dq_generic_kernel<T, DH, CAUSAL>), dim3(cdiv(a.max_seqlen, BQ), a.S, a.Hq),
-                     dim3(BQ), 0, st, (const T*)a.q, (const T*)a.k, (const T*)a.v, a.ld_qkv,
-                     (const T*)d_o, ldo, lse, delta, a.cu_dev, (T*)dq, ldd, a.T, a.Hq / a.Hkv, scale);
-  hipLaunchKernelGGL((attn_dkdv_generic_kernel<T, DH, CAUSAL>),
-                     dim3(cdiv(a.max_seqlen, BQ), a.S, a.Hkv), dim3(BQ), 0, st, (const T*)a.q,
-                     (const T*)a.k, (const T*)a.v, a.ld_qkv, (const T*)d_o, ldo, lse, delta, a.cu_dev,
-                     (T*)dk, (T*)dv, ldd, a.T, a.Hq / a.Hkv, scale);
+  if (n > 0) {
+    hipLaunchKernelGGL((attn_delta_kernel<T, DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const T*)o,
+                       (const T*)d_o, ldo, delta, a.T, a.Hq);
+    hipLaunchKernelGGL((attn_dq_generic_kernel<T, DH, CAUSAL>), dim3(cdiv(a.max_seqlen, BQ), a.S, a.Hq),
+                       dim3(BQ), 0, st, (const T*)a.q, (const T*)a.k, (const T*)a.v, a.ld_qkv, a.kv_ld(),
+                       (const T*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), (T*)dq, ldd, a.T,
+                       a.Hq / a.Hkv, scale);
+  }
+  if (a.kv_T() > 0)
+    hipLaunchKernelGGL((attn_dkdv_generic_kernel<T, DH, CAUSAL>),
+                       dim3(cdiv(a.kv_max_len(), BQ), a.S, a.Hkv), dim3(BQ), 0, st, (const T*)a.q,
+                       (const T*)a.k, (const T*)a.v, a.ld_qkv, a.kv_ld(), (const T*)d_o, ldo, lse, delta,
+                       a.cu_dev, a.kv_cu_dev(), (T*)dk, (T*)dv, a.ld_dkv ? a.ld_dkv : ldd, a.T,
+                       a.Hq / a.Hkv, scale);
   BM_CHECK_LAUNCH("attn_bwd_generic");
   return BM_OK;
 }
@@ -286,7 +296,7 @@ bm_status attention_forward_generic(const AttnArgs& a, void* o, float* lse, hipS
 bm_status attention_backward_generic(const AttnArgs& a, const void* o, const void* d_o,
                                      const float* lse, void* dq, void* dk, void* dv, int ldd,
                                      float* delta, hipStream_t st) {
-  if (a.T == 0) return BM_OK;
+  if (a.T == 0 && a.kv_T() == 0) return BM_OK;
 #define BM_CALL(D)                                                                             \
   if (a.dtype == BM_DTYPE_BF16)                                                                \
     return a.causal ? bwd_launch<bf16_t, D, true>(a, o, d_o, lse, dq, dk, dv, ldd, delta, st)  \

@@ -161,8 +161,9 @@ constexpr int FK = 64;    // keys per step
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
-    const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ o, int ldo, float* __restrict__ lse,
-    int Ttot, int Hq, int group, float scale_log2) {
+    int ldk, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk, int S,
+    bf16_t* __restrict__ o, int ldo, float* __restrict__ lse, int Ttot, int Hq, int group,
+    float scale_log2) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
   int seq, qt, nqt, tile_id, hq;
@@ -170,11 +171,25 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
   const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
+  // keys and values may be packed on their own (a chunk of a context-parallel partition)
+  const int lok = cuk[seq], Lk = cuk[seq + 1] - lok;
   const int q0 = qt * FQ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5;
   const int qpos = q0 + wave * 32 + (lane & 31);          // this lane's query (column of S^T)
   const int qrow = min(qpos, L - 1);
+  if (Lk == 0) {
+    // no key in this chunk (workgroup-uniform): zero output, lse = -inf
+    if (qpos < L) {
+      bf16_t* op = o + (size_t)(lo + qpos) * ldo + hq * DH;
+      for (int c = half * (DH / 2); c < (half + 1) * (DH / 2); c += 4) {
+        bf16x4 z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+        *reinterpret_cast<bf16x4*>(op + c) = z;
+      }
+      if (half == 0) lse[(size_t)hq * Ttot + lo + qpos] = -INFINITY;
+    }
+    return;
+  }
 
   bf16x8 qf[HeadDim<DH>::KS];
   {
@@ -189,13 +204,13 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     for (int r = 0; r < 16; ++r) oacc[j][r] = 0.f;
   float m = -INFINITY, lsum = 0.f;
 
-  const int kend = CAUSAL ? min(L, q0 + FQ) : L;
+  const int kend = CAUSAL ? min(Lk, q0 + FQ) : Lk;
   const int nkt = (kend + FK - 1) / FK;
-  const bf16_t* kbase = k + (size_t)lo * ld + hk * DH;
-  const bf16_t* vbase = v + (size_t)lo * ld + hk * DH;
+  const bf16_t* kbase = k + (size_t)lok * ldk + hk * DH;
+  const bf16_t* vbase = v + (size_t)lok * ldk + hk * DH;
   TileStage<FK, DH, 256> sk, sv;
-  sk.load(kbase, ld, 0, L, tid);
-  sv.load(vbase, ld, 0, L, tid);
+  sk.load(kbase, ldk, 0, Lk, tid);
+  sv.load(vbase, ldk, 0, Lk, tid);
 
   for (int kt = 0; kt < nkt; ++kt) {
     __syncthreads();                       // previous step's readers are done
@@ -203,8 +218,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     sv.store(Vs, tid);
     __syncthreads();
     if (kt + 1 < nkt) {
-      sk.load(kbase, ld, (kt + 1) * FK, L, tid);
-      sv.load(vbase, ld, (kt + 1) * FK, L, tid);
+      sk.load(kbase, ldk, (kt + 1) * FK, Lk, tid);
+      sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
     }
     const int key0 = kt * FK;
     // S^T = K Q^T for both 32-key blocks first: the MFMAs of block 1 run while the
@@ -221,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
                                                           sacc[b], 0, 0, 0);
     }
     // mask: keys past the sequence end, and keys after the query under a causal mask
-    const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
+    const bool need_mask = (key0 + FK > Lk) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
       float mx = -INFINITY;
@@ -229,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
       for (int r = 0; r < 16; ++r) {
         if (need_mask) {
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          if (key >= L || (CAUSAL && key > qpos)) sacc[b][r] = -INFINITY;
+          if (key >= Lk || (CAUSAL && key > qpos)) sacc[b][r] = -INFINITY;
         }
         mx = fmaxf(mx, sacc[b][r]);
       }
@@ -291,11 +306,12 @@ int count_tiles(const int32_t* cu_host, int S, int rows) {
 template <int DH>
 bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
   dim3 grid(count_tiles(a.cu_host, a.S, FQ) * a.Hq), block(256);
+  if (grid.x == 0) return BM_OK;
   const float sl2 = LOG2E / sqrtf((float)a.dh);
 #define BM_L(C)                                                                                  \
   hipLaunchKernelGGL((fa_fwd_kernel<DH, C>), grid, block, 0, st, (const bf16_t*)a.q,             \
-                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.cu_dev, a.S, (bf16_t*)o, \
-                     a.Hq * a.dh, lse, a.T, a.Hq, a.Hq / a.Hkv, sl2)
+                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(), a.cu_dev,      \
+                     a.kv_cu_dev(), a.S, (bf16_t*)o, a.Hq * a.dh, lse, a.T, a.Hq, a.Hq / a.Hkv, sl2)
   if (a.causal) BM_L(true); else BM_L(false);
 #undef BM_L
   BM_CHECK_LAUNCH("fa_fwd");
@@ -333,10 +349,12 @@ constexpr int BK_Q = 64;       // query rows per step
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
-    const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
-    const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dk,
-    bf16_t* __restrict__ dv, int ldd, int Ttot, int Hkv, int group, float scale, float scale_log2,
-    int gsplit, float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
+    int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
+    const float* __restrict__ delta, const int32_t* __restrict__ cuq, const int32_t* __restrict__ cu,
+    int S, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int ldd, int Tq, int Ttot, int Hkv, int group,
+    float scale, float scale_log2, int gsplit,
+    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
+  // cu, Ttot, ldk: the packing of the keys/values (and of dk, dv); cuq, Tq, ld: of the queries
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
@@ -352,6 +370,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
   kt = nkt - 1 - kt;                                   // early key tiles see the most queries
   const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int loq = cuq[seq], Lq = cuq[seq + 1] - loq;
   const int kb0 = kt * BK_KEYS;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const int kpos = kb0 + wave * 32 + (lane & 31);       // this lane's key (column of S)
@@ -359,8 +378,8 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 
   bf16x8 kf[HeadDim<DH>::KS], vf[HeadDim<DH>::KS];
   {
-    const bf16_t* kp = k + (size_t)(lo + krow) * ld + hk * DH;
-    const bf16_t* vp = v + (size_t)(lo + krow) * ld + hk * DH;
+    const bf16_t* kp = k + (size_t)(lo + krow) * ldk + hk * DH;
+    const bf16_t* vp = v + (size_t)(lo + krow) * ldk + hk * DH;
 #pragma unroll
     for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
       kf[ks] = load_chunk<DH>(kp, ks * 2 + half);
@@ -374,22 +393,22 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     for (int r = 0; r < 16; ++r) { dkacc[j][r] = 0.f; dvacc[j][r] = 0.f; }
 
   const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
-  const int nqt = (L - qstart + BK_Q - 1) / BK_Q;
+  const int nqt = Lq > qstart ? (Lq - qstart + BK_Q - 1) / BK_Q : 0;   // no query: dk = dv = 0
   const int iters = nqt * gpart;
   TileStage<BK_Q, DH, 256> sq, sd;
   float st_l = 0.f, st_d = 0.f;
   auto fetch = [&](int it) {
     const int hq = hk * group + gs * gpart + it / nqt;
     const int q0 = qstart + (it % nqt) * BK_Q;
-    sq.load(q + (size_t)lo * ld + hq * DH, ld, q0, L, tid);
-    sd.load(d_o + (size_t)lo * ldo + hq * DH, ldo, q0, L, tid);
+    sq.load(q + (size_t)loq * ld + hq * DH, ld, q0, Lq, tid);
+    sd.load(d_o + (size_t)loq * ldo + hq * DH, ldo, q0, Lq, tid);
     if (tid < BK_Q) {
-      const int qi = min(q0 + tid, L - 1);
-      st_l = lse[(size_t)hq * Ttot + lo + qi] * LOG2E;
-      st_d = delta[(size_t)hq * Ttot + lo + qi];
+      const int qi = min(q0 + tid, Lq - 1);
+      st_l = lse[(size_t)hq * Tq + loq + qi] * LOG2E;
+      st_d = delta[(size_t)hq * Tq + loq + qi];
     }
   };
-  fetch(0);
+  if (iters > 0) fetch(0);
   for (int it = 0; it < iters; ++it) {
     __syncthreads();
     sq.store(Qs, tid);
@@ -398,7 +417,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     __syncthreads();
     if (it + 1 < iters) fetch(it + 1);
     const int q0 = qstart + (it % nqt) * BK_Q;
-    const bool need_mask = (q0 + BK_Q > L) || (kb0 + BK_KEYS > L) ||
+    const bool need_mask = (q0 + BK_Q > Lq) || (kb0 + BK_KEYS > L) ||
                            (CAUSAL && q0 < kb0 + wave * 32 + 32);
     // S = Q K^T and dP = dO V^T for both 32-query blocks first, then per block the
     // softmax arithmetic (under the other block's MFMAs) followed by its dV / dK MFMAs.
@@ -426,7 +445,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
           float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][r], scale_log2, -l4[e]));
           if (need_mask) {
             const int qi = q0 + qoff + e;
-            if (qi >= L || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
+            if (qi >= Lq || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
           }
           sacc[qb][r] = p;
           dpacc[qb][r] = p * (dpacc[qb][r] - d4[e]);
@@ -483,9 +502,9 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
-    const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
-    const float* __restrict__ delta, const int32_t* __restrict__ cu, int S, bf16_t* __restrict__ dq,
-    int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
+    int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
+    const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
+    int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
   int seq, qt, nqt, tile_id, hq;
@@ -493,10 +512,22 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
   const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int lok = cuk[seq], Lk = cuk[seq + 1] - lok;
   const int q0 = qt * FQ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const int qpos = q0 + wave * 32 + (lane & 31);
   const int qrow = min(qpos, L - 1);
+  if (Lk == 0) {
+    // no key in this chunk (workgroup-uniform): dq = 0
+    if (qpos < L) {
+      bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
+      for (int c = half * (DH / 2); c < (half + 1) * (DH / 2); c += 4) {
+        bf16x4 z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+        *reinterpret_cast<bf16x4*>(pq + c) = z;
+      }
+    }
+    return;
+  }
 
   bf16x8 qf[HeadDim<DH>::KS], dof[HeadDim<DH>::KS];
   {
@@ -516,24 +547,24 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqacc[j][r] = 0.f;
 
-  const int kend = CAUSAL ? min(L, q0 + FQ) : L;
+  const int kend = CAUSAL ? min(Lk, q0 + FQ) : Lk;
   const int nkt = (kend + FK - 1) / FK;
-  const bf16_t* kbase = k + (size_t)lo * ld + hk * DH;
-  const bf16_t* vbase = v + (size_t)lo * ld + hk * DH;
+  const bf16_t* kbase = k + (size_t)lok * ldk + hk * DH;
+  const bf16_t* vbase = v + (size_t)lok * ldk + hk * DH;
   TileStage<FK, DH, 256> sk, sv;
-  sk.load(kbase, ld, 0, L, tid);
-  sv.load(vbase, ld, 0, L, tid);
+  sk.load(kbase, ldk, 0, Lk, tid);
+  sv.load(vbase, ldk, 0, Lk, tid);
   for (int kt = 0; kt < nkt; ++kt) {
     __syncthreads();
     sk.store(Ks, tid);
     sv.store(Vs, tid);
     __syncthreads();
     if (kt + 1 < nkt) {
-      sk.load(kbase, ld, (kt + 1) * FK, L, tid);
-      sv.load(vbase, ld, (kt + 1) * FK, L, tid);
+      sk.load(kbase, ldk, (kt + 1) * FK, Lk, tid);
+      sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
     }
     const int key0 = kt * FK;
-    const bool need_mask = (key0 + FK > L) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
+    const bool need_mask = (key0 + FK > Lk) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
     f32x16 sacc[FK / 32], dpacc[FK / 32];
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
@@ -552,7 +583,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
         float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], scale_log2, -my_lse));
         if (need_mask) {
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          if (key >= L || (CAUSAL && key > qpos)) p = 0.f;
+          if (key >= Lk || (CAUSAL && key > qpos)) p = 0.f;
         }
         dpacc[b][r] = p * (dpacc[b][r] - my_delta);
       }
@@ -613,29 +644,36 @@ template <int DH>
 bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const float* lse, void* dq,
                      void* dk, void* dv, int ldd, float* delta, hipStream_t st) {
   const int ldo = a.Hq * a.dh;
+  const int ldd_kv = a.ld_dkv ? a.ld_dkv : ldd;
   const float scale = 1.0f / sqrtf((float)a.dh);
   const float sl2 = scale * LOG2E;
   const long n = (long)a.T * a.Hq;
-  hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
-                     (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
-  const int ktiles = count_tiles(a.cu_host, a.S, BK_KEYS);
-  const int gsplit = dkdv_group_split(ktiles, a.Hkv, a.Hq / a.Hkv);
+  if (n > 0)
+    hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
+                       (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
+  const int ktiles = count_tiles(a.kv_cu_host(), a.S, BK_KEYS);
+  const int gsplit = ktiles > 0 ? dkdv_group_split(ktiles, a.Hkv, a.Hq / a.Hkv) : 1;
   float* part = delta + align_up((size_t)a.Hq * a.T, 64);      // after the delta plane
+  const int Tk = a.kv_T();
   dim3 gkv(ktiles * a.Hkv * gsplit), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
 #define BM_L(C)                                                                                  \
-  hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,      \
-                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
-                     lse, delta, a.cu_dev, a.S, (bf16_t*)dk, (bf16_t*)dv, ldd, a.T, a.Hkv,       \
-                     a.Hq / a.Hkv, scale, sl2, gsplit, part);                                    \
-  hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,        \
-                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, (const bf16_t*)d_o, ldo,  \
-                     lse, delta, a.cu_dev, a.S, (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2)
+  if (ktiles > 0)                                                                                \
+    hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,    \
+                       (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
+                       (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
+                       (bf16_t*)dk, (bf16_t*)dv, ldd_kv, a.T, Tk, a.Hkv, a.Hq / a.Hkv, scale, sl2, \
+                       gsplit, part);                                                            \
+  if (gq.x > 0)                                                                                  \
+    hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,      \
+                       (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
+                       (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
+                       (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2)
   if (a.causal) { BM_L(true); } else { BM_L(false); }
 #undef BM_L
-  if (gsplit > 1) {
-    const long n4 = (long)a.T * a.Hkv * a.dh / 4;
-    hipLaunchKernelGGL(fa_dkdv_reduce_kernel, dim3(cdiv(n4, 256)), dim3(256), 0, st, part, gsplit, a.T,
-                       a.Hkv * a.dh, (bf16_t*)dk, (bf16_t*)dv, ldd);
+  if (gsplit > 1 && ktiles > 0) {
+    const long n4 = (long)Tk * a.Hkv * a.dh / 4;
+    hipLaunchKernelGGL(fa_dkdv_reduce_kernel, dim3(cdiv(n4, 256)), dim3(256), 0, st, part, gsplit, Tk,
+                       a.Hkv * a.dh, (bf16_t*)dk, (bf16_t*)dv, ldd_kv);
   }
   BM_CHECK_LAUNCH("fa_bwd");
   return BM_OK;
@@ -644,7 +682,8 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
 }  // namespace
 
 bool attention_mfma_supported(const AttnArgs& a) {
-  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 72 || a.dh == 128) && a.ld_qkv % 8 == 0;
+  return a.dtype == BM_DTYPE_BF16 && (a.dh == 64 || a.dh == 72 || a.dh == 128) && a.ld_qkv % 8 == 0 &&
+         a.kv_ld() % 8 == 0;
 }
 
 bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
@@ -653,11 +692,12 @@ bm_status attention_forward_mfma(const AttnArgs& a, void* o, float* lse, hipStre
   return fwd_launch<64>(a, o, lse, st);
 }
 
-size_t attention_backward_mfma_scratch_bytes(int Hq, int Hkv, int dh, int T) {
-  // the delta plane, then room for the fp32 dK/dV partials of the largest q-head split
-  const size_t delta = align_up((size_t)Hq * T, 64) * sizeof(float);
+size_t attention_backward_mfma_scratch_bytes(int Hq, int Hkv, int dh, int Tq, int Tk) {
+  // the delta plane of the query rows, then room for the fp32 dK/dV partials of the largest
+  // q-head split
+  const size_t delta = align_up((size_t)Hq * Tq, 64) * sizeof(float);
   const int group = Hq / Hkv;
-  const size_t part = group > 1 ? (size_t)group * 2 * T * Hkv * dh * sizeof(float) : 0;
+  const size_t part = group > 1 ? (size_t)group * 2 * Tk * Hkv * dh * sizeof(float) : 0;
   return align_up(delta + part, 256);
 }
 

@@ -204,9 +204,22 @@ struct AttnArgs {
   const int32_t* cu_dev;
   const int32_t* cu_host;
   int S, T, max_seqlen;
+  // Keys/values packed on their own (one chunk of a context-parallel partition of the same S
+  // sequences): offsets, rows, row stride and longest segment.  cu_k_dev == nullptr: they share
+  // the queries' packing and row stride.  Under a causal mask both packings must be equal (the
+  // chunk attends to itself).  ld_dkv: row stride of dk/dv when it differs from dq's.
+  const int32_t* cu_k_dev = nullptr;
+  const int32_t* cu_k_host = nullptr;
+  int Tk = 0, ld_kv = 0, max_klen = 0, ld_dkv = 0;
+  const int32_t* kv_cu_dev() const { return cu_k_dev ? cu_k_dev : cu_dev; }
+  const int32_t* kv_cu_host() const { return cu_k_dev ? cu_k_host : cu_host; }
+  int kv_T() const { return cu_k_dev ? Tk : T; }
+  int kv_ld() const { return cu_k_dev ? ld_kv : ld_qkv; }
+  int kv_max_len() const { return cu_k_dev ? max_klen : max_seqlen; }
 };
 bm_status attention_forward(const AttnArgs& a, void* o, float* lse, hipStream_t st);
 size_t attention_backward_scratch_bytes(int Hq, int Hkv, int dh, int T);
+size_t attention_backward_scratch_bytes(int Hq, int Hkv, int dh, int Tq, int Tk);
 bm_status attention_backward(const AttnArgs& a, const void* o, const void* d_o, const float* lse,
                              void* dq, void* dk, void* dv, int ld_dqkv, void* scratch,
                              size_t scratch_bytes, hipStream_t st);
