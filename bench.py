@@ -5,6 +5,7 @@ transformer block on one MI355X, through the C-ABI library.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2|config3|config4|dit|moe|mmdit]
   python bench.py --workload config5 --batch 8|16|32 [--unit-size 1] [--steps K]
   python bench.py --workload pipeline [--steps K]
+  python bench.py --workload cp [--steps K]
 
 One step = bm_block_forward + bm_block_backward over one batch of seeded
 synthetic packed tokens that is already resident in HBM.  Prints ONE JSON line:
@@ -128,6 +129,93 @@ def cpu_baseline_mmdit(case, budget_flops=2.0e12):
     return {"value": (3.0 * g + 3.5 * a) / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "sample": f"numpy fp64 oracle fwd+bwd on the first {n} samples ({T_sub} of {T} tokens) "
                       f"of the same batch, {dt:.1f} s"}
+
+
+def copy_calibration():
+    """Three plain 1 GiB device copies: the yardstick for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE."""
+    import torch
+    src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
+def run_cp_workload(args):
+    """One rank of a context-parallel group of 4 on a 32768-token causal document (the 8 B GQA
+    attention shape): the last rank, whose 8192 queries see all four key/value chunks."""
+    import numpy as np
+    import torch
+    from paper_2605_25451_amd import binding as bm, synth
+    from paper_2605_25451_amd.cp import ContextParallelGroup
+    Hq, Hkv, dh, C, L = 32, 8, 128, 4, 32768
+    dt = synth.DTYPE_BF16
+    rng = np.random.default_rng(7)
+    cu = synth.cu_from_lengths([L])
+    mk = lambda w: synth.to_storage(rng.standard_normal((L, w), dtype=np.float32), dt)
+    q, k, v, d_o = mk(Hq * dh), mk(Hkv * dh), mk(Hkv * dh), mk(Hq * dh)
+    rank = C - 1
+    g = ContextParallelGroup(dt, Hq, Hkv, dh, True, cu, C, q, k, v, d_o, ranks=[rank])
+    n = L // C
+    pairs = (C - 1) * float(n) * n + n * (n + 1) / 2.0
+    fwd_flops = 4.0 * dh * Hq * pairs
+    step_flops = 3.5 * fwd_flops
+    def step():
+        g.forward(); g.backward()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    bm.profile_begin()
+    for _ in range(args.steps):
+        step()
+    prof = bm.profile_end()
+    torch.cuda.synchronize()
+    breakdown = {c: {"ms_per_step": m / args.steps, "launches_per_step": cnt / args.steps,
+                     "avg_launch_us": m / cnt * 1e3,
+                     **({"tflops": w / (m * 1e-3) / 1e12} if c.startswith("attn") else {"gbs": w / (m * 1e-3) / 1e9})}
+                 for c, (m, w, cnt) in prof.items() if cnt}
+    dom = max(breakdown, key=lambda c: breakdown[c]["ms_per_step"])
+    d_ms, d_work, d_n = prof[dom]
+    ach = d_work / (d_ms * 1e-3) / 1e12
+    tflops = step_flops / (ms * 1e-3) / 1e12
+    out = {"metric": "context-parallel attention fwd+bwd TFLOP/s of one rank (bf16)", "value": tflops,
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "cp4_last_rank_causal_32k", "document_tokens": L, "cp_degree": C, "rank": rank,
+                      "queries": n, "heads": f"{Hq}q/{Hkv}kv x {dh}",
+                      "step": "4 chunk-pair forwards + merge, 4 chunk-pair backwards + sum of the dq parts",
+                      "flops_per_step": step_flops},
+           "mfma_util_pct": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+           "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_us": d_ms / d_n * 1e3,
+                        "traffic": None},
+           "breakdown": breakdown, "paper_context": PAPER_CONTEXT}
+    if args.copy_calibration:
+        copy_calibration()
+    if not args.no_cpu_baseline:
+        from oracle import cp_attention_oracle as co
+        Ls = 12288                                   # same shape, a 12288-token document
+        cus = synth.cu_from_lengths([Ls])
+        ch = synth.context_chunks(cus, C)
+        r3 = lambda a, w: a[:Ls].astype(np.float64).reshape(Ls, -1, dh)
+        q3, k3, v3, do3 = r3(q, Hq), r3(k, Hkv), r3(v, Hkv), r3(d_o, Hq)
+        t0 = time.perf_counter()
+        rq, cq = ch[rank]
+        parts = [co.chunk_forward(q3[rq], k3[ch[j][0]], v3[ch[j][0]], cq, ch[j][1], j == rank) for j in range(C)]
+        o, lse = co.merge([p[0] for p in parts], [p[1] for p in parts])
+        for j in range(C):
+            co.chunk_backward(q3[rq], k3[ch[j][0]], v3[ch[j][0]], o, do3[rq], lse, cq, ch[j][1], j == rank)
+        dt_s = time.perf_counter() - t0
+        ns = Ls // C
+        fl = 3.5 * 4.0 * dh * Hq * ((C - 1) * float(ns) * ns + ns * (ns + 1) / 2.0)
+        out["cpu_baseline"] = {"value": fl / dt_s / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"numpy fp64 oracle, the same rank of a {Ls}-token document, {dt_s:.1f} s"}
+    print(json.dumps(out))
 
 
 def measured_peaks():
@@ -346,6 +434,8 @@ def main():
         return run_stage_workload(args)
     if args.workload == "pipeline":
         return run_pipeline_workload(args)
+    if args.workload == "cp":
+        return run_cp_workload(args)
     if args.workload == "mmdit":
         import numpy as np
         from paper_2605_25451_amd.runner import TwoStreamOnDevice
@@ -434,11 +524,7 @@ def main():
         "paper_context": PAPER_CONTEXT,
     }
     if args.copy_calibration:
-        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+        copy_calibration()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = baseline()
     print(json.dumps(out))

@@ -321,24 +321,26 @@ bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
 // =============================================================================
 // backward
 // =============================================================================
-// delta[h, t] = sum_c dO[t,h,c] * O[t,h,c]
+// delta[h, t] = sum_c dO[t,h,c] * O[t,h,c]; 16 lanes share one (row, head), 16 bytes each, so a
+// wavefront reads whole contiguous row segments
 template <int DH>
 __global__ void fa_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int ldo,
                                 float* __restrict__ delta, int Ttot, int Hq) {
-  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= (long)Ttot * Hq) return;
-  const int t = (int)(gid / Hq), hq = (int)(gid % Hq);
-  const bf16_t* po = o + (size_t)t * ldo + hq * DH;
-  const bf16_t* pd = d_o + (size_t)t * ldo + hq * DH;
+  const long gid = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+  const int c = (threadIdx.x & 15) * 8;
   float s = 0.f;
-#pragma unroll
-  for (int c = 0; c < DH; c += 8) {
+  const bool live = gid < (long)Ttot * Hq;
+  const int t = live ? (int)(gid / Hq) : 0, hq = live ? (int)(gid % Hq) : 0;
+  if (live && c < DH) {
     float a[8], b[8];
-    load16(po + c, a); load16(pd + c, b);
+    load16(o + (size_t)t * ldo + hq * DH + c, a);
+    load16(d_o + (size_t)t * ldo + hq * DH + c, b);
 #pragma unroll
     for (int e = 0; e < 8; ++e) s = fmaf(a[e], b[e], s);
   }
-  delta[(size_t)hq * Ttot + t] = s;
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (live && c == 0) delta[(size_t)hq * Ttot + t] = s;
 }
 
 constexpr int BK_KEYS = 128;   // keys per workgroup in the dK/dV kernel (32 per wavefront)
@@ -649,7 +651,7 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const float sl2 = scale * LOG2E;
   const long n = (long)a.T * a.Hq;
   if (n > 0)
-    hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n, 256)), dim3(256), 0, st, (const bf16_t*)o,
+    hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n * 16, 256)), dim3(256), 0, st, (const bf16_t*)o,
                        (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
   const int ktiles = count_tiles(a.kv_cu_host(), a.S, BK_KEYS);
   const int gsplit = ktiles > 0 ? dkdv_group_split(ktiles, a.Hkv, a.Hq / a.Hkv) : 1;
