@@ -65,6 +65,35 @@ bm_status bm_cp_attention_backward(int32_t dtype, int32_t mask, int32_t n_q_head
 bm_status bm_cp_sum_parts(int32_t dtype, int64_t n, int32_t n_parts, const void* const* parts, void* out,
                           void* hip_stream);
 
+/* ---- encoder -> LLM layout conversion (Sec. 3.3: encoder and LLM may use different context-parallel
+ * degrees; the handoff then re-lays the modality embeddings with an all-to-all, and the encoder unit
+ * grows to pp_size * llm_cp / enc_cp microbatches).  Host-side planning only.
+ *
+ * Layout rule on both sides: a sequence of length L is cut into C contiguous position ranges, chunk c
+ * = positions [c*L/C, (c+1)*L/C) (integer division); a rank's buffer holds its chunk of every
+ * sequence, sequence by sequence.  Encoder sequences are the images (image_lens[n_images] patch
+ * tokens each), LLM sequences the documents (cu_docs[n_docs+1], offsets into the packed microbatch);
+ * image_rows[k] is the row of that pack which encoder token k fills, tokens counted image by image
+ * (distinct rows).  All pointers are host memory.
+ *
+ * Output: counts[e*llm_cp + l] = tokens that encoder rank e sends to LLM rank l; src_rows / dst_rows
+ * [sum of image_lens]: for each pair (e, l) in that order, the rows of rank e's buffer to send, ascending,
+ * and the rows of rank l's buffer where they land. */
+bm_status bm_cp_conversion_plan(int32_t enc_cp, int32_t llm_cp, int32_t n_images, const int32_t* image_lens,
+                                const int32_t* image_rows, int32_t n_docs, const int32_t* cu_docs,
+                                int32_t* counts, int32_t* src_rows, int32_t* dst_rows);
+
+/* *unit_size = pp_size * llm_cp / enc_cp (Sec. 3.3); an error unless the division is exact. */
+bm_status bm_cp_encoder_unit_size(int32_t pp_size, int32_t llm_cp, int32_t enc_cp, int32_t* unit_size);
+
+/* Row moves that apply a plan (or any handoff index list, Sec. 3.2 "Module handoff") on device
+ * memory: dst[i, :] = src[rows[i], :] and dst[rows[i], :] = src[i, :] for i < n; rows is a device
+ * array of distinct indices, width in elements (a multiple of 16 bytes). */
+bm_status bm_row_gather(int32_t dtype, const void* src, const int32_t* rows_dev, void* dst, int32_t n,
+                        int32_t width, void* hip_stream);
+bm_status bm_row_scatter(int32_t dtype, const void* src, const int32_t* rows_dev, void* dst, int32_t n,
+                         int32_t width, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -190,6 +190,12 @@ def lib() -> C.CDLL:
         for name in ("bm_cp_attention_forward", "bm_cp_attention_merge", "bm_cp_attention_backward",
                      "bm_cp_sum_parts"):
             getattr(l, name).restype = C.c_int
+        l.bm_cp_conversion_plan.argtypes = [i32, i32, i32, pi32, pi32, i32, pi32, pi32, pi32, pi32]
+        l.bm_cp_encoder_unit_size.argtypes = [i32, i32, i32, pi32]
+        l.bm_row_gather.argtypes = [i32, vp, vp, vp, i32, i32, vp]
+        l.bm_row_scatter.argtypes = [i32, vp, vp, vp, i32, i32, vp]
+        for name in ("bm_cp_conversion_plan", "bm_cp_encoder_unit_size", "bm_row_gather", "bm_row_scatter"):
+            getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
 
@@ -375,6 +381,36 @@ def cp_attention_backward(dtype, mask, Hq, Hkv, dh, q, ld_q, k, v, ld_kv, o, d_o
 def cp_sum_parts(dtype, n, parts, out, stream=None):
     _check(lib().bm_cp_sum_parts(dtype, n, len(parts), _ptr_array(parts), _ptr(out),
                                  _stream() if stream is None else stream))
+
+
+def cp_conversion_plan(enc_cp, llm_cp, image_lens, image_rows, cu_docs):
+    """(counts [enc_cp, llm_cp], src_rows, dst_rows) as int32 numpy arrays (host planning)."""
+    il = np.ascontiguousarray(image_lens, dtype=np.int32)
+    ir = np.ascontiguousarray(image_rows, dtype=np.int32)
+    cd = np.ascontiguousarray(cu_docs, dtype=np.int32)
+    n = int(il.sum()) if len(il) else 0
+    counts = np.zeros(enc_cp * llm_cp, dtype=np.int32)
+    src, dst = np.zeros(max(n, 1), dtype=np.int32), np.zeros(max(n, 1), dtype=np.int32)
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(lib().bm_cp_conversion_plan(enc_cp, llm_cp, len(il), p(il), p(ir), len(cd) - 1, p(cd), p(counts),
+                                       p(src), p(dst)))
+    return counts.reshape(enc_cp, llm_cp), src[:n], dst[:n]
+
+
+def cp_encoder_unit_size(pp_size, llm_cp, enc_cp) -> int:
+    out = C.c_int32(0)
+    _check(lib().bm_cp_encoder_unit_size(pp_size, llm_cp, enc_cp, C.byref(out)))
+    return out.value
+
+
+def row_gather(dtype, src, rows_dev, dst, n, width, stream=None):
+    _check(lib().bm_row_gather(dtype, _ptr(src), _ptr(rows_dev), _ptr(dst), n, width,
+                               _stream() if stream is None else stream))
+
+
+def row_scatter(dtype, src, rows_dev, dst, n, width, stream=None):
+    _check(lib().bm_row_scatter(dtype, _ptr(src), _ptr(rows_dev), _ptr(dst), n, width,
+                                _stream() if stream is None else stream))
 
 
 def probe_mfma(blocks, iters, out, stream=None):
