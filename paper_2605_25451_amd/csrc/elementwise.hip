@@ -145,7 +145,7 @@ bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, 
 // gradient written here (the bias gradients of the two neighbouring linear
 // layers, whose output gradients these are).  With h_out the normalised row is
 // written again for the weight-gradient GEMM that follows.
-constexpr int NORM_BWD_MAX_BLOCKS = 512;
+constexpr int NORM_BWD_MAX_BLOCKS = 768;
 
 template <int KIND, bool SUMS> struct NormBwdParts {
   static constexpr int NP = (KIND == BM_NORM_LAYERNORM ? 2 : KIND == BM_NORM_RMSNORM ? 1 : 0) + (SUMS ? 2 : 0);
@@ -189,8 +189,14 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     const float mean = stats[row], rstd = stats[rows + row];
     const float* mrow = nullptr;
     if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod;
-    float xv[NV][VEC], gv[NV][VEC];
+    float xv[NV][VEC], gv[NV][VEC], resv[NV][VEC];
     float s1 = 0.f, s2 = 0.f;
+    // the residual gradient is only needed after the row reductions: fetch it with the rest
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int col = (i * WAVE + lane) * VEC;
+      if (col < d) load16(dres + off + col, resv[i]);
+    }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       int col = (i * WAVE + lane) * VEC;
@@ -224,8 +230,8 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     for (int i = 0; i < NV; ++i) {
       int col = (i * WAVE + lane) * VEC;
       if (col < d) {
-        float out[VEC], res[VEC];
-        load16(dres + off + col, res);
+        float out[VEC];
+        const float (&res)[VEC] = resv[i];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           float v;
