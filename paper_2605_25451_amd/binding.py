@@ -117,6 +117,9 @@ def lib() -> C.CDLL:
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2605_25451_amd.build` "
                 "(there is no fallback path)")
+        # torch ships its own HIP runtime: load it first so that this library binds to the same
+        # one (two runtimes in one process do not share devices, streams or allocations)
+        import torch  # noqa: F401
         l = C.CDLL(LIB_PATH)
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         pi32 = C.POINTER(C.c_int32)
