@@ -62,6 +62,32 @@ bm_status gemm(int layout, int dtype, int M, int N, int K, const void* A, int ld
   return gemm_generic(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, epi, scratch, scratch_bytes, st);
 }
 
+size_t gemm_tn_pair_scratch_bytes(int K, int M0, int N0, int M1, int N1, int dtype) {
+  // run separately the two share the buffer; run together each has its own part
+  const size_t a = gemm_scratch_bytes(GEMM_TN, M0, N0, K, dtype), b = gemm_scratch_bytes(GEMM_TN, M1, N1, K, dtype);
+  const size_t both = dtype == BM_DTYPE_BF16 ? gemm_mfma_tn_pair_scratch_bytes(K, M0, N0, M1, N1) : 0;
+  const size_t one = a > b ? a : b;
+  return both > one ? both : one;
+}
+
+bm_status gemm_tn_pair(int dtype, int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0,
+                       void* C0, int ldc0, int M1, int N1, const void* A1, int lda1, const void* B1, int ldb1,
+                       void* C1, int ldc1, void* scratch, size_t scratch_bytes, hipStream_t st) {
+  if (dtype == BM_DTYPE_BF16 && K > 0 && M0 > 0 && N0 > 0 && M1 > 0 && N1 > 0) {
+    if (gemm_mfma_tn_pair(K, M0, N0, A0, lda0, B0, ldb0, C0, ldc0, M1, N1, A1, lda1, B1, ldb1, C1, ldc1, scratch,
+                          scratch_bytes, st, nullptr)) {
+      bm_status rc;
+      ProfScope prof(PROF_GEMM_TN, 2.0 * K * ((double)M0 * N0 + (double)M1 * N1), st);
+      gemm_mfma_tn_pair(K, M0, N0, A0, lda0, B0, ldb0, C0, ldc0, M1, N1, A1, lda1, B1, ldb1, C1, ldc1, scratch,
+                        scratch_bytes, st, &rc);
+      return rc;
+    }
+  }
+  const GemmEpilogue none;
+  BM_RETURN_IF(gemm(GEMM_TN, dtype, M0, N0, K, A0, lda0, B0, ldb0, C0, ldc0, none, scratch, scratch_bytes, st));
+  return gemm(GEMM_TN, dtype, M1, N1, K, A1, lda1, B1, ldb1, C1, ldc1, none, scratch, scratch_bytes, st);
+}
+
 bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
                        const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st) {
   if (M <= 0 || N <= 0) return BM_OK;

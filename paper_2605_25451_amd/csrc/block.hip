@@ -124,8 +124,7 @@ size_t max_gemm_tn_scratch(const Dims& m, int dtype) {
     v = gemm_scratch_bytes(GEMM_TN, m.d, m.F, m.T, dtype); b = v > b ? v : b;
     v = gemm_scratch_bytes(GEMM_TN, m.UP, m.d, m.T, dtype); b = v > b ? v : b;
   }
-  v = gemm_scratch_bytes(GEMM_TN, m.d, m.QD, m.T, dtype); b = v > b ? v : b;
-  v = gemm_scratch_bytes(GEMM_TN, m.QKV, m.d, m.T, dtype); b = v > b ? v : b;
+  v = gemm_tn_pair_scratch_bytes(m.T, m.QKV, m.d, m.d, m.QD, dtype); b = v > b ? v : b;
   if (m.ada) {
     v = gemm_scratch_bytes(GEMM_TN, 6 * m.d, m.d, m.S, dtype); b = v > b ? v : b;
     v = gemm_scratch_bytes(GEMM_TN, (int)align_up(m.S, 8), m.d, 6 * m.d, dtype); b = v > b ? v : b;
@@ -500,8 +499,8 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
                                 6 * d, ws.norm_ws, st)); }
     dattn = ws.dgated;
   }
-  BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.QD, T, dattn, d, sv.o, m.QD, grads->w_o, m.QD, none, ws.gemm_ws,
-                    ws.gemm_ws_bytes, st));
+  // (the weight gradient of the output projection is small: it shares a launch with the one of
+  // the QKV projection at the end; dattn and the saved o stay untouched until then)
   if (c.linear_bias && !fused_sums)
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(colsum_accumulate(dt, dattn, d, T, d, (float*)grads->b_o, ws.colsum_ws, st)); }
   BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.QD, d, dattn, d, w->w_o, m.QD, ws.d_o, m.QD, none, nullptr, 0, st));
@@ -530,8 +529,8 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
     BM_RETURN_IF(norm_backward(n1, x, sv.stats1, ws.dh, ws.dx1, dx, ws.h, (float*)grads->norm1_g,
                                (float*)grads->norm1_b, nullptr, nullptr, ws.dmod, cu_dev, S,
                                ws.norm_ws, st)); }
-  BM_RETURN_IF(gemm(GEMM_TN, dt, m.QKV, d, T, ws.dqkv, m.QKV, ws.h, d, grads->w_qkv, d, none,
-                    ws.gemm_ws, ws.gemm_ws_bytes, st));
+  BM_RETURN_IF(gemm_tn_pair(dt, T, m.QKV, d, ws.dqkv, m.QKV, ws.h, d, grads->w_qkv, d,
+                            d, m.QD, dattn, d, sv.o, m.QD, grads->w_o, m.QD, ws.gemm_ws, ws.gemm_ws_bytes, st));
 
   // ---- adaLN: mod = silu(cond) W_ada^T + b_ada
   if (m.ada) {

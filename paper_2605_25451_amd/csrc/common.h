@@ -149,6 +149,17 @@ struct GemmGroups {
   long c_stride = 0;                     // elements between the C matrices of two groups (TN)
   long routed_rows = 0;                  // rows that carry tokens (profiling: algorithmic flops)
 };
+// Two weight gradients over the same rows, C_i[M_i,N_i] += A_i[K,M_i]^T B_i[K,N_i] (fp32 C), as one
+// launch when that fills the chip better, else one after the other; scratch as for the larger sum
+// of both (gemm_pair_scratch_bytes).
+size_t gemm_tn_pair_scratch_bytes(int K, int M0, int N0, int M1, int N1, int dtype);
+bm_status gemm_tn_pair(int dtype, int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0,
+                       void* C0, int ldc0, int M1, int N1, const void* A1, int lda1, const void* B1, int ldb1,
+                       void* C1, int ldc1, void* scratch, size_t scratch_bytes, hipStream_t st);
+size_t gemm_mfma_tn_pair_scratch_bytes(int K, int M0, int N0, int M1, int N1);
+bool gemm_mfma_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0,
+                       int M1, int N1, const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1,
+                       void* scratch, size_t scratch_bytes, hipStream_t st, bm_status* rc);
 bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
                        const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st);
 bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc);

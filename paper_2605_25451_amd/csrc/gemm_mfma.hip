@@ -46,6 +46,13 @@ struct GemmParams {
   const int32_t* group_rows;
   long b_group_stride, c_group_stride;
   int grid_groups;              // host: workgroups = tiles * splits * grid_groups (>= 1)
+  // paired launch: workgroups pair_wgs0.. of the grid work on a second problem of the same
+  // kind and the same K (two weight gradients that each leave CUs idle share one grid)
+  int pair_wgs0;                // 0: one problem
+  struct Second {
+    const bf16_t* A; const bf16_t* B; void* C; float* partial;
+    int M, N, lda, ldb, ldc, tiles_m, tiles_n, splits, k_per_split, xcd_split;
+  } second;
 };
 
 // ---- LDS layouts ---------------------------------------------------------
@@ -207,11 +214,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
+  int pid = blockIdx.x;
+  if (p.pair_wgs0 > 0 && pid >= p.pair_wgs0) {
+    // second problem of a paired launch (workgroup-uniform): take its description over
+    pid -= p.pair_wgs0;
+    p.A = p.second.A; p.B = p.second.B; p.C = p.second.C; p.partial = p.second.partial;
+    p.M = p.second.M; p.N = p.second.N; p.lda = p.second.lda; p.ldb = p.second.ldb; p.ldc = p.second.ldc;
+    p.tiles_m = p.second.tiles_m; p.tiles_n = p.second.tiles_n; p.splits = p.second.splits;
+    p.k_per_split = p.second.k_per_split; p.xcd_split = p.second.xcd_split;
+  }
   const int tiles = p.tiles_m * p.tiles_n;
-  int split = blockIdx.x / tiles;
+  int split = pid / tiles;
   int tm, tn;
-  if (p.xcd_split) split_tile_of_block(blockIdx.x, tiles, p.splits, p.tiles_m, p.tiles_n, &split, &tm, &tn);
-  else tile_of_block(blockIdx.x % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
+  if (p.xcd_split) split_tile_of_block(pid, tiles, p.splits, p.tiles_m, p.tiles_n, &split, &tm, &tn);
+  else tile_of_block(pid % tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   int kbeg = split * p.k_per_split;
   int kend = min(p.K, kbeg + p.k_per_split);
@@ -478,7 +494,9 @@ bm_status launch_k(const GemmParams& p, hipStream_t st) {
     BM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_done = true;
   }
-  dim3 grid(p.tiles_m * p.tiles_n * p.splits * p.grid_groups), block(WM * WN * 64);
+  int wgs = p.tiles_m * p.tiles_n * p.splits * p.grid_groups;
+  if (p.pair_wgs0 > 0) wgs = p.pair_wgs0 + p.second.tiles_m * p.second.tiles_n * p.second.splits;
+  dim3 grid(wgs), block(WM * WN * 64);
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);
   BM_CHECK_LAUNCH("gemm_mfma");
   return BM_OK;
@@ -529,7 +547,7 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
   p.out_fp32 = epi.out_fp32;
   p.tile_group = nullptr; p.group_rows = nullptr; p.b_group_stride = 0; p.c_group_stride = 0;
-  p.grid_groups = 1;
+  p.grid_groups = 1; p.pair_wgs0 = 0; p.second = {};
   {
     p.xcd_split = xcd_split_possible(pl.tiles_m * pl.tiles_n, pl.splits) ? 1 : 0;
   }
@@ -556,6 +574,95 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   return BM_OK;
 }
 
+// common k split of a paired launch (0: the pair does not qualify)
+static int pair_splits(int K, int M0, int N0, int M1, int N1) {
+  if (K % BK || M0 < 256 || N0 < 256 || M1 < 256 || N1 < 256) return 0;
+  const long tiles = (long)cdiv(M0, 256) * cdiv(N0, 256) + (long)cdiv(M1, 256) * cdiv(N1, 256);
+  const int slices = K / BK;
+  int sp = (int)(NUM_CU / tiles);
+  if (sp > 32) sp = 32;
+  if (sp > slices / 4) sp = slices / 4;
+  for (; sp >= 1; --sp)
+    if (cdiv(slices, cdiv(slices, sp)) == sp) break;
+  return sp < 1 ? 0 : sp;
+}
+
+size_t gemm_mfma_tn_pair_scratch_bytes(int K, int M0, int N0, int M1, int N1) {
+  const int sp = pair_splits(K, M0, N0, M1, N1);
+  if (sp <= 1) return 0;
+  return align_up((size_t)sp * M0 * N0 * sizeof(float), 256) + (size_t)sp * M1 * N1 * sizeof(float);
+}
+
+// Two weight gradients C_i[M_i,N_i] += A_i[K,M_i]^T B_i[K,N_i] over the same K in ONE grid, when
+// both plans use 256x256 tiles and whole slices: a gradient whose tiles x splits do not fill
+// the chip (1024x1024 next to 3072x1024 in a ViT-L block) no longer has the machine to itself.
+// Returns false (nothing launched) when the pair does not qualify; the caller then runs two GEMMs.
+bool gemm_mfma_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0,
+                       int M1, int N1, const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1,
+                       void* scratch, size_t scratch_bytes, hipStream_t st, bm_status* rc) {
+  // rc == nullptr: only answer whether the pair qualifies
+  const GemmEpilogue none;
+  if (rc) *rc = BM_OK;
+  if (K % BK) return false;
+  if (!gemm_mfma_supported(GEMM_TN, BM_DTYPE_BF16, M0, N0, K, lda0, ldb0, ldc0, none) ||
+      !gemm_mfma_supported(GEMM_TN, BM_DTYPE_BF16, M1, N1, K, lda1, ldb1, ldc1, none)) return false;
+  // one plan for both: 256x256 tiles and the largest common k split whose workgroups fit the chip
+  // in one round, so that all of them run equally long; it must beat the two separate plans
+  const int sp = pair_splits(K, M0, N0, M1, N1);
+  if (sp < 1) return false;
+  const int slices = K / BK;
+  Plan a{}, b{};
+  a.bm = a.bn = b.bm = b.bn = 256;
+  a.tiles_m = cdiv(M0, 256); a.tiles_n = cdiv(N0, 256);
+  b.tiles_m = cdiv(M1, 256); b.tiles_n = cdiv(N1, 256);
+  a.splits = b.splits = sp;
+  a.k_per_split = b.k_per_split = cdiv(slices, sp) * BK;
+  {
+    const auto model = [&](int M, int N) {                      // what make_plan expects for one problem
+      const Plan q = make_plan(GEMM_TN, M, N, K);
+      const bool big = q.bm == 256;
+      const long wg = (long)q.tiles_m * q.tiles_n * q.splits, slots = big ? NUM_CU : 2 * NUM_CU;
+      double t = (double)((wg + slots - 1) / slots) * (q.k_per_split / BK * (big ? 1.85 : 1.25) + (big ? 8.0 : 4.0));
+      if (q.splits > 1) t += 3.0 + 1.3 * q.splits * (double)M * N * 4.0 / 3.0e6;
+      return t;
+    };
+    double together = a.k_per_split / BK * 1.85 + 8.0;
+    if (sp > 1) together += 6.0 + 1.3 * sp * ((double)M0 * N0 + (double)M1 * N1) * 4.0 / 3.0e6;
+    if (together >= model(M0, N0) + model(M1, N1)) return false;
+  }
+  const size_t part0 = a.splits > 1 ? align_up((size_t)a.splits * M0 * N0 * sizeof(float), 256) : 0;
+  const size_t part1 = b.splits > 1 ? (size_t)b.splits * M1 * N1 * sizeof(float) : 0;
+  if (part0 + part1 > scratch_bytes || (part0 + part1 > 0 && !scratch)) return false;
+  const int wgs0 = a.tiles_m * a.tiles_n * a.splits;
+  const bool xa = xcd_split_possible(a.tiles_m * a.tiles_n, a.splits), xb = xcd_split_possible(b.tiles_m * b.tiles_n, b.splits);
+  if (xb && wgs0 % 8) return false;               // the second problem's XCD pinning needs an aligned start
+  if (!rc) return true;
+  GemmParams p;
+  p.A = (const bf16_t*)A0; p.B = (const bf16_t*)B0; p.C = C0; p.bias = nullptr; p.residual = nullptr;
+  p.partial = (float*)scratch;
+  p.M = M0; p.N = N0; p.K = K; p.lda = lda0; p.ldb = ldb0; p.ldc = ldc0;
+  p.tiles_m = a.tiles_m; p.tiles_n = a.tiles_n; p.splits = a.splits; p.k_per_split = a.k_per_split;
+  p.out_fp32 = 0; p.xcd_split = xa ? 1 : 0;
+  p.tile_group = nullptr; p.group_rows = nullptr; p.b_group_stride = 0; p.c_group_stride = 0; p.grid_groups = 1;
+  p.pair_wgs0 = wgs0;
+  p.second.A = (const bf16_t*)A1; p.second.B = (const bf16_t*)B1; p.second.C = C1;
+  p.second.partial = (float*)((char*)scratch + part0);
+  p.second.M = M1; p.second.N = N1; p.second.lda = lda1; p.second.ldb = ldb1; p.second.ldc = ldc1;
+  p.second.tiles_m = b.tiles_m; p.second.tiles_n = b.tiles_n; p.second.splits = b.splits;
+  p.second.k_per_split = b.k_per_split; p.second.xcd_split = xb ? 1 : 0;
+  *rc = launch_k<256, 256, 2, 2, true, true, true, false>(p, st);
+  if (*rc != BM_OK) return true;
+  if (a.splits > 1)
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(cdiv((long)M0 * N0 / 4, 256)), dim3(256), 0, st, p.partial, a.splits,
+                       M0, N0, (float*)C0, ldc0);
+  if (b.splits > 1)
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(cdiv((long)M1 * N1 / 4, 256)), dim3(256), 0, st, p.second.partial,
+                       b.splits, M1, N1, (float*)C1, ldc1);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) *rc = hip_fail(e, "splitk_reduce");
+  return true;
+}
+
 bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc) {
   if (dtype != BM_DTYPE_BF16) return false;
   if (N < 64 || lda % 8 || ldb % 8) return false;
@@ -572,7 +679,7 @@ bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int 
   p.bias = nullptr; p.residual = nullptr; p.partial = nullptr;
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   p.tiles_m = cdiv(M, 128); p.tiles_n = cdiv(N, 128); p.splits = 1; p.k_per_split = cdiv(K, BK) * BK;
-  p.out_fp32 = 0; p.xcd_split = 0;
+  p.out_fp32 = 0; p.xcd_split = 0; p.pair_wgs0 = 0; p.second = {};
   p.tile_group = layout == GEMM_TN ? nullptr : g.tile_group;
   p.group_rows = layout == GEMM_TN ? g.group_rows : nullptr;
   p.b_group_stride = g.b_stride; p.c_group_stride = g.c_stride;
