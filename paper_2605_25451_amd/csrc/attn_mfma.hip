@@ -21,6 +21,8 @@
 // owner, so there are no floating-point atomics and results are reproducible.
 #include "common.h"
 
+#include <type_traits>
+
 namespace bm {
 
 namespace {
@@ -212,7 +214,13 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   sk.load(kbase, ldk, 0, Lk, tid);
   sv.load(vbase, ldk, 0, Lk, tid);
 
-  for (int kt = 0; kt < nkt; ++kt) {
+  // The step comes in two copies, without and with the per-element mask test, each in a loop of
+  // its own: the leading key tiles lie wholly inside the sequence (and before the diagonal under a
+  // causal mask) and need no test; written as a run-time condition inside the unrolled code, the
+  // test becomes compare/select pairs that every step pays for.  Every wavefront runs nkt steps
+  // in total (the split may differ between wavefronts; the barrier count per step does not).
+  auto step = [&](int kt, auto masked) {
+    constexpr bool MASKED = decltype(masked)::value;
     __syncthreads();                       // previous step's readers are done
     sk.store(Ks, tid);
     sv.store(Vs, tid);
@@ -236,13 +244,12 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
                                                           sacc[b], 0, 0, 0);
     }
     // mask: keys past the sequence end, and keys after the query under a causal mask
-    const bool need_mask = (key0 + FK > Lk) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
       float mx = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        if (need_mask) {
+        if (MASKED) {
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (key >= Lk || (CAUSAL && key > qpos)) sacc[b][r] = -INFINITY;
         }
@@ -278,7 +285,14 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
         oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Vs, j * 32, b * 32 + 16, lane), p1, oacc[j], 0, 0, 0);
       }
     }
-  }
+  };
+  // tiles kt < n_plain need no test: key0 + FK <= Lk, and key0 + FK - 1 <= this wavefront's first query
+  int n_plain = Lk / FK;
+  if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
+  n_plain = min(n_plain, nkt);
+  int kt = 0;
+  for (; kt < n_plain; ++kt) step(kt, std::false_type{});
+  for (; kt < nkt; ++kt) step(kt, std::true_type{});
   lsum += __shfl_xor(lsum, 32, 64);
   if (qpos < L) {
     const float inv = 1.0f / lsum;
@@ -411,7 +425,9 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     }
   };
   if (iters > 0) fetch(0);
-  for (int it = 0; it < iters; ++it) {
+  // one step; MASKED is a compile-time copy with the per-element tests (see the forward kernel)
+  auto step = [&](int it, auto masked) {
+    constexpr bool MASKED = decltype(masked)::value;
     __syncthreads();
     sq.store(Qs, tid);
     sd.store(Ds, tid);
@@ -419,8 +435,6 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     __syncthreads();
     if (it + 1 < iters) fetch(it + 1);
     const int q0 = qstart + (it % nqt) * BK_Q;
-    const bool need_mask = (q0 + BK_Q > Lq) || (kb0 + BK_KEYS > L) ||
-                           (CAUSAL && q0 < kb0 + wave * 32 + 32);
     // S = Q K^T and dP = dO V^T for both 32-query blocks first, then per block the
     // softmax arithmetic (under the other block's MFMAs) followed by its dV / dK MFMAs.
     f32x16 sacc[BK_Q / 32], dpacc[BK_Q / 32];
@@ -445,7 +459,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
           float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][r], scale_log2, -l4[e]));
-          if (need_mask) {
+          if (MASKED) {
             const int qi = q0 + qoff + e;
             if (qi >= Lq || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
           }
@@ -462,6 +476,23 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
         dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32, lane), s0, dkacc[j], 0, 0, 0);
         dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32 + 16, lane), s1, dkacc[j], 0, 0, 0);
       }
+    }
+  };
+  // Which query tiles need the tests: all of them when this key tile is cut by the sequence end;
+  // else, per q head, the first ones under a causal mask (queries before this wavefront's last
+  // key) and the last one when it is cut by the sequence end.  Every wavefront runs `iters`
+  // steps; only the split between the copies differs.
+  if (kb0 + BK_KEYS > L) {
+    for (int it = 0; it < iters; ++it) step(it, std::true_type{});
+  } else {
+    const int n_front = CAUSAL ? min(nqt, (wave * 32 + 32 + BK_Q - 1) / BK_Q) : 0;
+    const int n_whole = max(n_front, (Lq - qstart) % BK_Q ? nqt - 1 : nqt);
+    int it = 0;
+    for (int h = 0; h < gpart; ++h) {
+      int t = 0;
+      for (; t < n_front; ++t, ++it) step(it, std::true_type{});
+      for (; t < n_whole; ++t, ++it) step(it, std::false_type{});
+      for (; t < nqt; ++t, ++it) step(it, std::true_type{});
     }
   }
   if (kpos < L && gsplit > 1) {
@@ -556,7 +587,9 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
   TileStage<FK, DH, 256> sk, sv;
   sk.load(kbase, ldk, 0, Lk, tid);
   sv.load(vbase, ldk, 0, Lk, tid);
-  for (int kt = 0; kt < nkt; ++kt) {
+  // two copies of the step, without and with the mask test, as in the forward kernel
+  auto step = [&](int kt, auto masked) {
+    constexpr bool MASKED = decltype(masked)::value;
     __syncthreads();
     sk.store(Ks, tid);
     sv.store(Vs, tid);
@@ -566,7 +599,6 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
       sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
     }
     const int key0 = kt * FK;
-    const bool need_mask = (key0 + FK > Lk) || (CAUSAL && key0 + FK - 1 > q0 + wave * 32);
     f32x16 sacc[FK / 32], dpacc[FK / 32];
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
@@ -583,7 +615,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], scale_log2, -my_lse));
-        if (need_mask) {
+        if (MASKED) {
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (key >= Lk || (CAUSAL && key > qpos)) p = 0.f;
         }
@@ -596,7 +628,15 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
         dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ks, j * 32, b * 32 + 16, lane), s1, dqacc[j], 0, 0, 0);
       }
     }
+  };
+  int kt = 0;
+  if (DH <= 72) {        // at head size 128 the second copy costs more in spilled registers than it saves
+    int n_plain = Lk / FK;
+    if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
+    n_plain = min(n_plain, nkt);
+    for (; kt < n_plain; ++kt) step(kt, std::false_type{});
   }
+  for (; kt < nkt; ++kt) step(kt, std::true_type{});
   if (qpos < L) {
     bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
 #pragma unroll
