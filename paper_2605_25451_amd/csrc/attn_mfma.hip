@@ -426,6 +426,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   };
   if (iters > 0) fetch(0);
   // one step; MASKED is a compile-time copy with the per-element tests (see the forward kernel)
+  constexpr bool FOLD_DELTA = DH <= 64;
   auto step = [&](int it, auto masked) {
     constexpr bool MASKED = decltype(masked)::value;
     __syncthreads();
@@ -442,6 +443,17 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     for (int qb = 0; qb < BK_Q / 32; ++qb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; dpacc[qb][r] = 0.f; }
+      // With several resident wavefronts to hide the LDS read, dP starts at -delta of its query
+      // row, so that the MFMAs leave dP - delta: one subtraction per score element less on the
+      // vector unit.  (With one wavefront per SIMD the read in front of the MFMAs costs more.)
+      if (FOLD_DELTA) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(Dl + qb * 32 + g * 8 + half * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dpacc[qb][g * 4 + e] = -d4[e];
+        }
+      }
 #pragma unroll
       for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
         sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Qs, qb * 32, ks, lane), kf[ks], sacc[qb], 0, 0, 0);
@@ -454,7 +466,8 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
       for (int g = 0; g < 4; ++g) {
         const int qoff = qb * 32 + g * 8 + half * 4;
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(Ls + qoff);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(Dl + qoff);
+        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+        if (!FOLD_DELTA) d4 = *reinterpret_cast<const f32x4*>(Dl + qoff);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
@@ -464,7 +477,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
             if (qi >= Lq || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
           }
           sacc[qb][r] = p;
-          dpacc[qb][r] = p * (dpacc[qb][r] - d4[e]);
+          dpacc[qb][r] = FOLD_DELTA ? p * dpacc[qb][r] : p * (dpacc[qb][r] - d4[e]);
         }
       }
       const bf16x8 p0 = acc_to_operand(sacc[qb], 0), p1 = acc_to_operand(sacc[qb], 1);
@@ -588,6 +601,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
   sk.load(kbase, ldk, 0, Lk, tid);
   sv.load(vbase, ldk, 0, Lk, tid);
   // two copies of the step, without and with the mask test, as in the forward kernel
+  constexpr bool FOLD_DELTA = DH <= 64;      // dP accumulators start at -delta (see the dK/dV kernel)
   auto step = [&](int kt, auto masked) {
     constexpr bool MASKED = decltype(masked)::value;
     __syncthreads();
@@ -603,7 +617,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
 #pragma unroll
     for (int b = 0; b < FK / 32; ++b) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[b][r] = 0.f; dpacc[b][r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { sacc[b][r] = 0.f; dpacc[b][r] = FOLD_DELTA ? -my_delta : 0.f; }   // MFMAs leave dP - delta
 #pragma unroll
       for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
         sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ks, b * 32, ks, lane), qf[ks], sacc[b], 0, 0, 0);
@@ -619,7 +633,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
           const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (key >= Lk || (CAUSAL && key > qpos)) p = 0.f;
         }
-        dpacc[b][r] = p * (dpacc[b][r] - my_delta);
+        dpacc[b][r] = FOLD_DELTA ? p * dpacc[b][r] : p * (dpacc[b][r] - my_delta);
       }
       const bf16x8 s0 = acc_to_operand(dpacc[b], 0), s1 = acc_to_operand(dpacc[b], 1);
 #pragma unroll
