@@ -235,13 +235,22 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     // block 0 run under the softmax of block 1.
     f32x16 sacc[FK / 32];
 #pragma unroll
-    for (int b = 0; b < FK / 32; ++b) {
+    for (int b = 0; b < FK / 32; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+    {
+      // K fragments are requested from LDS AHEAD MFMAs before their use (a ring of register sets)
+      constexpr int KS = HeadDim<DH>::KS, NSTEP = (FK / 32) * KS, AHEAD = 2;
+      bf16x8 fk[AHEAD + 1];
 #pragma unroll
-      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks)
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ks, b * 32, ks, lane), qf[ks],
-                                                          sacc[b], 0, 0, 0);
+      for (int n = 0; n < AHEAD && n < NSTEP; ++n) fk[n] = frag_rows<HeadDim<DH>::DHL>(Ks, (n / KS) * 32, n % KS, lane);
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) {
+        const int m = n + AHEAD;
+        if (m < NSTEP) fk[m % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Ks, (m / KS) * 32, m % KS, lane);
+        sacc[n / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[n % (AHEAD + 1)], qf[n % KS], sacc[n / KS], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     // mask: keys past the sequence end, and keys after the query under a causal mask
 #pragma unroll
@@ -278,11 +287,22 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
       }
       lsum += psum;
       const bf16x8 p0 = acc_to_operand(sacc[b], 0), p1 = acc_to_operand(sacc[b], 1);
-      // O^T += V^T P^T
+      // O^T += V^T P^T, the transposed V operands requested one pair of MFMAs ahead
+      {
+        constexpr int NB = HeadDim<DH>::NB;
+        bf16x8 fr[2][2];
+        fr[0][0] = frag_cols<HeadDim<DH>::DHL>(Vs, 0, b * 32, lane);
+        fr[0][1] = frag_cols<HeadDim<DH>::DHL>(Vs, 0, b * 32 + 16, lane);
 #pragma unroll
-      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
-        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Vs, j * 32, b * 32, lane), p0, oacc[j], 0, 0, 0);
-        oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Vs, j * 32, b * 32 + 16, lane), p1, oacc[j], 0, 0, 0);
+        for (int j = 0; j < NB; ++j) {
+          if (j + 1 < NB) {
+            fr[(j + 1) & 1][0] = frag_cols<HeadDim<DH>::DHL>(Vs, (j + 1) * 32, b * 32, lane);
+            fr[(j + 1) & 1][1] = frag_cols<HeadDim<DH>::DHL>(Vs, (j + 1) * 32, b * 32 + 16, lane);
+          }
+          oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][0], p0, oacc[j], 0, 0, 0);
+          oacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][1], p1, oacc[j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   };
@@ -454,10 +474,28 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
           for (int e = 0; e < 4; ++e) dpacc[qb][g * 4 + e] = -d4[e];
         }
       }
+    }
+    {
+      // the operand fragments of step n + AHEAD are requested from LDS before the MFMAs of step n
+      // are issued (a ring of AHEAD + 1 register sets): with one wavefront per SIMD nothing else
+      // would cover the LDS latency in front of every MFMA
+      constexpr int KS = HeadDim<DH>::KS, NSTEP = (BK_Q / 32) * KS, AHEAD = 2;
+      bf16x8 fq[AHEAD + 1], fd[AHEAD + 1];
 #pragma unroll
-      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
-        sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Qs, qb * 32, ks, lane), kf[ks], sacc[qb], 0, 0, 0);
-        dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ds, qb * 32, ks, lane), vf[ks], dpacc[qb], 0, 0, 0);
+      for (int n = 0; n < AHEAD && n < NSTEP; ++n) {
+        fq[n] = frag_rows<HeadDim<DH>::DHL>(Qs, (n / KS) * 32, n % KS, lane);
+        fd[n] = frag_rows<HeadDim<DH>::DHL>(Ds, (n / KS) * 32, n % KS, lane);
+      }
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) {
+        const int qb = n / KS, ks = n % KS, m = n + AHEAD;
+        if (m < NSTEP) {
+          fq[m % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Qs, (m / KS) * 32, m % KS, lane);
+          fd[m % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Ds, (m / KS) * 32, m % KS, lane);
+        }
+        sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % (AHEAD + 1)], kf[ks], sacc[qb], 0, 0, 0);
+        dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[n % (AHEAD + 1)], vf[ks], dpacc[qb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 #pragma unroll
@@ -482,12 +520,27 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
       }
       const bf16x8 p0 = acc_to_operand(sacc[qb], 0), p1 = acc_to_operand(sacc[qb], 1);
       const bf16x8 s0 = acc_to_operand(dpacc[qb], 0), s1 = acc_to_operand(dpacc[qb], 1);
+      {
+        // dV += dO^T P, dK += Q^T dS: 4 MFMAs per 32 columns of dh, their transposed operands
+        // requested one group ahead
+        constexpr int NB = HeadDim<DH>::NB;
+        bf16x8 fr[2][4];
+        auto request = [&](int j, bf16x8 (&f)[4]) {
+          f[0] = frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32, lane);
+          f[1] = frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32 + 16, lane);
+          f[2] = frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32, lane);
+          f[3] = frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32 + 16, lane);
+        };
+        request(0, fr[0]);
 #pragma unroll
-      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
-        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32, lane), p0, dvacc[j], 0, 0, 0);
-        dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ds, j * 32, qb * 32 + 16, lane), p1, dvacc[j], 0, 0, 0);
-        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32, lane), s0, dkacc[j], 0, 0, 0);
-        dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Qs, j * 32, qb * 32 + 16, lane), s1, dkacc[j], 0, 0, 0);
+        for (int j = 0; j < NB; ++j) {
+          if (j + 1 < NB) request(j + 1, fr[(j + 1) & 1]);
+          dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][0], p0, dvacc[j], 0, 0, 0);
+          dvacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][1], p1, dvacc[j], 0, 0, 0);
+          dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][2], s0, dkacc[j], 0, 0, 0);
+          dkacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][3], s1, dkacc[j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   };
@@ -551,8 +604,12 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
     int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
+  // At head size 128 the dO operand of this tile's queries lives in LDS instead of registers:
+  // with it in registers the kernel spills inside the MFMA loop at two wavefronts per SIMD.
+  constexpr bool DO_LDS = DH > 72;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Dos[DO_LDS ? FQ * HeadDim<DH>::DHL : 8];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
@@ -575,15 +632,21 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     return;
   }
 
-  bf16x8 qf[HeadDim<DH>::KS], dof[HeadDim<DH>::KS];
+  bf16x8 qf[HeadDim<DH>::KS], dof[DO_LDS ? 1 : HeadDim<DH>::KS];
   {
     const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH;
     const bf16_t* dp = d_o + (size_t)(lo + qrow) * ldo + hq * DH;
 #pragma unroll
     for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
       qf[ks] = load_chunk<DH>(qp, ks * 2 + half);
-      dof[ks] = load_chunk<DH>(dp, ks * 2 + half);
+      if (!DO_LDS) dof[ks] = load_chunk<DH>(dp, ks * 2 + half);
     }
+  }
+  if (DO_LDS) {
+    // (visible to every wavefront after the barriers that open the first step)
+    TileStage<FQ, DH, 256> sdo;
+    sdo.load(d_o + (size_t)lo * ldo + hq * DH, ldo, q0, L, tid);
+    sdo.store(Dos, tid);
   }
   const float my_lse = lse[(size_t)hq * Ttot + lo + qrow] * LOG2E;
   const float my_delta = delta[(size_t)hq * Ttot + lo + qrow];
@@ -613,43 +676,76 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
       sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
     }
     const int key0 = kt * FK;
-    f32x16 sacc[FK / 32], dpacc[FK / 32];
+    // S^T = K Q^T and dP^T = V dO^T of BP 32-key blocks are issued before any softmax arithmetic,
+    // so that one block's MFMAs run under the other's vector work; at head size 128 that is one
+    // block at a time (two sets of accumulators do not fit next to two resident wavefronts).
+    constexpr int NBLK = FK / 32, BP = DH > 72 ? 1 : NBLK, KS = HeadDim<DH>::KS;
 #pragma unroll
-    for (int b = 0; b < FK / 32; ++b) {
+    for (int b0 = 0; b0 < NBLK; b0 += BP) {
+      f32x16 sacc[BP], dpacc[BP];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[b][r] = 0.f; dpacc[b][r] = FOLD_DELTA ? -my_delta : 0.f; }   // MFMAs leave dP - delta
+      for (int bi = 0; bi < BP; ++bi)
 #pragma unroll
-      for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Ks, b * 32, ks, lane), qf[ks], sacc[b], 0, 0, 0);
-        dpacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<HeadDim<DH>::DHL>(Vs, b * 32, ks, lane), dof[ks], dpacc[b], 0, 0, 0);
-      }
-    }
+        for (int r = 0; r < 16; ++r) { sacc[bi][r] = 0.f; dpacc[bi][r] = FOLD_DELTA ? -my_delta : 0.f; }   // MFMAs leave dP - delta
+      {
+        // operand fragments are requested AHEAD MFMA pairs before their use (see the dK/dV kernel)
+        constexpr int NSTEP = BP * KS, AHEAD = 2;
+        bf16x8 fk[AHEAD + 1], fv[AHEAD + 1], fo[AHEAD + 1];
+        auto request = [&](int n) {
+          fk[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Ks, (b0 + n / KS) * 32, n % KS, lane);
+          fv[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Vs, (b0 + n / KS) * 32, n % KS, lane);
+          if (DO_LDS) fo[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Dos, wave * 32, n % KS, lane);
+        };
 #pragma unroll
-    for (int b = 0; b < FK / 32; ++b) {
+        for (int n = 0; n < AHEAD && n < NSTEP; ++n) request(n);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], scale_log2, -my_lse));
-        if (MASKED) {
-          const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          if (key >= Lk || (CAUSAL && key > qpos)) p = 0.f;
+        for (int n = 0; n < NSTEP; ++n) {
+          const int bi = n / KS, ks = n % KS;
+          if (n + AHEAD < NSTEP) request(n + AHEAD);
+          sacc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[n % (AHEAD + 1)], qf[ks], sacc[bi], 0, 0, 0);
+          dpacc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[n % (AHEAD + 1)], DO_LDS ? fo[n % (AHEAD + 1)] : dof[DO_LDS ? 0 : ks],
+                                                              dpacc[bi], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        dpacc[b][r] = FOLD_DELTA ? p * dpacc[b][r] : p * (dpacc[b][r] - my_delta);
       }
-      const bf16x8 s0 = acc_to_operand(dpacc[b], 0), s1 = acc_to_operand(dpacc[b], 1);
 #pragma unroll
-      for (int j = 0; j < HeadDim<DH>::NB; ++j) {
-        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ks, j * 32, b * 32, lane), s0, dqacc[j], 0, 0, 0);
-        dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<HeadDim<DH>::DHL>(Ks, j * 32, b * 32 + 16, lane), s1, dqacc[j], 0, 0, 0);
+      for (int bi = 0; bi < BP; ++bi) {
+        const int b = b0 + bi;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[bi][r], scale_log2, -my_lse));
+          if (MASKED) {
+            const int key = key0 + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (key >= Lk || (CAUSAL && key > qpos)) p = 0.f;
+          }
+          dpacc[bi][r] = FOLD_DELTA ? p * dpacc[bi][r] : p * (dpacc[bi][r] - my_delta);
+        }
+        const bf16x8 s0 = acc_to_operand(dpacc[bi], 0), s1 = acc_to_operand(dpacc[bi], 1);
+        {
+          // dQ += dS K, the transposed K operands requested one pair of MFMAs ahead
+          constexpr int NB = HeadDim<DH>::NB;
+          bf16x8 fr[2][2];
+          fr[0][0] = frag_cols<HeadDim<DH>::DHL>(Ks, 0, b * 32, lane);
+          fr[0][1] = frag_cols<HeadDim<DH>::DHL>(Ks, 0, b * 32 + 16, lane);
+#pragma unroll
+          for (int j = 0; j < NB; ++j) {
+            if (j + 1 < NB) {
+              fr[(j + 1) & 1][0] = frag_cols<HeadDim<DH>::DHL>(Ks, (j + 1) * 32, b * 32, lane);
+              fr[(j + 1) & 1][1] = frag_cols<HeadDim<DH>::DHL>(Ks, (j + 1) * 32, b * 32 + 16, lane);
+            }
+            dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][0], s0, dqacc[j], 0, 0, 0);
+            dqacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 1][1], s1, dqacc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
       }
     }
   };
+  int n_plain = Lk / FK;
+  if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
+  n_plain = min(n_plain, nkt);
   int kt = 0;
-  if (DH <= 72) {        // at head size 128 the second copy costs more in spilled registers than it saves
-    int n_plain = Lk / FK;
-    if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
-    n_plain = min(n_plain, nkt);
-    for (; kt < n_plain; ++kt) step(kt, std::false_type{});
-  }
+  for (; kt < n_plain; ++kt) step(kt, std::false_type{});
   for (; kt < nkt; ++kt) step(kt, std::true_type{});
   if (qpos < L) {
     bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
