@@ -92,6 +92,18 @@ __device__ inline bf16x8 frag_cols(const bf16_t* t, int col0, int r0, int lane) 
   return u.v;
 }
 
+// max / sum of a value with the one held by the lane 32 away (the two halves of a wavefront own
+// the same score column): v_permlane32_swap exchanges the halves in the vector unit, without the
+// trip through the LDS crossbar that a lane shuffle takes
+__device__ inline float max_with_other_half(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float sum_with_other_half(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // accumulator rows 8t..8t+7 of a 32x32 block -> bf16 B operand of a k=16 step
 __device__ inline bf16x8 acc_to_operand(const f32x16& a, int t) {
   bf16x8 r;
@@ -264,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
         }
         mx = fmaxf(mx, sacc[b][r]);
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+      mx = max_with_other_half(mx) * scale_log2;
       // Lazy rescaling: the running maximum only moves (and O, l are only rescaled)
       // when some row's maximum grew by more than 2^8; until then probabilities are
       // taken relative to the older maximum (they stay below 2^8, exact in fp32).
@@ -313,7 +325,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   int kt = 0;
   for (; kt < n_plain; ++kt) step(kt, std::false_type{});
   for (; kt < nkt; ++kt) step(kt, std::true_type{});
-  lsum += __shfl_xor(lsum, 32, 64);
+  lsum = sum_with_other_half(lsum);
   if (qpos < L) {
     const float inv = 1.0f / lsum;
     bf16_t* op = o + (size_t)(lo + qpos) * ldo + hq * DH;
