@@ -189,13 +189,18 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     const float mean = stats[row], rstd = stats[rows + row];
     const float* mrow = nullptr;
     if (KIND == BM_NORM_ADALN) mrow = mod + (size_t)tok_seq[row] * ld_mod;
-    float xv[NV][VEC], gv[NV][VEC], resv[NV][VEC];
+    // The residual gradient is only needed after the row reductions.  Narrow rows fetch it with
+    // the rest (one memory latency per row less); wide rows would pay for that with registers
+    // and lose a resident wavefront, so they fetch it late.
+    constexpr bool EARLY_RES = NV <= 4;
+    float xv[NV][VEC], gv[NV][VEC], resv[EARLY_RES ? NV : 1][VEC];
     float s1 = 0.f, s2 = 0.f;
-    // the residual gradient is only needed after the row reductions: fetch it with the rest
+    if (EARLY_RES) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      int col = (i * WAVE + lane) * VEC;
-      if (col < d) load16(dres + off + col, resv[i]);
+      for (int i = 0; i < NV; ++i) {
+        int col = (i * WAVE + lane) * VEC;
+        if (col < d) load16(dres + off + col, resv[EARLY_RES ? i : 0]);
+      }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -230,8 +235,13 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     for (int i = 0; i < NV; ++i) {
       int col = (i * WAVE + lane) * VEC;
       if (col < d) {
-        float out[VEC];
-        const float (&res)[VEC] = resv[i];
+        float out[VEC], res[VEC];
+        if (EARLY_RES) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) res[e] = resv[EARLY_RES ? i : 0][e];
+        } else {
+          load16(dres + off + col, res);
+        }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           float v;
