@@ -155,7 +155,9 @@ template <int KIND, bool SUMS> struct NormBwdParts {
 // per lane at 128 and the column accumulators spill)
 template <int NV> struct NormBwdWaves { static constexpr int N = 4; };
 
-template <typename T, int KIND, int NV, bool SUMS>
+// SPLIT wavefronts share one row (wide rows: half the registers per wavefront, twice the resident
+// wavefronts); they exchange their partial row sums through LDS, one barrier per row.
+template <typename T, int KIND, int NV, bool SUMS, int SPLIT = 1>
 __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dh,
     const T* __restrict__ dres, T* __restrict__ dx, T* __restrict__ h_out,
@@ -167,14 +169,19 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
   constexpr int NP = NormBwdParts<KIND, SUMS>::NP;
   constexpr int NS = SUMS ? NV : 1;
   constexpr int NW = NormBwdWaves<NV>::N;
+  constexpr int RPB = NW / SPLIT;          // rows per workgroup and trip
   extern __shared__ float sm[];   // [d]
+  __shared__ float rowsum[2][RPB][SPLIT][2];     // two trips' worth: one barrier per trip is enough
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int slot = wave / SPLIT, part = wave % SPLIT;
+  // column of vector i of this wavefront
+  auto col_of = [&](int i) { return ((i * SPLIT + part) * WAVE + lane) * VEC; };
   float gam[NV][VEC];
   float acc_g[NV][VEC], acc_b[NV][VEC];
   float acc_r[NS][VEC], acc_o[NS][VEC];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int col = (i * WAVE + lane) * VEC;
+    const int col = col_of(i);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { acc_g[i][e] = 0.f; acc_b[i][e] = 0.f; gam[i][e] = 1.f; }
     if (KIND != BM_NORM_ADALN && col < d) load16(gamma + col, gam[i]);
@@ -184,7 +191,13 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { acc_r[i][e] = 0.f; acc_o[i][e] = 0.f; }
   const float inv_d = 1.0f / (float)d;
-  for (int row = blockIdx.x * NW + wave; row < rows; row += gridDim.x * NW) {
+  int trip = 0;
+  // With rows shared between wavefronts every wavefront of the workgroup makes the same trips (the
+  // barrier below); one whose row lies past the end works on the last row again and stores nothing.
+  // Unshared rows need neither: such a wavefront simply stops.
+  for (int base = blockIdx.x * RPB; SPLIT > 1 ? base < rows : base + slot < rows; base += gridDim.x * RPB, ++trip) {
+    const bool live = SPLIT > 1 ? base + slot < rows : true;
+    const int row = live ? base + slot : rows - 1;
     const size_t off = (size_t)row * d;
     const float mean = stats[row], rstd = stats[rows + row];
     const float* mrow = nullptr;
@@ -198,17 +211,21 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
     if (EARLY_RES) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        int col = (i * WAVE + lane) * VEC;
+        const int col = col_of(i);
         if (col < d) load16(dres + off + col, resv[EARLY_RES ? i : 0]);
       }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int col = (i * WAVE + lane) * VEC;
+      const int col = col_of(i);
       if (col < d) {
         float dhv[VEC];
         load16(x + off + col, xv[i]);
         load16(dh + off + col, dhv);
+        if (!live) {          // a repeated row must not count in the column sums
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) dhv[e] = 0.f;
+        }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           float g;
@@ -228,12 +245,21 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
         }
       }
     }
-    s2 = wave_sum(s2) * inv_d;
-    if (KIND != BM_NORM_RMSNORM) s1 = wave_sum(s1) * inv_d;
+    s2 = wave_sum(s2);
+    if (KIND != BM_NORM_RMSNORM) s1 = wave_sum(s1);
+    if (SPLIT > 1) {
+      if (lane == 0) { rowsum[trip & 1][slot][part][0] = s1; rowsum[trip & 1][slot][part][1] = s2; }
+      __syncthreads();
+      s1 = 0.f; s2 = 0.f;
+#pragma unroll
+      for (int q = 0; q < SPLIT; ++q) { s1 += rowsum[trip & 1][slot][q][0]; s2 += rowsum[trip & 1][slot][q][1]; }
+    }
+    s2 *= inv_d;
+    s1 *= inv_d;
     const float r3 = rstd * rstd * rstd;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int col = (i * WAVE + lane) * VEC;
+      const int col = col_of(i);
       if (col < d) {
         float out[VEC], res[VEC];
         if (EARLY_RES) {
@@ -249,14 +275,17 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
           else v = rstd * (gv[i][e] - s1 - xv[i][e] * s2);
           out[e] = res[e] + v;
         }
-        store16(dx + off + col, out);
+        if (live) store16(dx + off + col, out);
         if (SUMS) {
           // sum what the consumer reads: the stored (rounded) gradient
           float stored[VEC];
 #pragma unroll
           for (int e = 0; e < VEC; ++e) stored[e] = Elt<T>::to_f(Elt<T>::from_f(out[e]));
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) { acc_r[SUMS ? i : 0][e] += res[e]; acc_o[SUMS ? i : 0][e] += stored[e]; }
+          for (int e = 0; e < VEC; ++e) {
+            acc_r[SUMS ? i : 0][e] += live ? res[e] : 0.f;
+            acc_o[SUMS ? i : 0][e] += live ? stored[e] : 0.f;
+          }
         }
         if (h_out) {
           float hv[VEC];
@@ -273,7 +302,7 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
             for (int e = 0; e < VEC; ++e)
               hv[e] = xv[i][e] * (1.0f + mrow[scale_off + col + e]) + mrow[shift_off + col + e];
           }
-          store16(h_out + off + col, hv);
+          if (live) store16(h_out + off + col, hv);
         }
       }
     }
@@ -286,13 +315,13 @@ __global__ __launch_bounds__(NormBwdWaves<NV>::N * 64) void norm_bwd_kernel(
       if (wave == w) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-          int col = (i * WAVE + lane) * VEC;
+          const int col = col_of(i);
           if (col < d) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
               float v = what == 0 ? acc_g[i][e] : what == 1 ? acc_b[i][e]
                       : what == 2 ? acc_r[SUMS ? i : 0][e] : acc_o[SUMS ? i : 0][e];
-              if (w == 0) sm[col + e] = v; else sm[col + e] += v;
+              if (w < SPLIT) sm[col + e] = v; else sm[col + e] += v;   // the first wavefront on these columns
             }
           }
         }
@@ -509,16 +538,19 @@ static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float
   int nv = cdiv(a.d, WAVE * VEC);
   dim3 grid(norm_bwd_blocks(a.T));
   size_t lds = (size_t)a.d * sizeof(float);
-#define BM_LAUNCH_NV(NVV)                                                                        \
-  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS>), grid, dim3(NormBwdWaves<NVV>::N * 64), lds, st, (const T*)x,   \
+#define BM_LAUNCH_NV(NVV, SP)                                                                    \
+  hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS, SP>), grid, dim3(NormBwdWaves<NVV>::N * 64), lds, st, (const T*)x,   \
                      stats, (const T*)dh, (const T*)dres, (T*)dx, (T*)h_out, (const T*)a.gamma,  \
                      (const T*)a.beta, a.mod, a.ld_mod, a.shift_off, a.scale_off, a.tok_seq,     \
                      partial, a.T, a.d)
-  if (nv <= 1) BM_LAUNCH_NV(1);
-  else if (nv <= 2) BM_LAUNCH_NV(2);
-  else if (nv <= 4) BM_LAUNCH_NV(4);
-  else if (nv <= 8) BM_LAUNCH_NV(8);
-  else if (nv <= 16) BM_LAUNCH_NV(16);
+  // rows of 4 or more vectors per lane are shared by two wavefronts (measured: 1152-wide rows are
+  // faster unshared, 2048-wide and wider ones shared)
+  if (nv <= 1) BM_LAUNCH_NV(1, 1);
+  else if (nv <= 2) BM_LAUNCH_NV(2, 1);
+  else if (nv <= 3) BM_LAUNCH_NV(4, 1);
+  else if (nv <= 4) BM_LAUNCH_NV(2, 2);
+  else if (nv <= 8) BM_LAUNCH_NV(4, 2);
+  else if (nv <= 16) BM_LAUNCH_NV(8, 2);
   else { set_error("norm: hidden %d too wide", a.d); return BM_ERR_UNSUPPORTED; }
 #undef BM_LAUNCH_NV
   BM_CHECK_LAUNCH("norm_bwd");

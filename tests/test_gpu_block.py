@@ -59,6 +59,12 @@ def small_cases():
     out.append(synth.make_case(synth.scaled(synth.dit_block(), hidden=144, n_q_heads=2, n_kv_heads=2,
                                             head_dim=72, mlp_hidden=160, dtype=f32), [50, 21], 34,
                                name="dit_dh72_fp32"))
+    # fp32 rows wider than four vectors per lane: the norm backward splits them over two wavefronts
+    out.append(synth.make_case(synth.scaled(synth.vit_tiny(f32), hidden=1280, n_q_heads=80, n_kv_heads=80,
+                                            head_dim=16, mlp_hidden=64), [9, 4], 35, name="vit_wide_d1280_fp32"))
+    out.append(synth.make_case(synth.scaled(synth.dit_block(), hidden=1536, n_q_heads=96, n_kv_heads=96,
+                                            head_dim=16, mlp_hidden=64, dtype=f32), [5, 6], 36,
+                               name="dit_wide_d1536_fp32"))
     return out
 
 
@@ -76,6 +82,13 @@ def medium_bf16_cases():
     out.append(synth.make_case(synth.dit_block(), [256, 256, 256], 44, name="dit_bf16_3img"))
     out.append(synth.make_case(synth.scaled(synth.vit_tiny(), dtype=synth.DTYPE_BF16), [16, 24], 45,
                                name="vit_tiny_bf16"))
+    # wide rows (two wavefronts share a row in the norm backward), odd row counts
+    out.append(synth.make_case(synth.scaled(synth.vit_large(), hidden=2560, n_q_heads=20, n_kv_heads=20,
+                                            head_dim=128, mlp_hidden=1024), [70, 1], 46, name="vit_wide_d2560_bf16"))
+    out.append(synth.make_case(synth.scaled(synth.decoder_7b(), mlp_hidden=1024), [33, 40], 47,
+                               name="decoder_wide_d4096_bf16"))
+    out.append(synth.make_case(synth.scaled(synth.dit_block(), hidden=3072, n_q_heads=24, n_kv_heads=24,
+                                            head_dim=128, mlp_hidden=1024), [64, 7, 64], 48, name="dit_wide_d3072_bf16"))
     return out
 
 
