@@ -274,8 +274,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   sa.store(smem, tid);
   sb.store(smem + 2 * A_TILE, tid);
   if (kbeg + BK < kend) {
-    sa.load(a_base + a_step, p.lda, kend - kbeg - BK, tid);
-    sb.load(b_base + b_step, p.ldb, kend - kbeg - BK, tid);
+    // same issue order as in the steady-state loop (part by part, A then B): the compiler's
+    // wait-count bookkeeping merges this order with the loop's at the loop header, and any
+    // difference makes the loop wait for younger loads than the one it stores
+    constexpr int PA0 = Stage<BM, NT, A_TR, KTAIL>::PER, PB0 = Stage<BN, NT, B_TR, KTAIL>::PER;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+#pragma unroll
+      for (int i = 0; i < PA0; ++i) sa.load_one(ks * PA0 + i, a_base + a_step, p.lda, kend - kbeg - BK, tid);
+#pragma unroll
+      for (int i = 0; i < PB0; ++i) sb.load_one(ks * PB0 + i, b_base + b_step, p.ldb, kend - kbeg - BK, tid);
+    }
   }
   __syncthreads();
 
