@@ -426,7 +426,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
             *reinterpret_cast<f32x4*>(c) = f32x4{out[0], out[1], out[2], out[3]};
             *reinterpret_cast<f32x4*>(c + 4) = f32x4{out[4], out[5], out[6], out[7]};
           } else {
-            store16((bf16_t*)p.C + idx, out);
+            {
+              union { u32x4 u; bf16_t h[8]; } pk;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) pk.h[e] = Elt<bf16_t>::from_f(out[e]);
+              __builtin_nontemporal_store(pk.u, reinterpret_cast<u32x4*>((bf16_t*)p.C + idx));
+            }
           }
         }
       }
