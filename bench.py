@@ -37,9 +37,9 @@ HBM_PEAK_GBS = 8000.0
 MIB = 1048576.0
 MEASURED_TRAFFIC_BYTES = {
     "config2_vit_large_bf16": {
-        "gemm_tn": 360.6 * MIB,
-        "gemm_nt": 232.4 * MIB,
-        "gemm_nn": 200.3 * MIB,
+        "gemm_tn": 392.4 * MIB,      # 3 launches (232.4 + 64.0) and 4 split-k reductions (60.0 + 12.0) per step
+        "gemm_nt": 236.4 * MIB,      # 164.4 fetched + 72.0 written
+        "gemm_nn": 200.4 * MIB,      # 144.4 fetched + 56.0 written
     },
 }
 
