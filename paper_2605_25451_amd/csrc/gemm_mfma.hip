@@ -702,6 +702,13 @@ bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int 
     set_error("grouped gemm: group tables are NULL");
     return BM_ERR_INVALID_ARG;
   }
+  // row tiles are pinned to 128 rows (one MOE_PAD block); 256 columns per tile where the output is
+  // wide enough: per flop a 128x256 tile writes and reads a quarter less LDS than two 128x128 ones
+  if (layout != GEMM_TN && N >= 256) {
+    p.tiles_n = cdiv(N, 256);
+    if (layout == GEMM_NT) return launch<128, 256, 2, 2, false, false, false>(p, st);
+    return launch<128, 256, 2, 2, false, true, false>(p, st);
+  }
   if (layout == GEMM_NT) return launch<128, 128, 2, 2, false, false, false>(p, st);
   if (layout == GEMM_NN) return launch<128, 128, 2, 2, false, true, false>(p, st);
   // weight gradient: rows are the contraction index, so the output tile is free; a group's
