@@ -342,16 +342,22 @@ __global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_kernel(
   __shared__ float sm[PR_GROUPS][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int g = threadIdx.x >> 6;
-  float s0 = 0.f, s1 = 0.f;
+  // eight independent loads in flight per thread: the partials come from L2 or further away and
+  // the loop is bound by that latency, not by bandwidth
+  float s[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) s[u] = 0.f;
   if (c < n) {
     int p = g;
-    for (; p + PR_GROUPS < nparts; p += 2 * PR_GROUPS) {
-      s0 += partial[(size_t)p * stride + c];
-      s1 += partial[(size_t)(p + PR_GROUPS) * stride + c];
+    for (; p + 7 * PR_GROUPS < nparts; p += 8 * PR_GROUPS) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s[u] += partial[(size_t)(p + u * PR_GROUPS) * stride + c];
     }
-    if (p < nparts) s0 += partial[(size_t)p * stride + c];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p + u * PR_GROUPS < nparts) s[u] += partial[(size_t)(p + u * PR_GROUPS) * stride + c];
   }
-  sm[g][threadIdx.x & 63] = s0 + s1;
+  sm[g][threadIdx.x & 63] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
   __syncthreads();
   if (g == 0 && c < n) {
     const int l = threadIdx.x;
@@ -372,16 +378,22 @@ __global__ __launch_bounds__(64 * PR_GROUPS) void partial_reduce_multi_kernel(
   float* __restrict__ out = t.out[blockIdx.y];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int g = threadIdx.x >> 6;
-  float s0 = 0.f, s1 = 0.f;
+  // eight independent loads in flight per thread: the partials come from L2 or further away and
+  // the loop is bound by that latency, not by bandwidth
+  float s[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) s[u] = 0.f;
   if (c < n) {
     int p = g;
-    for (; p + PR_GROUPS < nparts; p += 2 * PR_GROUPS) {
-      s0 += partial[(size_t)p * stride + c];
-      s1 += partial[(size_t)(p + PR_GROUPS) * stride + c];
+    for (; p + 7 * PR_GROUPS < nparts; p += 8 * PR_GROUPS) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s[u] += partial[(size_t)(p + u * PR_GROUPS) * stride + c];
     }
-    if (p < nparts) s0 += partial[(size_t)p * stride + c];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p + u * PR_GROUPS < nparts) s[u] += partial[(size_t)(p + u * PR_GROUPS) * stride + c];
   }
-  sm[g][threadIdx.x & 63] = s0 + s1;
+  sm[g][threadIdx.x & 63] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
   __syncthreads();
   if (g == 0 && c < n) {
     const int l = threadIdx.x;
