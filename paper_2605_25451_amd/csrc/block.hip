@@ -310,7 +310,8 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
   hipStream_t st = (hipStream_t)hip_stream;
   const int dt = c.dtype;
 
-  BM_RETURN_IF(launch_tok_seq(cu_dev, S, T, ws.tok_seq, st));
+  // token -> sequence map: read by the rotary embedding and by the per-sequence modulation only
+  if (c.rope || m.ada) BM_RETURN_IF(launch_tok_seq(cu_dev, S, T, ws.tok_seq, st));
   if (m.ada) {
     BM_RETURN_IF(silu_forward(dt, cond, ws.sc, (long)S * m.d, st));
     GemmEpilogue e; e.bias = w->b_ada; e.out_fp32 = 1;
@@ -418,7 +419,8 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   const GemmEpilogue none;
   const int d = m.d;
 
-  BM_RETURN_IF(launch_tok_seq(cu_dev, S, T, ws.tok_seq, st));
+  // token -> sequence map: read by the rotary embedding and by the per-sequence modulation only
+  if (c.rope || m.ada) BM_RETURN_IF(launch_tok_seq(cu_dev, S, T, ws.tok_seq, st));
 
   // ---- y = x1 + [g2 *] m,  m = a W_down^T + b_down
   const void* dm = dy;
