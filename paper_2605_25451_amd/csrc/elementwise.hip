@@ -558,7 +558,7 @@ static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float
   // rows of 4 or more vectors per lane are shared by two wavefronts (measured: 1152-wide rows are
   // faster unshared, 2048-wide and wider ones shared)
   if (nv <= 1) BM_LAUNCH_NV(1, 1);
-  else if (nv <= 2) BM_LAUNCH_NV(2, 1);
+  else if (nv <= 2) { if (SUMS) BM_LAUNCH_NV(1, 2); else BM_LAUNCH_NV(2, 1); }
   else if (nv <= 3) BM_LAUNCH_NV(4, 1);
   else if (nv <= 4) BM_LAUNCH_NV(2, 2);
   else if (nv <= 8) BM_LAUNCH_NV(4, 2);
