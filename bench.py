@@ -41,6 +41,11 @@ MEASURED_TRAFFIC_BYTES = {
         "gemm_nt": 236.4 * MIB,      # 164.4 fetched + 72.0 written
         "gemm_nn": 200.4 * MIB,      # 144.4 fetched + 56.0 written
     },
+    "config3_decoder_7b_bf16": {     # no k split at these sizes: the class is the GEMM kernel alone
+        "gemm_tn": 1666.3 * MIB,     # 1473.3 fetched + 193.0 written
+        "gemm_nt": 1360.3 * MIB,     # 1194.3 fetched + 166.0 written
+        "gemm_nn": 1259.4 * MIB,     # 1168.4 fetched + 91.0 written
+    },
 }
 
 
