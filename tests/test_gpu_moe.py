@@ -76,6 +76,9 @@ BF16_CASES = [
     ("moe_e8k2_d512_bf16", moe_cfg(synth.DTYPE_BF16, 512, 4, 2, 128, 256, 8, 2, 0.2), [300, 257, 143, 1, 67], 64),
     ("moe_e128k8_d1024_bf16", moe_cfg(synth.DTYPE_BF16, 1024, 8, 2, 128, 256, 128, 8, 0.1), [700, 324], 65),
     ("moe_e16k4_d512_empty_experts_bf16", moe_cfg(synth.DTYPE_BF16, 512, 4, 4, 128, 128, 16, 4, 0.5), [5, 3], 67),
+    # expert width 200: the 256-column tiles of the grouped products end in a ragged tile (400 = 256 + 144
+    # columns) and the down projection contracts over a k range that is not a whole number of slices
+    ("moe_e8k2_d512_f200_bf16", moe_cfg(synth.DTYPE_BF16, 512, 4, 2, 128, 200, 8, 2, 0.2), [190, 333, 64], 68),
 ]
 
 
