@@ -103,7 +103,11 @@ const char* bm_last_error(void);
 
 /* Bytes the caller must provide for `saved` (kept from forward to backward)
  * and for `scratch` (free after each call; max over forward and backward).
- * T packed tokens in S sequences, none longer than max_seqlen. */
+ * T packed tokens in S sequences, none longer than max_seqlen.
+ * Size limit of every block call: rows x widest row (the larger of the packed
+ * q|k|v width, the up-projection width and hidden; rows = T, or the padded
+ * expert capacity of a mixture block) must stay below 2^31 elements; larger
+ * packs return BM_ERR_INVALID_ARG and are to be split by the caller. */
 bm_status bm_block_sizes(const bm_block_desc* desc, int32_t T, int32_t S, int32_t max_seqlen,
                          size_t* saved_bytes, size_t* scratch_bytes);
 

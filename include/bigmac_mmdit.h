@@ -42,6 +42,9 @@ typedef struct {
   void* k_norm_g[2];
 } bm_mmdit_params;              /* gradients: same layout, fp32                                    */
 
+/* Size limit of every call: (T_text + T_img) x widest row (the larger of the packed q|k|v
+ * width, mlp_hidden and hidden) must stay below 2^31 elements; larger packs return
+ * BM_ERR_INVALID_ARG. */
 bm_status bm_mmdit_sizes(const bm_mmdit_desc* desc, int32_t T_text, int32_t T_img, int32_t S,
                          size_t* saved_bytes, size_t* scratch_bytes);
 

@@ -275,12 +275,28 @@ NormArgs norm_args(const bm_block_desc& c, const Dims& m, int which, const bm_bl
 
 using namespace bm;
 
+// No tensor of a call may reach 2^31 elements: the packs the kernels have been exercised on stay
+// far below (32768 tokens x 28672 columns), and larger ones are refused rather than trusted.
+static bm_status check_extent(const bm_block_desc& c, int T, int S) {
+  // the token count alone must leave room for the padded expert capacity of a mixture block
+  BM_ARG_CHECK(c.n_experts == 0 || (long)T * c.top_k + (long)c.n_experts * MOE_PAD < (1L << 31),
+               "T = %d tokens x %d choices is too large", T, c.top_k);
+  const Dims m = make_dims(c, T, S);
+  long widest = m.QKV > m.UP ? m.QKV : m.UP;
+  if (m.d > widest) widest = m.d;
+  const long rows = m.cap > T ? m.cap : T;
+  BM_ARG_CHECK(rows * widest < (1L << 31),
+               "%ld rows x %ld columns reach 2^31 elements: split the pack", rows, widest);
+  return BM_OK;
+}
+
 extern "C" bm_status bm_block_sizes(const bm_block_desc* desc, int32_t T, int32_t S,
                                     int32_t max_seqlen, size_t* saved_bytes, size_t* scratch_bytes) {
   BM_RETURN_IF(check_desc(desc));
   BM_ARG_CHECK(T >= 1 && S >= 1 && S <= T && max_seqlen >= 1 && max_seqlen <= T,
                "bm_block_sizes: bad T=%d S=%d max_seqlen=%d", T, S, max_seqlen);
   BM_ARG_CHECK(saved_bytes && scratch_bytes, "bm_block_sizes: output pointers are NULL");
+  BM_RETURN_IF(check_extent(*desc, T, S));
   Dims m = make_dims(*desc, T, S);
   *saved_bytes = layout_saved(m, nullptr).bytes;
   size_t f = layout_fwd(m, nullptr).bytes, b = layout_bwd(m, desc->dtype, nullptr).bytes;
@@ -296,6 +312,7 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
   BM_RETURN_IF(check_desc(desc));
   const bm_block_desc& c = *desc;
   BM_RETURN_IF(check_seqs(cu_dev, cu_host, S, T, max_seqlen));
+  BM_RETURN_IF(check_extent(c, T, S));
   BM_RETURN_IF(check_params(c, w, "w"));
   NEED_PTR(x); NEED_PTR(y); NEED_PTR(saved); NEED_PTR(scratch);
   BM_ARG_CHECK(x != y, "y must not alias x");
@@ -402,6 +419,7 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   BM_RETURN_IF(check_desc(desc));
   const bm_block_desc& c = *desc;
   BM_RETURN_IF(check_seqs(cu_dev, cu_host, S, T, max_seqlen));
+  BM_RETURN_IF(check_extent(c, T, S));
   BM_RETURN_IF(check_params(c, w, "w"));
   BM_RETURN_IF(check_params(c, grads, "grads"));
   NEED_PTR(x); NEED_PTR(dy); NEED_PTR(dx); NEED_PTR(saved); NEED_PTR(scratch);

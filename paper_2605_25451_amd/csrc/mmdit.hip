@@ -434,6 +434,16 @@ bm_status check_streams(const int32_t* const cu_dev[2], const int32_t* const cu_
   return BM_OK;
 }
 
+// no tensor of a call may reach 2^31 elements (joint rows x the widest row), as for the single-stream block
+bm_status check_mextent(const bm_mmdit_desc& c, long T_text, long T_img) {
+  const long d = c.block.hidden, qkv = 3L * c.block.n_q_heads * c.block.head_dim, up = c.block.mlp_hidden;
+  long widest = qkv > up ? qkv : up;
+  if (d > widest) widest = d;
+  BM_ARG_CHECK((T_text + T_img) * widest < (1L << 31),
+               "%ld joint rows x %ld columns reach 2^31 elements: split the pack", T_text + T_img, widest);
+  return BM_OK;
+}
+
 NormArgs ada_norm_args(const bm_block_desc& c, int T, int which, const float* mod, const int32_t* tok_seq) {
   NormArgs n;
   n.dtype = c.dtype; n.kind = BM_NORM_ADALN; n.T = T; n.d = c.hidden; n.eps = c.norm_eps;
@@ -465,6 +475,7 @@ extern "C" bm_status bm_mmdit_sizes(const bm_mmdit_desc* desc, int32_t T_text, i
   BM_RETURN_IF(check_mdesc(desc));
   BM_ARG_CHECK(S >= 1 && T_text >= S && T_img >= S, "bm_mmdit_sizes: bad T_text=%d T_img=%d S=%d", T_text, T_img, S);
   BM_ARG_CHECK(saved_bytes && scratch_bytes, "bm_mmdit_sizes: output pointers are NULL");
+  BM_RETURN_IF(check_mextent(*desc, T_text, T_img));
   MDims m = make_mdims(*desc, T_text, T_img, S);
   *saved_bytes = layout_saved(m, nullptr).bytes;
   size_t f = layout_fwd(m, nullptr).bytes, b = layout_bwd(m, desc->block.dtype, nullptr).bytes;
@@ -485,6 +496,7 @@ extern "C" bm_status bm_mmdit_forward(const bm_mmdit_desc* desc, const bm_mmdit_
   std::vector<int32_t> jcu_host;
   int Ts[2], max_joint;
   BM_RETURN_IF(check_streams(cu_dev, cu_host, S, jcu_host, Ts, &max_joint));
+  BM_RETURN_IF(check_mextent(*desc, Ts[0], Ts[1]));
   BM_RETURN_IF(check_stream_params(*desc, w, "w"));
   NEED_PTR(x_text); NEED_PTR(x_img); NEED_PTR(y_text); NEED_PTR(y_img); NEED_PTR(cond); NEED_PTR(saved);
   NEED_PTR(scratch);
@@ -578,6 +590,7 @@ extern "C" bm_status bm_mmdit_backward(const bm_mmdit_desc* desc, const bm_mmdit
   std::vector<int32_t> jcu_host;
   int Ts[2], max_joint;
   BM_RETURN_IF(check_streams(cu_dev, cu_host, S, jcu_host, Ts, &max_joint));
+  BM_RETURN_IF(check_mextent(*desc, Ts[0], Ts[1]));
   BM_RETURN_IF(check_stream_params(*desc, w, "w"));
   BM_RETURN_IF(check_stream_params(*desc, grads, "grads"));
   NEED_PTR(x_text); NEED_PTR(x_img); NEED_PTR(dy_text); NEED_PTR(dy_img); NEED_PTR(dx_text); NEED_PTR(dx_img);

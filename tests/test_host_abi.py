@@ -92,3 +92,11 @@ def test_block_sizes_and_descriptor_validation():
     assert e.value.status == bm.BM_ERR_UNSUPPORTED
     with pytest.raises(bm.BmError):
         bm.block_sizes(desc, 0, 1, 1)
+    # no tensor of a call may reach 2^31 elements: 2^19 tokens x 4096 columns is refused, half of it is not
+    with pytest.raises(bm.BmError) as e:
+        bm.block_sizes(desc, 1 << 19, 512, 1024)
+    assert e.value.status == bm.BM_ERR_INVALID_ARG and "2^31" in str(e.value)
+    bm.block_sizes(desc, (1 << 18), 256, 1024)
+    moe = bm.make_desc(synth.decoder_moe())
+    with pytest.raises(bm.BmError):
+        bm.block_sizes(moe, 1 << 28, 1 << 10, 1 << 18)         # tokens x choices leaves the int range
