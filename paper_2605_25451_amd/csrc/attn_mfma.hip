@@ -367,13 +367,15 @@ bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
 // =============================================================================
 // backward
 // =============================================================================
-// delta[h, t] = sum_c dO[t,h,c] * O[t,h,c]; 16 lanes share one (row, head), 16 bytes each, so a
-// wavefront reads whole contiguous row segments
+// delta[h, t] = sum_c dO[t,h,c] * O[t,h,c]; 8 (head size 64) or 16 lanes share one (row, head),
+// 16 bytes each, so a wavefront reads whole contiguous row segments
+template <int DH> struct DeltaLanes { static constexpr int N = DH <= 64 ? 8 : 16, SHIFT = DH <= 64 ? 3 : 4; };
 template <int DH>
 __global__ void fa_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int ldo,
                                 float* __restrict__ delta, int Ttot, int Hq) {
-  const long gid = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
-  const int c = (threadIdx.x & 15) * 8;
+  constexpr int LP = DeltaLanes<DH>::N;
+  const long gid = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> DeltaLanes<DH>::SHIFT;
+  const int c = (threadIdx.x & (LP - 1)) * 8;
   float s = 0.f;
   const bool live = gid < (long)Ttot * Hq;
   const int t = live ? (int)(gid / Hq) : 0, hq = live ? (int)(gid % Hq) : 0;
@@ -385,7 +387,7 @@ __global__ void fa_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __re
     for (int e = 0; e < 8; ++e) s = fmaf(a[e], b[e], s);
   }
 #pragma unroll
-  for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  for (int off = LP / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
   if (live && c == 0) delta[(size_t)hq * Ttot + t] = s;
 }
 
@@ -813,7 +815,7 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const float sl2 = scale * LOG2E;
   const long n = (long)a.T * a.Hq;
   if (n > 0)
-    hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n * 16, 256)), dim3(256), 0, st, (const bf16_t*)o,
+    hipLaunchKernelGGL((fa_delta_kernel<DH>), dim3(cdiv(n * DeltaLanes<DH>::N, 256)), dim3(256), 0, st, (const bf16_t*)o,
                        (const bf16_t*)d_o, ldo, delta, a.T, a.Hq);
   const int ktiles = count_tiles(a.kv_cu_host(), a.S, BK_KEYS);
   const int gsplit = ktiles > 0 ? dkdv_group_split(ktiles, a.Hkv, a.Hq / a.Hkv) : 1;
