@@ -179,6 +179,27 @@ bm_status bm_attention_backward(int32_t dtype, int32_t mask, int32_t Hq, int32_t
                                 void* dq, void* dk, void* dv, int32_t ld_dqkv,
                                 void* scratch, size_t scratch_bytes, void* hip_stream);
 
+/* The same operation for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is
+ * bm_attention_backward with the workspace taken from a fixed array of
+ * BM_ATTENTION_STATIC_SCRATCH_BYTES that is part of the library's device code (each GPU the
+ * library runs on holds its own copy until the process ends); the call allocates and frees
+ * nothing.  Arguments, outputs and validation are those of bm_attention_backward.  Shapes whose
+ * workspace (bm_attention_backward_scratch_bytes) exceeds the array return
+ * BM_ERR_WORKSPACE_TOO_SMALL and launch nothing.  Every call on a GPU shares that GPU's array:
+ * calls that overlap on one GPU (two streams, two threads) race on it and must be serialised
+ * by the caller.  The array keeps the previous call's contents; nothing in it needs clearing,
+ * because every byte the kernels read from it is written earlier in the same call.
+ * bm_attention_backward_static_capacity() returns BM_ATTENTION_STATIC_SCRATCH_BYTES. */
+#define BM_ATTENTION_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+size_t    bm_attention_backward_static_capacity(void);
+bm_status bm_attention_backward_static(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv, int32_t dh,
+                                       const void* q, const void* k, const void* v, int32_t ld_qkv,
+                                       const void* o, const void* d_o, const float* lse,
+                                       const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                                       int32_t S, int32_t T, int32_t max_seqlen,
+                                       void* dq, void* dk, void* dv, int32_t ld_dqkv, void* hip_stream);
+
 /* ---- measurement: per-kernel-class timing ------------------------------------------- */
 
 /* Between bm_profile_begin() and bm_profile_end() every kernel group the library

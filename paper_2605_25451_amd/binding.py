@@ -137,6 +137,11 @@ def lib() -> C.CDLL:
         l.bm_attention_backward_scratch_bytes.restype = sz
         l.bm_attention_backward.argtypes = ([i32] * 5 + [vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32,
                                                           i32, vp, vp, vp, i32, vp, sz, vp])
+        l.bm_attention_backward_static_capacity.argtypes = []
+        l.bm_attention_backward_static_capacity.restype = sz
+        l.bm_attention_backward_static.argtypes = ([i32] * 5 + [vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32,
+                                                                i32, vp, vp, vp, i32, vp])
+        l.bm_attention_backward_static.restype = C.c_int
         l.bm_profile_begin.argtypes = []
         l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.bm_probe_mfma.argtypes = [i32, i32, vp, vp]
@@ -342,6 +347,19 @@ def attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, c
                                        cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
                                        _ptr(dv), ld_dqkv, _ptr(scratch), scratch_bytes,
                                        _stream() if stream is None else stream))
+
+
+def attention_backward_static_capacity() -> int:
+    return lib().bm_attention_backward_static_capacity()
+
+
+def attention_backward_static(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, cu_seqlens_dev,
+                              cu_seqlens_host, S, T, max_seqlen, dq, dk, dv, ld_dqkv, stream=None):
+    cu_h = _host_cu(cu_seqlens_host)
+    _check(lib().bm_attention_backward_static(dtype, mask, Hq, Hkv, dh, _ptr(q), _ptr(k), _ptr(v), ld_qkv,
+                                              _ptr(o), _ptr(d_o), _ptr(lse), _ptr(cu_seqlens_dev),
+                                              cu_h.ctypes.data, S, T, max_seqlen, _ptr(dq), _ptr(dk),
+                                              _ptr(dv), ld_dqkv, _stream() if stream is None else stream))
 
 
 def _ptr_array(tensors):

@@ -6,6 +6,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
 #include <vector>
 
 namespace bm {
@@ -222,4 +223,65 @@ extern "C" bm_status bm_attention_backward(int32_t dtype, int32_t mask, int32_t 
   AttnArgs a{dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, cu_dev, cu_host, S, T, max_seqlen};
   return attention_backward(a, o, d_o, lse, dq, dk, dv, ld_dqkv, scratch, scratch_bytes,
                             (hipStream_t)hip_stream);
+}
+
+// ---- attention backward for callers that cannot allocate ----------------------------------
+// The workspace of bm_attention_backward (the delta plane and, for grouped-query attention over
+// short packs, the fp32 dK/dV partials) lives in device memory that belongs to the code object.
+// Each GPU holds its own copy of the array at its own address; the array's name is only a host
+// stand-in, so the device address is looked up once per device and kept.
+namespace {
+constexpr size_t kStaticScratchBytes = BM_ATTENTION_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};
+
+bm_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return bm::hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) {
+    bm::set_error("device ordinal %d outside the %d the static workspace table covers", dev, kMaxDevices);
+    return BM_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return bm::hip_fail(e, "hipGetSymbolAddress(static attention workspace)");
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return BM_OK;
+}
+}  // namespace
+
+extern "C" size_t bm_attention_backward_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" bm_status bm_attention_backward_static(int32_t dtype, int32_t mask, int32_t Hq, int32_t Hkv,
+                                                  int32_t dh, const void* q, const void* k, const void* v,
+                                                  int32_t ld_qkv, const void* o, const void* d_o,
+                                                  const float* lse, const int32_t* cu_dev,
+                                                  const int32_t* cu_host, int32_t S, int32_t T,
+                                                  int32_t max_seqlen, void* dq, void* dk, void* dv,
+                                                  int32_t ld_dqkv, void* hip_stream) {
+  if (Hq <= 0 || Hkv <= 0 || dh <= 0 || T <= 0) {
+    bm::set_error("attention backward (static workspace): non-positive size");
+    return BM_ERR_INVALID_ARG;
+  }
+  const size_t need = bm::attention_backward_scratch_bytes(Hq, Hkv, dh, T);
+  if (need > kStaticScratchBytes) {
+    bm::set_error("attention backward (static workspace) needs %zu bytes, the built-in workspace holds %zu; "
+                  "use bm_attention_backward with a caller workspace", need, kStaticScratchBytes);
+    return BM_ERR_WORKSPACE_TOO_SMALL;
+  }
+  void* ws = nullptr;
+  BM_RETURN_IF(static_scratch(&ws));
+  // every byte the kernels read from the workspace is written earlier in the same call
+  // (delta plane by the row-sum kernel, partials by the dK/dV kernel), so nothing is cleared
+  return bm_attention_backward(dtype, mask, Hq, Hkv, dh, q, k, v, ld_qkv, o, d_o, lse, cu_dev, cu_host,
+                               S, T, max_seqlen, dq, dk, dv, ld_dqkv, ws, kStaticScratchBytes, hip_stream);
 }

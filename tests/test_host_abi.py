@@ -100,3 +100,19 @@ def test_block_sizes_and_descriptor_validation():
     moe = bm.make_desc(synth.decoder_moe())
     with pytest.raises(bm.BmError):
         bm.block_sizes(moe, 1 << 28, 1 << 10, 1 << 18)         # tokens x choices leaves the int range
+
+
+def test_static_workspace_entry_refuses_oversized_packs_without_a_gpu():
+    """The size check of the allocation-free attention backward comes before any device call."""
+    import numpy as np
+    cap = bm.attention_backward_static_capacity()
+    assert cap == 64 << 20
+    Hq, Hkv, dh, T = 32, 8, 128, 8192
+    assert bm.attention_backward_scratch_bytes(Hq, Hkv, dh, T) > cap
+    cu = np.array([0, T], dtype=np.int32)
+    p, ld = 4096, (Hq + 2 * Hkv) * dh          # never dereferenced: the call stops at the size check
+    with pytest.raises(bm.BmError) as e:
+        bm.attention_backward_static(synth.DTYPE_BF16, 1, Hq, Hkv, dh, p, p, p, ld, p, p, p, p, cu, 1, T, T,
+                                     p, p, p, ld, stream=0)
+    assert e.value.status == -3
+    assert "built-in workspace" in str(e.value)
