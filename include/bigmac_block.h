@@ -73,8 +73,8 @@ typedef struct {
   float   norm_eps;
   int32_t linear_bias;  /* 0/1: biases on the four linear layers                           */
   int32_t dtype;        /* BM_DTYPE_*                                                      */
-  int32_t deterministic;/* reserved; every kernel here is free of floating-point atomics,
-                           so results are run-to-run bit-identical either way             */
+  int32_t deterministic;/* ignored: every kernel here is free of floating-point atomics, so
+                           results are run-to-run bit-identical whatever this field holds  */
   int32_t n_experts;    /* 0: dense FFN.  > 0 (<= 256): mixture-of-experts FFN (the paper's
                            LLM backbone, Sec. 4.1): router logits h W_r^T, softmax over the
                            experts, the top_k most probable experts (ties: lower index) with
@@ -127,6 +127,17 @@ bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_params* w,
                            const int32_t* cu_seqlens_host, int32_t S, int32_t T,
                            int32_t max_seqlen, const void* cond, void* y, void* saved,
                            void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* Where a mixture-of-experts forward left its routing decisions: device pointers INTO `saved`
+ * (valid as long as the caller keeps that buffer; nothing is copied or launched).
+ *   expert_out  -> int32 [T, top_k]  experts chosen for each token, most probable first
+ *   gate_out    -> fp32  [T, top_k]  their gates (probabilities renormalised to sum 1)
+ * T and S are those of the forward call.  The choice is an integer taken from floating-point
+ * router logits (Sec. 4.1 names the mixture-of-experts backbone, Sec. 3.3 its load imbalance),
+ * so a caller that compares two implementations, or balances load, reads it here.
+ * BM_ERR_INVALID_ARG for a block without experts. */
+bm_status bm_block_moe_routing(const bm_block_desc* desc, int32_t T, int32_t S, const void* saved,
+                               const int32_t** expert_out /* host */, const float** gate_out /* host */);
 
 /* Backward of one block.
  *   x, cond, cu_*   as given to the forward call that filled `saved`

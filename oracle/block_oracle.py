@@ -211,25 +211,36 @@ ACT_GELU, ACT_SWIGLU = 0, 1
 # auxiliary loss.
 # ---------------------------------------------------------------------------
 
-def moe_route(logits, k):
-    """(idx [T,k] by descending probability, gate [T,k], probs [T,E])."""
+def moe_route(logits, k, expert_choice=None):
+    """(idx [T,k] by descending probability, gate [T,k], probs [T,E]).
+
+    ``expert_choice`` (int [T,k], distinct experts per token) replaces the top-k decision: the
+    choice is an integer taken from floating-point logits, so where two logits are closer than
+    the rounding of an implementation's own arithmetic several choices are correct; a test
+    hands that implementation's (admissible) choice in and compares everything else, which is
+    then unique.  Probabilities, gates and every gradient formula are unchanged."""
     z = logits - logits.max(axis=1, keepdims=True)
     e = np.exp(z)
     probs = e / e.sum(axis=1, keepdims=True)
     T, E = probs.shape
-    # descending probability, ties to the lower expert index (stable sort of the negated row)
-    idx = np.argsort(-probs, axis=1, kind="stable")[:, :k]
+    if expert_choice is not None:
+        idx = np.asarray(expert_choice, dtype=np.int64)
+        assert idx.shape == (T, k) and idx.min() >= 0 and idx.max() < E
+        assert all(len(set(row)) == k for row in idx.tolist()), "an expert is chosen twice for one token"
+    else:
+        # descending probability, ties to the lower expert index (stable sort of the negated row)
+        idx = np.argsort(-probs, axis=1, kind="stable")[:, :k]
     sel = np.take_along_axis(probs, idx, axis=1)
     gate = sel / sel.sum(axis=1, keepdims=True)
     return idx, gate, probs
 
 
-def moe_ffn_fwd(h, p, E, k, F):
+def moe_ffn_fwd(h, p, E, k, F, expert_choice=None):
     """out[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(h[t]);  returns (out, cache).
     Expert by expert: the tokens (and their choice slot j) that picked expert e."""
     T, d = h.shape
     logits = h @ p["w_router"].T
-    idx, gate, probs = moe_route(logits, k)
+    idx, gate, probs = moe_route(logits, k, expert_choice)
     w_up = p["w_up"].reshape(E, 2 * F, d)
     w_down = p["w_down"].reshape(E, d, F)
     ys = np.zeros((T, k, d))
@@ -279,10 +290,10 @@ def moe_ffn_bwd(dm, h, p, mc, E, k, F):
     return dh, {"w_router": g_router, "w_up": g_up.reshape(E * 2 * F, d), "w_down": g_down.reshape(E * d, F)}
 
 
-def block_forward(cfg, params, x, cu_seqlens, cond=None):
+def block_forward(cfg, params, x, cu_seqlens, cond=None, expert_choice=None):
     """Forward of one block.  ``cfg`` needs the fields hidden, n_q_heads,
     n_kv_heads, head_dim, mlp_hidden, norm, act, mask, rope, rope_base,
-    norm_eps.  Returns (y, cache)."""
+    norm_eps.  ``expert_choice``: see moe_route.  Returns (y, cache)."""
     p = {k: _f64(v) for k, v in params.items()}
     x = _f64(x); cu = np.asarray(cu_seqlens, dtype=np.int64)
     T, d = x.shape
@@ -331,7 +342,7 @@ def block_forward(cfg, params, x, cu_seqlens, cond=None):
         h2 = xhat2 * (1.0 + sc2[sid]) + sh2[sid]
     E = getattr(cfg, "n_experts", 0)
     if E > 0:
-        m, c["moe"] = moe_ffn_fwd(h2, p, E, cfg.top_k, F)
+        m, c["moe"] = moe_ffn_fwd(h2, p, E, cfg.top_k, F, expert_choice)
         up = a = None
     else:
         up = h2 @ p["w_up"].T
@@ -443,7 +454,7 @@ def block_backward(cfg, params, cache, dy):
     return dx, g, dcond
 
 
-def block_fwd_bwd(cfg, params, x, cu_seqlens, dy, cond=None):
-    y, cache = block_forward(cfg, params, x, cu_seqlens, cond)
+def block_fwd_bwd(cfg, params, x, cu_seqlens, dy, cond=None, expert_choice=None):
+    y, cache = block_forward(cfg, params, x, cu_seqlens, cond, expert_choice)
     dx, grads, dcond = block_backward(cfg, params, cache, dy)
     return y, dx, grads, dcond

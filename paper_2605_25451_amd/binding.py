@@ -129,6 +129,8 @@ def lib() -> C.CDLL:
                                        i32, i32, vp, vp, vp, vp, sz, vp]
         l.bm_block_backward.argtypes = [C.POINTER(BlockDesc), C.POINTER(BlockParams), vp, vp, vp, vp,
                                         i32, i32, i32, vp, vp, vp, C.POINTER(BlockParams), vp, vp, sz, vp]
+        l.bm_block_moe_routing.argtypes = [C.POINTER(BlockDesc), i32, i32, vp, C.POINTER(vp), C.POINTER(vp)]
+        l.bm_block_moe_routing.restype = C.c_int
         l.bm_gemm_scratch_bytes.argtypes = [i32] * 5
         l.bm_gemm_scratch_bytes.restype = sz
         l.bm_gemm.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, sz, vp]
@@ -273,6 +275,13 @@ def block_backward(desc, w: BlockParams, x, dy, cu_seqlens_dev, cu_seqlens_host,
                                    _ptr(cond), _ptr(saved), _ptr(dx), C.byref(grads), _ptr(dcond),
                                    _ptr(scratch), scratch_bytes,
                                    _stream() if stream is None else stream))
+
+
+def block_moe_routing(desc, T, S, saved):
+    """Device addresses (inside ``saved``) of the expert choice int32 [T, top_k] and the gates fp32 [T, top_k]."""
+    e, g = C.c_void_p(), C.c_void_p()
+    _check(lib().bm_block_moe_routing(C.byref(desc), T, S, _ptr(saved), C.byref(e), C.byref(g)))
+    return e.value, g.value
 
 
 def make_mmdit_desc(cfg, qk_norm: int, qk_norm_eps: float = 1e-6) -> MmditDesc:

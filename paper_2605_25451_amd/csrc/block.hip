@@ -304,6 +304,20 @@ extern "C" bm_status bm_block_sizes(const bm_block_desc* desc, int32_t T, int32_
   return BM_OK;
 }
 
+extern "C" bm_status bm_block_moe_routing(const bm_block_desc* desc, int32_t T, int32_t S,
+                                          const void* saved, const int32_t** expert_out,
+                                          const float** gate_out) {
+  BM_RETURN_IF(check_desc(desc));
+  BM_ARG_CHECK(desc->n_experts > 0, "bm_block_moe_routing: the block has no experts");
+  BM_ARG_CHECK(T >= 1 && S >= 1 && S <= T, "bm_block_moe_routing: bad T=%d S=%d", T, S);
+  BM_ARG_CHECK(saved && expert_out && gate_out, "bm_block_moe_routing: NULL pointer");
+  BM_RETURN_IF(check_extent(*desc, T, S));
+  Saved sv = layout_saved(make_dims(*desc, T, S), const_cast<void*>(saved));
+  *expert_out = sv.moe.idx;
+  *gate_out = sv.moe.gate;
+  return BM_OK;
+}
+
 extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_params* w,
                                       const void* x, const int32_t* cu_dev, const int32_t* cu_host,
                                       int32_t S, int32_t T, int32_t max_seqlen, const void* cond,

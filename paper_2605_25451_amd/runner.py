@@ -90,6 +90,17 @@ class CaseOnDevice:
         self.forward()
         self.backward()
 
+    def moe_routing(self):
+        """(experts int32 [T, top_k], gates fp32 [T, top_k]) the forward left in ``saved``, as numpy arrays."""
+        torch.cuda.synchronize()
+        T, S, k = self.case.T, self.case.S, self.case.cfg.top_k
+        e_ptr, g_ptr = bm.block_moe_routing(self.runner.desc, T, S, self.saved)
+        base = self.saved.data_ptr()
+        n = T * k * 4
+        experts = self.saved[e_ptr - base:e_ptr - base + n].view(torch.int32).reshape(T, k)
+        gates = self.saved[g_ptr - base:g_ptr - base + n].view(torch.float32).reshape(T, k)
+        return experts.cpu().numpy(), gates.cpu().numpy()
+
     def results(self):
         """(y, dx, grads, dcond) as float64 numpy arrays."""
         torch.cuda.synchronize()

@@ -68,16 +68,16 @@ def test_nested_order_matches_oracle_fp32(gen, unit_size):
     from paper_2605_25451_amd import binding as bm
     stage = stage_fp32(gen, 5, unit_size)
     loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
-    # a stage chains six blocks and two projectors: ten times the single-block bound
-    compare((loss, grads), eo.run_stage(stage), 1e-4)
+    # six chained blocks and two projectors still meet the single-block bound (measured <= 1e-6)
+    compare((loss, grads), eo.run_stage(stage), 1e-5)
 
 
 def test_nested_order_matches_oracle_bf16():
     from paper_2605_25451_amd import binding as bm
     stage = stage_bf16(True, 4, 1)
     loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
-    # bf16 through six chained blocks: twice the single-block bound
-    compare((loss, grads), eo.run_stage(stage), 4e-2)
+    # bf16 through six chained blocks still meets the single-block bound (measured 1.3e-2)
+    compare((loss, grads), eo.run_stage(stage), 2e-2)
 
 
 def test_orders_agree_and_encoder_memory_is_flat():
@@ -167,4 +167,4 @@ def test_stage_with_mixture_of_experts_llm_blocks_fp32():
     stage = synth.make_stage(enc, llm, g, 2, 2, 2, 4, 1, 256, 90, image_range=(16, 48), text_range=(8, 32),
                              tokens_per_image=8, proj_std=0.1)
     loss, grads, _ = run_gpu(stage, bm.ORDER_NESTED)
-    compare((loss, grads), eo.run_stage(stage), 1e-4)
+    compare((loss, grads), eo.run_stage(stage), 1e-5)

@@ -72,3 +72,23 @@ def test_encoder_unit_size():
     assert lo.encoder_unit_size(4, 2, 2) == 4
     with pytest.raises(ValueError):
         lo.encoder_unit_size(3, 1, 2)
+
+
+@pytest.mark.parametrize("C", [1, 2, 3, 4, 8])
+def test_the_input_generators_partition_is_the_oracles_layout(C):
+    """The seeded input module cuts packs into context-parallel chunks for the plumbing and the
+    tests (synth.context_chunks); the oracle states the same rule on its own (chunk_layout).
+    Both must describe one layout: rank c's k-th row of sequence s is the same pack row."""
+    from paper_2605_25451_amd import synth
+    rng = np.random.default_rng(100 + C)
+    for lens in ([1], [7, 1, 2, 30], [C, C + 1, 2 * C - 1, 5 * C], rng.integers(1, 200, size=9).tolist()):
+        cu = synth.cu_from_lengths(lens)
+        chunks = synth.context_chunks(cu, C)
+        owner, fill = lo.chunk_layout(lens, C)
+        assert [len(rows) for rows, _ in chunks] == fill
+        for c, (rows, cu_c) in enumerate(chunks):
+            assert np.array_equal(np.diff(cu_c), [(c + 1) * L // C - c * L // C for L in lens])
+        for s, L in enumerate(lens):
+            for p in range(L):
+                c, local = owner[s][p]
+                assert chunks[c][0][local] == cu[s] + p, (s, p)

@@ -133,3 +133,67 @@ def test_ffn_matches_torch_autograd(E, k):
     assert np.allclose(g["w_router"], wr.grad.numpy(), rtol=1e-10, atol=1e-12)
     assert np.allclose(g["w_up"], wu.grad.numpy().reshape(E * 2 * F, d), rtol=1e-10, atol=1e-12)
     assert np.allclose(g["w_down"], wd.grad.numpy().reshape(E * d, F), rtol=1e-10, atol=1e-12)
+
+
+# ---- a given expert choice (the integer decision handed in) --------------------------------
+
+def test_given_own_choice_reproduces_the_result_bit_for_bit():
+    case = moe_case(E=6, k=3, seed=40)
+    y0, dx0, g0, _ = bo.block_fwd_bwd(case.cfg, case.params, case.x, case.cu_seqlens, case.dy)
+    _, cache = bo.block_forward(case.cfg, case.params, case.x, case.cu_seqlens)
+    y1, dx1, g1, _ = bo.block_fwd_bwd(case.cfg, case.params, case.x, case.cu_seqlens, case.dy,
+                                      expert_choice=cache["moe"]["idx"])
+    assert np.array_equal(y0, y1) and np.array_equal(dx0, dx1)
+    for n in g0:
+        assert np.array_equal(g0[n], g1[n]), n
+
+
+def test_order_of_a_given_choice_does_not_matter():
+    case = moe_case(E=6, k=3, seed=41)
+    _, cache = bo.block_forward(case.cfg, case.params, case.x, case.cu_seqlens)
+    idx = cache["moe"]["idx"]
+    y0, dx0, g0, _ = bo.block_fwd_bwd(case.cfg, case.params, case.x, case.cu_seqlens, case.dy, expert_choice=idx)
+    y1, dx1, g1, _ = bo.block_fwd_bwd(case.cfg, case.params, case.x, case.cu_seqlens, case.dy,
+                                      expert_choice=idx[:, ::-1])
+    assert np.allclose(y0, y1, rtol=1e-13, atol=1e-14) and np.allclose(dx0, dx1, rtol=1e-12, atol=1e-14)
+    for n in g0:
+        assert np.allclose(g0[n], g1[n], rtol=1e-12, atol=1e-14), n
+
+
+@pytest.mark.parametrize("E,k", [(5, 2), (6, 3)])
+def test_given_choice_matches_torch_autograd_with_that_choice(E, k):
+    """A choice that is NOT the top-k one: gates are the chosen probabilities renormalised, and the
+    gradients are those of that fixed selection (torch gathers with the same indices)."""
+    case = moe_case(E=E, k=k, seed=50 + E)
+    cfg = case.cfg
+    F, d = cfg.mlp_hidden, cfg.hidden
+    p = {n: v.astype(np.float64) for n, v in case.params.items()}
+    rng = np.random.default_rng(E + 100)
+    T = 8
+    h = rng.standard_normal((T, d))
+    dm = rng.standard_normal((T, d))
+    choice = np.stack([rng.permutation(E)[:k] for _ in range(T)])
+    own = bo.moe_route(h @ p["w_router"].T, k)[0]
+    assert any(set(a) != set(b) for a, b in zip(choice.tolist(), own.tolist()))
+    out, mc = bo.moe_ffn_fwd(h, p, E, k, F, expert_choice=choice)
+    dh, g = bo.moe_ffn_bwd(dm, h, p, mc, E, k, F)
+
+    th = torch.tensor(h, requires_grad=True)
+    wr = torch.tensor(p["w_router"], requires_grad=True)
+    wu = torch.tensor(p["w_up"].reshape(E, 2 * F, d), requires_grad=True)
+    wd = torch.tensor(p["w_down"].reshape(E, d, F), requires_grad=True)
+    probs = Fn.softmax(th @ wr.T, dim=1)
+    idx = torch.tensor(choice)
+    sel = torch.gather(probs, 1, idx)
+    gate = sel / sel.sum(dim=1, keepdim=True)
+    tout = torch.zeros_like(th)
+    for j in range(k):
+        up = torch.einsum("tfd,td->tf", wu[idx[:, j]], th)
+        a = Fn.silu(up[:, :F]) * up[:, F:]
+        tout = tout + gate[:, j:j + 1] * torch.einsum("tdf,tf->td", wd[idx[:, j]], a)
+    (tout * torch.tensor(dm)).sum().backward()
+    assert np.allclose(out, tout.detach().numpy(), rtol=1e-12, atol=1e-13)
+    assert np.allclose(dh, th.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["w_router"], wr.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["w_up"], wu.grad.numpy().reshape(E * 2 * F, d), rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["w_down"], wd.grad.numpy().reshape(E * d, F), rtol=1e-10, atol=1e-12)
