@@ -32,8 +32,35 @@ which prints no worked numerical example.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 from scipy.special import erf
+
+# Attention evaluates the kv heads of a sequence independently of each other, so a test that has
+# to get through a 16384-token document in minutes may spread them over a few threads
+# (BM_ORACLE_THREADS, default 1 = the plain loop).  Nothing about the arithmetic changes: every
+# (sequence, head) matrix is computed by the same statements and the q heads of a group are
+# added to their kv head's gradient in the same order, so the result is bit-identical to the
+# serial loop (pinned in tests/test_oracle_block.py).
+KV_HEAD_THREADS = max(1, int(os.environ.get("BM_ORACLE_THREADS", "1")))
+KV_HEAD_DONE = None      # optional callable(kv_head): a long test prints its progress from here
+
+
+def _each_kv_head(n, fn):
+    def run(b):
+        fn(b)
+        if KV_HEAD_DONE is not None:
+            KV_HEAD_DONE(b)
+
+    w = min(KV_HEAD_THREADS, n)
+    if w <= 1:
+        for b in range(n):
+            run(b)
+    else:
+        with ThreadPoolExecutor(max_workers=w) as ex:
+            list(ex.map(run, range(n)))
 
 F64 = np.float64
 
@@ -155,10 +182,13 @@ def attention_fwd(q, k, v, cu, causal):
     o = np.zeros_like(q)
     for s in range(len(cu) - 1):
         lo, hi = int(cu[s]), int(cu[s + 1])
-        for a in range(Hq):
-            b = a // group
-            p = attention_probs(q[lo:hi, a], k[lo:hi, b], causal)
-            o[lo:hi, a] = p @ v[lo:hi, b]
+
+        def kv_head(b):
+            for a in range(b * group, (b + 1) * group):
+                p = attention_probs(q[lo:hi, a], k[lo:hi, b], causal)
+                o[lo:hi, a] = p @ v[lo:hi, b]
+
+        _each_kv_head(k.shape[1], kv_head)
     return o
 
 
@@ -169,15 +199,18 @@ def attention_bwd(do, q, k, v, cu, causal):
     scale = 1.0 / np.sqrt(dh)
     for s in range(len(cu) - 1):
         lo, hi = int(cu[s]), int(cu[s + 1])
-        for a in range(Hq):
-            b = a // group
-            p = attention_probs(q[lo:hi, a], k[lo:hi, b], causal)
-            d_o = do[lo:hi, a]
-            dv[lo:hi, b] += p.T @ d_o
-            dp = d_o @ v[lo:hi, b].T
-            dsc = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
-            dq[lo:hi, a] = dsc @ k[lo:hi, b] * scale
-            dk[lo:hi, b] += dsc.T @ q[lo:hi, a] * scale
+
+        def kv_head(b):
+            for a in range(b * group, (b + 1) * group):
+                p = attention_probs(q[lo:hi, a], k[lo:hi, b], causal)
+                d_o = do[lo:hi, a]
+                dv[lo:hi, b] += p.T @ d_o
+                dp = d_o @ v[lo:hi, b].T
+                dsc = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
+                dq[lo:hi, a] = dsc @ k[lo:hi, b] * scale
+                dk[lo:hi, b] += dsc.T @ q[lo:hi, a] * scale
+
+        _each_kv_head(k.shape[1], kv_head)
     return dq, dk, dv
 
 

@@ -1,17 +1,19 @@
 // Host-side nested schedule (integer logic only).
 //
-// The nested order follows the paper's BuildSchedule algorithm (Sec. 3.1,
-// "Memory efficiency" and the BuildSchedule figure): the LLM schedule is kept
-// as given; W encoder-forward units are warmed up; after each LLM column the
-// generator runs forward+backward for a unit whose LLM output just completed,
-// and the encoder runs backward -- followed at once by the next pending
-// encoder forward -- for a unit whose input gradient just completed.
+// The nested order of Sec. 3.1 ("Compute operator", "Memory efficiency", the BuildSchedule
+// figure) is produced here from the dependency rule the text states rather than by walking
+// the printed loop: the LLM op sequence is fixed, and every encoder / generator op is placed
+// at the first point of that sequence where what it consumes exists and what it needs is free:
+//   - an encoder forward needs a free encoder slot (at most W units hold encoder activations);
+//   - a generator forward+backward needs the LLM output of every microbatch of its unit;
+//   - an encoder backward needs the LLM input gradient of every microbatch of its unit, and
+//     frees the unit's slot, which the next pending encoder forward takes at once.
+// Completion counters per unit decide readiness after each single LLM op.
 //
-// Reading for one pipeline stage acting as both entry and exit of the LLM: a
-// unit is unit_size consecutive microbatches; the LLM schedule is 1F1B at unit
-// granularity with llm_depth units in flight; a unit's LLM output is complete
-// at the forward of its last microbatch, its encoder gradient at the backward
-// of its last microbatch.
+// Reading for one pipeline stage acting as both entry and exit of the LLM: a unit is unit_size
+// consecutive microbatches; the LLM order is 1F1B at unit granularity with llm_depth units in
+// flight.  The compute-efficient order of Sec. 2.2 is the same placement with as many encoder
+// slots as units and every encoder backward held back to the end.
 #include "common.h"
 
 #include <vector>
@@ -24,58 +26,64 @@ struct Units {
   int M, unit_size, U;
   int first(int u) const { return u * unit_size; }
   int last(int u) const { int e = (u + 1) * unit_size; return (e < M ? e : M) - 1; }
+  int size(int u) const { return last(u) - first(u) + 1; }
   int of(int mb) const { return mb / unit_size; }
 };
 
-// columns of the 1F1B order: (is_backward, unit)
-std::vector<std::pair<bool, int>> llm_columns(const Units& un, int depth) {
-  std::vector<std::pair<bool, int>> cols;
-  int warm = depth < un.U ? depth : un.U;
-  for (int u = 0; u < warm; ++u) cols.push_back({false, u});
-  int next_f = warm;
-  for (int u = 0; u < un.U; ++u) {
-    cols.push_back({true, u});
-    if (next_f < un.U) cols.push_back({false, next_f++});
+// One stage's 1F1B order as a flat op list: forward the next unit while fewer than `depth`
+// units are in flight, otherwise back the oldest unit in flight.
+std::vector<Op> llm_order(const Units& un, int depth) {
+  std::vector<Op> ops;
+  int forwarded = 0, backed = 0;
+  while (backed < un.U) {
+    const bool fwd = forwarded < un.U && forwarded - backed < depth;
+    const int u = fwd ? forwarded++ : backed++;
+    for (int mb = un.first(u); mb <= un.last(u); ++mb)
+      ops.push_back({fwd ? BM_OP_LLM_FWD : BM_OP_LLM_BWD, mb});
   }
-  return cols;
+  return ops;
 }
 
-void emit_column(std::vector<Op>& out, const Units& un, bool bwd, int u) {
-  for (int mb = un.first(u); mb <= un.last(u); ++mb)
-    out.push_back({bwd ? BM_OP_LLM_BWD : BM_OP_LLM_FWD, mb});
-}
-
-std::vector<Op> build(int order, const Units& un, int W, int depth, bool gen) {
-  std::vector<Op> out;
-  if (order == BM_ORDER_SEQUENTIAL) {
-    for (int u = 0; u < un.U; ++u) {
-      out.push_back({BM_OP_ENC_FWD, u});
-      emit_column(out, un, false, u);
-      if (gen) { out.push_back({BM_OP_GEN_FWD, u}); out.push_back({BM_OP_GEN_BWD, u}); }
-      emit_column(out, un, true, u);
-      out.push_back({BM_OP_ENC_BWD, u});
-    }
-    return out;
-  }
-  const bool nested = order == BM_ORDER_NESTED;
-  int next_enc = 0;
-  const int warm = nested ? (W < un.U ? W : un.U) : un.U;
-  while (next_enc < warm) out.push_back({BM_OP_ENC_FWD, next_enc++});
-  for (auto& col : llm_columns(un, depth)) {
-    const bool bwd = col.first;
-    const int u = col.second;
-    emit_column(out, un, bwd, u);
-    // the column's last op completes the unit's LLM output (forward) or its
-    // encoder-input gradient (backward)
-    if (!bwd && gen) { out.push_back({BM_OP_GEN_FWD, u}); out.push_back({BM_OP_GEN_BWD, u}); }
-    if (bwd && nested) {
-      out.push_back({BM_OP_ENC_BWD, u});
-      if (next_enc < un.U) out.push_back({BM_OP_ENC_FWD, next_enc++});
+// Places encoder and generator ops into the LLM order.  enc_slots: units that may hold encoder
+// activations at once; hold_enc_bwd: encoder backwards wait for the end of the LLM order.
+// Returns false when an LLM forward comes up before its unit's encoder output can exist.
+bool place(const Units& un, const std::vector<Op>& llm, int enc_slots, bool hold_enc_bwd, bool gen,
+           std::vector<Op>& out) {
+  std::vector<int> fwd_done(un.U, 0), bwd_done(un.U, 0);
+  int live_enc = 0, next_enc = 0;
+  auto fill_encoder_slots = [&] {
+    while (live_enc < enc_slots && next_enc < un.U) { out.push_back({BM_OP_ENC_FWD, next_enc++}); ++live_enc; }
+  };
+  fill_encoder_slots();
+  for (const Op& op : llm) {
+    const int u = un.of(op.index);
+    if (op.code == BM_OP_LLM_FWD) {
+      if (u >= next_enc) return false;               // its encoder unit has not run
+      out.push_back(op);
+      if (++fwd_done[u] == un.size(u) && gen) {      // the unit's LLM output is complete
+        out.push_back({BM_OP_GEN_FWD, u});
+        out.push_back({BM_OP_GEN_BWD, u});
+      }
+    } else {
+      out.push_back(op);
+      if (++bwd_done[u] == un.size(u) && !hold_enc_bwd) {   // the unit's input gradient is complete
+        out.push_back({BM_OP_ENC_BWD, u});
+        --live_enc;
+        fill_encoder_slots();
+      }
     }
   }
-  if (!nested)
+  if (hold_enc_bwd)
     for (int u = 0; u < un.U; ++u) out.push_back({BM_OP_ENC_BWD, u});
-  return out;
+  return true;
+}
+
+bool build(int order, const Units& un, int W, int depth, bool gen, std::vector<Op>& out) {
+  if (order == BM_ORDER_SEQUENTIAL)                  // one unit in flight everywhere
+    return place(un, llm_order(un, 1), 1, false, gen, out);
+  if (order == BM_ORDER_COMPUTE_EFFICIENT)
+    return place(un, llm_order(un, depth), un.U, true, gen, out);
+  return place(un, llm_order(un, depth), W, false, gen, out);
 }
 
 }  // namespace
@@ -93,7 +101,12 @@ extern "C" bm_status bm_build_schedule(int32_t order, int32_t M, int32_t unit_si
   BM_ARG_CHECK(order != BM_ORDER_NESTED || W >= (llm_depth < un.U ? llm_depth : un.U),
                "bm_build_schedule: W=%d encoder units cannot feed an LLM order with %d units in flight",
                W, llm_depth);
-  std::vector<Op> ops = build(order, un, W, llm_depth, has_generator != 0);
+  std::vector<Op> ops;
+  if (!build(order, un, W, llm_depth, has_generator != 0, ops)) {
+    set_error("bm_build_schedule: an LLM forward would run before its encoder unit (W=%d, %d units in flight)",
+              W, llm_depth);
+    return BM_ERR_INVALID_ARG;
+  }
   const int32_t cap = *n_ops;
   *n_ops = (int32_t)ops.size();
   if (cap < (int32_t)ops.size() || !ops_out) {

@@ -46,6 +46,45 @@ def test_schedule_matches_oracle(M, us, gen):
         assert peak == (ref_peak["enc"], ref_peak["gen"], ref_peak["llm"])
 
 
+@pytest.mark.parametrize("depth", [1, 2, 3, 4])
+@pytest.mark.parametrize("extra_w", [0, 1, 3])
+@pytest.mark.parametrize("us", [1, 2, 3])
+@pytest.mark.parametrize("gen", [0, 1])
+def test_nested_schedule_properties_for_any_depth_and_warm_up(depth, extra_w, us, gen):
+    """What Sec. 3.1 states about the nested order, checked on the library's output without the
+    oracle's generator: dependencies hold, the LLM order is untouched, at most W encoder units
+    and one generator unit are alive, every nested op sits at the first point where its inputs
+    exist, and the order property F_i, F_{i+1}, F_{i+2} < G_i < F_{i+3} holds at depth 3 (G_i = the
+    backward that completes unit i's gradient at the LLM entry)."""
+    W = depth + extra_w
+    for M in (1, 2, 3, 5, 7, 12, 13):
+        U = -(-M // us)
+        ops = bm.build_schedule(bm.ORDER_NESTED, M, us, W, depth, gen)
+        peak = bm.check_schedule(ops, M, us, gen)                       # raises on a broken dependency
+        assert peak[0] == min(W, U) and peak[1] == (1 if gen else 0) and peak[2] <= depth * us
+        llm = [op for op in ops if op[0] in (bm.OP_LLM_FWD, bm.OP_LLM_BWD)]
+        flat = [(CODE[k], i) for col in so.llm_schedule_1f1b(M, us, depth) for k, i in col]
+        assert llm == flat                                              # the LLM schedule is kept verbatim
+        pos = {op: i for i, op in enumerate(ops)}
+        last = lambda u: min((u + 1) * us, M) - 1
+        for u in range(U):
+            if gen:                                                     # right behind the unit's last forward
+                assert pos[(bm.OP_GEN_FWD, u)] == pos[(bm.OP_LLM_FWD, last(u))] + 1
+                assert pos[(bm.OP_GEN_BWD, u)] == pos[(bm.OP_GEN_FWD, u)] + 1
+            assert pos[(bm.OP_ENC_BWD, u)] == pos[(bm.OP_LLM_BWD, last(u))] + 1
+            if u + W < U:                                               # the freed slot is taken at once
+                assert pos[(bm.OP_ENC_FWD, u + W)] == pos[(bm.OP_ENC_BWD, u)] + 1
+            if u < min(W, U):
+                assert pos[(bm.OP_ENC_FWD, u)] == u                     # warm-up fills every slot
+        if depth == 3:                               # G_i: the unit's gradient reaches the entry stage
+            first = lambda u: u * us
+            for i in range(U):
+                g = pos[(bm.OP_LLM_BWD, last(i))]
+                assert all(pos[(bm.OP_LLM_FWD, first(j))] < g for j in range(i, min(i + 3, U)))
+                if i + 3 < U:
+                    assert g < pos[(bm.OP_LLM_FWD, first(i + 3))]
+
+
 def test_check_schedule_rejects_unsafe_orders():
     ops = bm.build_schedule(bm.ORDER_NESTED, 4, 1, 3, 3, 1)
     i = ops.index((bm.OP_LLM_FWD, 0)); j = ops.index((bm.OP_ENC_FWD, 0))

@@ -340,3 +340,24 @@ def test_adaln_unit_gate_equals_plain_prenorm_block():
     plain.update(norm1_g=np.ones(d), norm1_b=np.zeros(d), norm2_g=np.ones(d), norm2_b=np.zeros(d))
     y2, _ = bo.block_forward(plain_cfg, plain, case.x, case.cu_seqlens)
     assert np.allclose(y, y2, rtol=1e-13, atol=1e-14)
+
+
+def test_kv_head_threads_leave_every_bit_unchanged():
+    """The oracle may spread independent kv heads over threads (for the 16384-token document of
+    the full-size parity test); results must equal the plain loop bit for bit."""
+    rng = np.random.default_rng(5)
+    T, Hq, Hkv, dh = 70, 8, 4, 8
+    cu = np.array([0, 33, 34, 70])
+    q, do = rng.standard_normal((T, Hq, dh)), rng.standard_normal((T, Hq, dh))
+    k, v = rng.standard_normal((T, Hkv, dh)), rng.standard_normal((T, Hkv, dh))
+    seen = []
+    try:
+        bo.KV_HEAD_THREADS = 1
+        ref = [bo.attention_fwd(q, k, v, cu, True), *bo.attention_bwd(do, q, k, v, cu, True)]
+        bo.KV_HEAD_THREADS, bo.KV_HEAD_DONE = 3, seen.append
+        got = [bo.attention_fwd(q, k, v, cu, True), *bo.attention_bwd(do, q, k, v, cu, True)]
+    finally:
+        bo.KV_HEAD_THREADS, bo.KV_HEAD_DONE = 1, None
+    for a, b in zip(got, ref):
+        assert np.array_equal(a, b)
+    assert sorted(seen) == sorted(list(range(Hkv)) * 3 * 2)      # every kv head of every sequence, fwd and bwd
