@@ -159,13 +159,22 @@ Sizes plan_sizes(const bm_executor_config& c, const bm_microbatch* mbs, const bm
     z.gen_set += al((size_t)maxS_img * c.gen.hidden * es) + 2 * al((size_t)maxS_img * c.llm.hidden * es) +
                  al((size_t)z.maxT_gen * c.gen.hidden * es);
   }
-  // scratch: block workspaces, projector split-K partials, loss partials; two ping-pong gradients
-  size_t sc = scratch_bytes_of(c.enc, z.maxT_enc, z.maxS_enc);
-  size_t v = scratch_bytes_of(c.llm, z.maxT_llm, z.maxS_llm); sc = v > sc ? v : sc;
-  if (c.n_gen_blocks > 0) { v = scratch_bytes_of(c.gen, z.maxT_gen, maxS_img); sc = v > sc ? v : sc; }
-  v = gemm_scratch_bytes(GEMM_TN, c.llm.hidden, c.enc.hidden, z.maxT_enc, c.llm.dtype); sc = v > sc ? v : sc;
-  if (c.n_gen_blocks > 0) { v = gemm_scratch_bytes(GEMM_TN, c.gen.hidden, c.llm.hidden, maxS_img, c.llm.dtype); sc = v > sc ? v : sc; }
-  v = loss_scratch_bytes(); sc = v > sc ? v : sc;
+  // scratch: block workspaces, projector split-K partials, loss partials; two ping-pong gradients.
+  // A block's workspace is not monotone in the token count (a shorter contraction can be cut into
+  // more k ranges, each with its own fp32 partial tile), so the largest pack alone does not bound
+  // it: the maximum is taken over the shape of every unit and microbatch that will run.
+  size_t sc = loss_scratch_bytes(), v;
+  auto upto = [&](size_t b) { sc = b > sc ? b : sc; };
+  for (int m = 0; m < c.M; ++m) upto(scratch_bytes_of(c.llm, mbs[m].T, mbs[m].S));
+  for (int u = 0; u < U; ++u) {
+    upto(scratch_bytes_of(c.enc, units[u].T, units[u].S));
+    upto(gemm_scratch_bytes(GEMM_TN, c.llm.hidden, c.enc.hidden, units[u].T, c.llm.dtype));
+    if (c.n_gen_blocks > 0) {
+      const int tpi = c.gen_tokens_per_image > 0 ? c.gen_tokens_per_image : 1;
+      upto(scratch_bytes_of(c.gen, units[u].S * tpi, units[u].S));
+      upto(gemm_scratch_bytes(GEMM_TN, c.gen.hidden, c.llm.hidden, units[u].S, c.llm.dtype));
+    }
+  }
   z.scratch = al(sc);
   size_t pg = (size_t)z.maxT_llm * c.llm.hidden;
   v = (size_t)z.maxT_enc * c.enc.hidden; pg = v > pg ? v : pg;
