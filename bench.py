@@ -35,6 +35,11 @@ HBM_PEAK_GBS = 8000.0
 # reduction that follows a weight-gradient GEMM is part of that class's launch.  Workloads
 # or classes without a summarised counter run report null.
 MIB = 1048576.0
+TRAFFIC_SOURCE = {
+    "config2_vit_large_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config2.md",
+    "config3_decoder_7b_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config3.md",
+    "config4_decoder_8b_gqa_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config4.md",
+}
 MEASURED_TRAFFIC_BYTES = {
     "config2_vit_large_bf16": {
         "gemm_tn": 392.4 * MIB,      # 3 launches (232.4 + 64.0) and 4 split-k reductions (60.0 + 12.0) per step
@@ -288,45 +293,62 @@ def cpu_baseline(case, budget_flops=2.0e12):
                       f"({sub.T} of {case.T} tokens) of the same pack, {dt:.1f} s"}
 
 
-def run_stage_workload(args):
-    """config 5: one pipeline stage's share -- 4 decoder blocks over `batch` microbatches of
-    8192 packed tokens, with 6 ViT-L blocks per encoder unit and 2 DiT blocks per generator
-    unit nested between them; reports LLM tokens/s and peak activation bytes for the nested
-    and the compute-efficient order."""
+def stage_sweep(batches, unit_size, steps):
+    """config 5: one pipeline stage's share -- 4 decoder blocks over M microbatches of 8192 packed
+    tokens, with 6 ViT-L blocks per encoder unit and 2 DiT blocks per generator unit nested between
+    them -- for every M in `batches` (8 seeded microbatches are drawn; larger batches run them
+    again cyclically).  Per M and order (nested / compute-efficient): LLM tokens/s, the executor's
+    activation high-water marks (all activations, and the encoder units' part) and the arena the
+    slots occupy in HBM."""
     import torch
     from paper_2605_25451_amd import binding as bm
     from paper_2605_25451_amd import synth
     from paper_2605_25451_amd.stage import StageOnDevice
-    M = args.batch
-    stage = synth.make_stage(synth.vit_large(), synth.decoder_7b(), synth.dit_block(), 6, 4, 2, M,
-                             args.unit_size, 8192, seed=4)
-    dev = StageOnDevice(stage)
-    U = len(stage.units)
+    Mdraw = min(max(batches), max(8, unit_size))
+    stage = synth.make_stage(synth.vit_large(), synth.decoder_7b(), synth.dit_block(), 6, 4, 2, Mdraw,
+                             unit_size, 8192, seed=4)
+    # batches above the drawn one reuse its microbatches cyclically (same read-only inputs in HBM):
+    # step time and activation memory do not depend on the values
+    dev = StageOnDevice(stage, repeat=-(-max(batches) // Mdraw))
+    units_all = [stage.units[u % len(stage.units)] for u in range(-(-max(batches) // unit_size))]
     depth = 3
+    out = {"blocks": "6 ViT-L / 4 decoder-7B / 2 DiT", "llm_tokens_per_microbatch": 8192,
+           "unit_size": unit_size, "encoder_slots_nested": 3, "llm_units_in_flight": depth,
+           "steps": steps, "batches": {}}
+    for M in batches:
+        U = -(-M // unit_size)
+        entry = {"encoder_tokens_per_unit": [int(u.cu_seqlens[-1]) for u in units_all[:U]]}
+        for name, order, slots in (("nested", bm.ORDER_NESTED, min(3, U)),
+                                   ("compute_efficient", bm.ORDER_COMPUTE_EFFICIENT, U)):
+            arena = dev.create(slots, depth * unit_size, M=M)
+            ops = bm.build_schedule(order, M, unit_size, 3, depth, 1)
+            dev.zero_grads()
+            dev.run(ops)                                     # warm-up step
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                dev.run(ops)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / steps
+            peak, peak_enc = dev.peak_bytes()
+            entry[name] = {"ms_per_step": dt * 1e3, "tokens_per_s": M * 8192 / dt,
+                           "peak_activation_bytes": peak, "peak_encoder_bytes": peak_enc,
+                           "arena_bytes": arena}
+            dev.destroy()
+        out["batches"][str(M)] = entry
+    return out
+
+
+def run_stage_workload(args):
+    """config 5 at one batch size: python bench.py --workload config5 --batch M [--unit-size U]."""
+    sweep = stage_sweep((args.batch,), args.unit_size, args.steps)
+    entry = sweep["batches"][str(args.batch)]
     out = {"metric": "stage tokens/s and peak activation bytes (config 5)", "unit": "tokens/s",
            "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "higher_is_better": True,
-           "config": {"workload": "config5_stage", "microbatches": M, "unit_size": args.unit_size,
-                      "llm_tokens_per_microbatch": 8192, "blocks": "6 ViT-L / 4 decoder-7B / 2 DiT",
-                      "encoder_tokens": [int(u.cu_seqlens[-1]) for u in stage.units]}, "orders": {}}
-    for name, order, slots in (("nested", bm.ORDER_NESTED, min(3, U)),
-                               ("compute_efficient", bm.ORDER_COMPUTE_EFFICIENT, U)):
-        torch.cuda.reset_peak_memory_stats()
-        arena = dev.create(slots, depth * args.unit_size)
-        ops = bm.build_schedule(order, M, args.unit_size, 3, depth, 1)
-        dev.zero_grads()
-        dev.run(ops)                                     # warm-up step
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            dev.run(ops)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
-        peak, peak_enc = dev.peak_bytes()
-        out["orders"][name] = {"ms_per_step": dt * 1e3, "tokens_per_s": M * 8192 / dt,
-                               "peak_activation_bytes": peak, "peak_encoder_bytes": peak_enc,
-                               "arena_bytes": arena,
-                               "torch_max_memory_allocated": torch.cuda.max_memory_allocated()}
-        dev.destroy()
+           "config": {"workload": "config5_stage", "microbatches": args.batch, "unit_size": args.unit_size,
+                      "llm_tokens_per_microbatch": 8192, "blocks": sweep["blocks"],
+                      "encoder_tokens": entry["encoder_tokens_per_unit"]},
+           "orders": {k: entry[k] for k in ("nested", "compute_efficient")}}
     out["value"] = out["orders"]["nested"]["tokens_per_s"]
     out["ms_per_step"] = out["orders"]["nested"]["ms_per_step"]
     out["steps"] = args.steps
@@ -415,7 +437,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config2")
+    ap.add_argument("--workload", default="headline",
+                    help="headline (default: config4 as the headline, config2/config3 and the config-5 stage "
+                         "sweep as extra keys) | config2 | config3 | config4 | dit | moe | mmdit | config5 | "
+                         "pipeline | cp")
+    ap.add_argument("--no-stage-sweep", action="store_true", help="headline run without the config-5 sweep")
     ap.add_argument("--batch", type=int, default=8, help="microbatches (config5 only)")
     ap.add_argument("--unit-size", type=int, default=1, help="microbatches per unit (config5 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -441,7 +467,33 @@ def main():
         return run_pipeline_workload(args)
     if args.workload == "cp":
         return run_cp_workload(args)
-    if args.workload == "mmdit":
+    if args.workload == "headline":
+        # the default line: the largest single-GPU block configuration as the headline, the two
+        # smaller block configurations and the stage sweep (peak activation memory against batch
+        # size) as extra keys of the same JSON line
+        out = bench_block("config4", args.steps, args.warmup, peaks=True, baseline=not args.no_cpu_baseline)
+        out["other_configs"] = {}
+        for name in ("config2", "config3"):
+            r = bench_block(name, max(args.steps // 2, 5), args.warmup, peaks=False, baseline=False)
+            out["other_configs"][r["config"]["workload"]] = {
+                k: r[k] for k in ("ms_per_step", "value", "unit", "mfma_util_pct", "gemm_tflops",
+                                  "attention_tflops", "tokens_per_s", "roofline", "breakdown")}
+            out["other_configs"][r["config"]["workload"]]["config"] = r["config"]
+        if not args.no_stage_sweep:
+            out["config5_stage_sweep"] = stage_sweep((8, 16, 32), 1, steps=2)
+        print(json.dumps(out))
+        return
+    out = bench_block(args.workload, args.steps, args.warmup, peaks=True, baseline=not args.no_cpu_baseline,
+                      copy_cal=args.copy_calibration)
+    print(json.dumps(out))
+
+
+def bench_block(workload, steps, warmup, peaks=True, baseline=True, copy_cal=False):
+    """Times `steps` forward+backward passes of one block workload and returns the result record."""
+    import torch
+    from paper_2605_25451_amd import binding as bm
+    from paper_2605_25451_amd.runner import CaseOnDevice
+    if workload == "mmdit":
         import numpy as np
         from paper_2605_25451_amd.runner import TwoStreamOnDevice
         case = mmdit_case()
@@ -452,30 +504,30 @@ def main():
         extra = {"text_tokens": int(case.cu[0][-1]), "image_tokens": int(case.cu[1][-1]),
                  "step": "one two-stream block forward + backward (joint attention over [text ; image], "
                          "q/k RMS norm, weight grads accumulated in fp32)"}
-        baseline = lambda: cpu_baseline_mmdit(case)
+        run_baseline = lambda: cpu_baseline_mmdit(case)
     else:
-        case = make_workload(args.workload)
+        case = make_workload(workload)
         dev = CaseOnDevice(case)
         gemm_f, attn_f = algorithmic_flops(case.cfg, case.cu_seqlens)
         tokens, n_seq, max_seqlen = case.T, case.S, case.max_seqlen
         extra = {"step": "one block forward + backward (weight grads accumulated in fp32)"}
-        baseline = lambda: cpu_baseline(case)
+        run_baseline = lambda: cpu_baseline(case)
     step_flops = 3.0 * gemm_f + 3.5 * attn_f
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         dev.step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         dev.step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step = elapsed / steps * 1e3
     tflops = step_flops / (ms_per_step * 1e-3) / 1e12
 
     # per-kernel-class durations: HIP events on the launch stream, same K steps
     bm.profile_begin()
-    for _ in range(args.steps):
+    for _ in range(steps):
         dev.step()
     prof = bm.profile_end()
     torch.cuda.synchronize()
@@ -484,7 +536,7 @@ def main():
         if n == 0:
             continue
         per_launch_ms = ms / n
-        entry = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+        entry = {"ms_per_step": ms / steps, "launches_per_step": n / steps,
                  "avg_launch_us": per_launch_ms * 1e3}
         if cls.startswith("gemm") or cls.startswith("attn"):
             entry["tflops"] = work / (ms * 1e-3) / 1e12 if ms > 0 else None
@@ -504,6 +556,8 @@ def main():
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "avg_launch_us": d_ms / d_n * 1e3, "traffic": traffic}
+    if traffic is not None:
+        roofline["traffic_source"] = TRAFFIC_SOURCE.get(case.name)
     gemm_ms = sum(prof[c][0] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     gemm_work = sum(prof[c][1] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     attn_ms = prof["attn_fwd"][0] + prof["attn_bwd"][0]
@@ -511,7 +565,7 @@ def main():
 
     out = {
         "metric": "block fwd+bwd TFLOP/s + MFMA util% on packed varlen multimodal tokens (bf16)",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": case.name, "tokens": tokens, "sequences": n_seq,
@@ -525,14 +579,17 @@ def main():
         "tokens_per_s": tokens / (ms_per_step * 1e-3),
         "roofline": roofline,
         "breakdown": breakdown,
-        "measured_peaks": measured_peaks(),
-        "paper_context": PAPER_CONTEXT,
     }
-    if args.copy_calibration:
+    if peaks:
+        out["measured_peaks"] = measured_peaks()
+        out["paper_context"] = PAPER_CONTEXT
+    if copy_cal:
         copy_calibration()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = baseline()
-    print(json.dumps(out))
+    del dev
+    torch.cuda.empty_cache()
+    if baseline:
+        out["cpu_baseline"] = run_baseline()
+    return out
 
 
 if __name__ == "__main__":

@@ -13,8 +13,12 @@ from .runner import to_device
 
 
 class StageOnDevice:
-    def __init__(self, stage: synth.StageCase, device="cuda:0"):
+    def __init__(self, stage: synth.StageCase, device="cuda:0", repeat: int = 1):
+        """repeat > 1: the executor sees repeat * M microbatches (and their units), entry k being
+        the stage's microbatch k mod M -- the same read-only device buffers again (a benchmark's way
+        to a larger batch without drawing and uploading more inputs)."""
         self.stage = stage
+        self.repeat = repeat
         dt = stage.llm_cfg.dtype
         dev = lambda a: to_device(a, dt, device)
         i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
@@ -46,7 +50,8 @@ class StageOnDevice:
                                    self.g_proj_out.data_ptr() if gen else None)
         self.keep += [enc_aw, enc_ag, llm_aw, llm_ag, gen_aw, gen_ag]
 
-        mbs = (bm.Microbatch * stage.M)()
+        assert repeat == 1 or stage.M % stage.unit_size == 0
+        mbs = (bm.Microbatch * (stage.M * repeat))()
         for m, mb in enumerate(stage.microbatches):
             cu_h = np.ascontiguousarray(mb.cu_seqlens, dtype=np.int32)
             t = dict(cu_d=i32(cu_h), base=dev(mb.base), rows=i32(mb.image_rows),
@@ -55,7 +60,9 @@ class StageOnDevice:
             mbs[m] = bm.Microbatch(mb.T, len(cu_h) - 1, t["cu_d"].data_ptr(), cu_h.ctypes.data,
                                    t["base"].data_ptr(), len(mb.image_rows), t["rows"].data_ptr(),
                                    len(mb.image_last_row), t["last"].data_ptr(), t["og"].data_ptr())
-        units = (bm.Unit * len(stage.units))()
+        for m in range(stage.M, stage.M * repeat):
+            mbs[m] = mbs[m % stage.M]
+        units = (bm.Unit * (len(stage.units) * repeat))()
         for u, un in enumerate(stage.units):
             cu_h = np.ascontiguousarray(un.cu_seqlens, dtype=np.int32)
             S = len(cu_h) - 1
@@ -67,19 +74,26 @@ class StageOnDevice:
             units[u] = bm.Unit(int(cu_h[-1]), S, t["cu_d"].data_ptr(), cu_h.ctypes.data,
                                t["patches"].data_ptr(), t["gcu_d"].data_ptr(), gcu_h.ctypes.data,
                                t["lat"].data_ptr() if gen else None, t["tgt"].data_ptr() if gen else None)
+        for u in range(len(stage.units), len(stage.units) * repeat):
+            units[u] = units[u % len(stage.units)]
         self.mbs, self.units = mbs, units
         self.cfg = bm.ExecutorConfig(bm.make_desc(stage.enc_cfg), bm.make_desc(stage.llm_cfg),
                                      bm.make_desc(stage.gen_cfg if gen else stage.enc_cfg),
                                      len(stage.enc_params), len(stage.llm_params),
-                                     len(stage.gen_params) if gen else 0, stage.M, stage.unit_size,
+                                     len(stage.gen_params) if gen else 0, stage.M * repeat, stage.unit_size,
                                      stage.tokens_per_image)
-        self.loss = torch.zeros(stage.M, dtype=torch.float32, device=device)
+        self.loss = torch.zeros(stage.M * repeat, dtype=torch.float32, device=device)
         self.ex = None
         self.arena = None
         self.device = device
 
-    def create(self, enc_slots: int, llm_slots: int):
+    def create(self, enc_slots: int, llm_slots: int, M: int = None):
+        """M: run only the first M microbatches of the stage (and the units they fill)."""
         self.destroy()
+        if M is not None:
+            total = self.stage.M * self.repeat
+            assert 1 <= M <= total and (M % self.stage.unit_size == 0 or M == total)
+            self.cfg.M = M
         nbytes = bm.executor_arena_bytes(self.cfg, self.mbs, self.units, enc_slots, llm_slots)
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         off = (-self.arena.data_ptr()) % 256
