@@ -247,7 +247,20 @@ def measured_peaks():
         bm.probe_copy(src, dst, n)
     e1.record(); torch.cuda.synchronize()
     hbm = 5 * 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": hbm}
+    # the two legs on their own, over a handful of launch shapes (workgroups per CU x loads in flight)
+    word = torch.zeros(256, dtype=torch.int32, device="cuda")
+    def timed(fn):
+        fn()
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return 5.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    reads = {f"{wpc}wg_per_cu_x{u}": timed(lambda: bm.probe_read(src, n, 256 * wpc, u, word))
+             for wpc, u in ((8, 1), (8, 4), (8, 8), (16, 4), (4, 8))}
+    fills = {f"{wpc}wg_per_cu": timed(lambda: bm.probe_fill(dst, n, 256 * wpc)) for wpc in (4, 8, 16)}
+    return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": hbm, "hbm_read_gbs": max(reads.values()),
+            "hbm_write_gbs": max(fills.values()), "hbm_read_sweep_gbs": reads, "hbm_write_sweep_gbs": fills}
 
 
 def make_workload(name):

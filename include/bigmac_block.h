@@ -231,6 +231,13 @@ bm_status bm_profile_end(double* ms /* host */, double* work /* host */, int64_t
  * bm_probe_copy streams bytes (multiple of 16) from src to dst (dev), 2*bytes of HBM traffic. */
 bm_status bm_probe_mfma(int32_t blocks, int32_t iters, float* out_dev, void* hip_stream);
 bm_status bm_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+/* The two legs of the copy on their own: bm_probe_read streams bytes (multiple of 16) from
+ * src_dev and writes nothing (out_dev: 256 words of dev memory that keep the loads alive), with
+ * `blocks` workgroups of 256 threads each holding `unroll` (1, 4 or 8) 16-byte loads in flight;
+ * bm_probe_fill writes bytes to dst_dev with `blocks` workgroups. */
+bm_status bm_probe_read(const void* src_dev, size_t bytes, int32_t blocks, int32_t unroll,
+                        void* out_dev, void* hip_stream);
+bm_status bm_probe_fill(void* dst_dev, size_t bytes, int32_t blocks, void* hip_stream);
 
 /* ---- nested schedule (host only; Sec. 3.1 and the BuildSchedule figure) ------------ */
 

@@ -148,6 +148,10 @@ def lib() -> C.CDLL:
         l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.bm_probe_mfma.argtypes = [i32, i32, vp, vp]
         l.bm_probe_copy.argtypes = [vp, vp, sz, vp]
+        l.bm_probe_read.argtypes = [vp, sz, i32, i32, vp, vp]
+        l.bm_probe_fill.argtypes = [vp, sz, i32, vp]
+        l.bm_probe_read.restype = C.c_int
+        l.bm_probe_fill.restype = C.c_int
         l.bm_probe_mfma.restype = C.c_int
         l.bm_probe_copy.restype = C.c_int
         l.bm_build_schedule.argtypes = [i32] * 6 + [pi32, pi32]
@@ -452,6 +456,14 @@ def probe_copy(src, dst, nbytes, stream=None):
 
 
 PROF_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "norm", "elementwise")
+
+
+def probe_read(src, nbytes, blocks, unroll, out, stream=None):
+    _check(lib().bm_probe_read(_ptr(src), nbytes, blocks, unroll, _ptr(out), _stream() if stream is None else stream))
+
+
+def probe_fill(dst, nbytes, blocks, stream=None):
+    _check(lib().bm_probe_fill(_ptr(dst), nbytes, blocks, _stream() if stream is None else stream))
 
 
 def profile_begin():

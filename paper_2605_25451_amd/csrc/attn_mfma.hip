@@ -610,6 +610,213 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   }
 }
 
+// dK, dV at head sizes above 64, where one wavefront cannot hold both accumulators next to a
+// second resident wavefront: every 32-key block of the 128-key tile is shared by a PAIR of
+// wavefronts that sit on the same SIMD (wavefronts w and w+4 of the 512-thread workgroup).
+//   role 0 ("value" wavefront): S = Q K^T -> P = exp2(S*scale - lse), hands P to its partner
+//                               through LDS, dV += dO^T P
+//   role 1 ("key" wavefront):   dP = dO V^T, takes P, dS = P (dP - delta), dK += Q^T dS
+// Each wavefront keeps one accumulator and one of K / V in registers (about 200 registers), so
+// two are resident per SIMD and one's vector work runs under the other's MFMAs.  P travels as
+// bf16 in the operand layout: role 0 feeds exactly these values to its own MFMAs, and role 1
+// owns the same (key, query) elements in the same lanes, so the exchange is lane-private.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
+    int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
+    const float* __restrict__ delta, const int32_t* __restrict__ cuq, const int32_t* __restrict__ cu,
+    int S, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int ldd, int Tq, int Ttot, int Hkv, int group,
+    float scale, float scale_log2, int gsplit,
+    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
+  constexpr int DHL = HeadDim<DH>::DHL, KS = HeadDim<DH>::KS, NB = HeadDim<DH>::NB, NQB = BK_Q / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * DHL];
+  __shared__ __attribute__((aligned(16))) bf16_t Ps[4 * NQB * 2 * 64 * 8];   // [key block][q block][half k-step][lane] x 16 B
+  __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
+  __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
+  int seq, kt, nkt, tile_id, hk, hk_gs;
+  tile_and_head(Hkv * gsplit, &tile_id, &hk_gs);
+  hk = hk_gs / gsplit;
+  const int gs = hk_gs % gsplit;
+  const int gpart = group / gsplit;
+  if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
+  kt = nkt - 1 - kt;                                   // early key tiles see the most queries
+  const int lo = cu[seq], L = cu[seq + 1] - lo;
+  const int loq = cuq[seq], Lq = cuq[seq + 1] - loq;
+  const int kb0 = kt * BK_KEYS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int kb = wave & 3, role = wave >> 2;            // wavefronts w and w+4 share a SIMD
+  const int tid_r = tid & 255;                          // index inside the role's 256 threads
+  const int kpos = kb0 + kb * 32 + (lane & 31);         // this lane's key (column of S)
+  const int krow = min(kpos, L - 1);
+
+  // role 0 keeps K (for S), role 1 keeps V (for dP)
+  bf16x8 kvf[KS];
+  {
+    const bf16_t* p = (role == 0 ? k : v) + (size_t)(lo + krow) * ldk + hk * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kvf[ks] = load_chunk<DH>(p, ks * 2 + half);
+  }
+  f32x16 acc[NB];                                       // role 0: dV^T, role 1: dK^T (unscaled)
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+  const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
+  const int nqt = Lq > qstart ? (Lq - qstart + BK_Q - 1) / BK_Q : 0;   // no query: dk = dv = 0
+  const int iters = nqt * gpart;
+  // role 0's threads stage the Q tile, role 1's the dO tile
+  TileStage<BK_Q, DH, 256> stg;
+  float st_l = 0.f, st_d = 0.f;
+  auto fetch = [&](int it) {
+    const int hq = hk * group + gs * gpart + it / nqt;
+    const int q0 = qstart + (it % nqt) * BK_Q;
+    if (role == 0) stg.load(q + (size_t)loq * ld + hq * DH, ld, q0, Lq, tid_r);
+    else stg.load(d_o + (size_t)loq * ldo + hq * DH, ldo, q0, Lq, tid_r);
+    if (tid < BK_Q) {
+      const int qi = min(q0 + tid, Lq - 1);
+      st_l = lse[(size_t)hq * Tq + loq + qi] * LOG2E;
+      st_d = delta[(size_t)hq * Tq + loq + qi];
+    }
+  };
+  if (iters > 0) fetch(0);
+  const bf16_t* rows_src = role == 0 ? Qs : Ds;         // phase 1 operand: Q (S) or dO (dP)
+  const bf16_t* cols_src = role == 0 ? Ds : Qs;         // phase 2 operand: dO^T (dV) or Q^T (dK)
+  bf16_t* my_p = Ps + (size_t)kb * (NQB * 2 * 64 * 8) + lane * 8;
+
+  auto step = [&](int it, auto masked) {
+    constexpr bool MASKED = decltype(masked)::value;
+    __syncthreads();                                    // previous step's readers are done
+    stg.store(role == 0 ? Qs : Ds, tid_r);
+    if (tid < BK_Q) { Ls[tid] = st_l; Dl[tid] = st_d; }
+    __syncthreads();
+    if (it + 1 < iters) fetch(it + 1);
+    const int q0 = qstart + (it % nqt) * BK_Q;
+    // phase 1: X[q, key] = rows(Q or dO) . (K or V)^T for both 32-query blocks
+    f32x16 xacc[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xacc[qb][r] = 0.f;
+    {
+      constexpr int NSTEP = NQB * KS, AHEAD = 2;
+      bf16x8 fx[AHEAD + 1];
+#pragma unroll
+      for (int n = 0; n < AHEAD && n < NSTEP; ++n) fx[n] = frag_rows<DHL>(rows_src, (n / KS) * 32, n % KS, lane);
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) {
+        const int m = n + AHEAD;
+        if (m < NSTEP) fx[m % (AHEAD + 1)] = frag_rows<DHL>(rows_src, (m / KS) * 32, m % KS, lane);
+        xacc[n / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[n % (AHEAD + 1)], kvf[n % KS], xacc[n / KS], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    bf16x8 op[NQB][2];                                  // B operands of phase 2: P (role 0) or dS (role 1)
+    if (role == 0) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int qoff = qb * 32 + g * 8 + half * 4;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(Ls + qoff);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = g * 4 + e;
+            float p = __builtin_amdgcn_exp2f(fmaf(xacc[qb][r], scale_log2, -l4[e]));
+            if (MASKED) {
+              const int qi = q0 + qoff + e;
+              if (qi >= Lq || kpos >= L || (CAUSAL && kpos > qi)) p = 0.f;
+            }
+            xacc[qb][r] = p;
+          }
+        }
+        op[qb][0] = acc_to_operand(xacc[qb], 0);
+        op[qb][1] = acc_to_operand(xacc[qb], 1);
+        *reinterpret_cast<bf16x8*>(my_p + (qb * 2 + 0) * 64 * 8) = op[qb][0];
+        *reinterpret_cast<bf16x8*>(my_p + (qb * 2 + 1) * 64 * 8) = op[qb][1];
+      }
+    }
+    __syncthreads();                                    // P of this step is in LDS
+    if (role == 1) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const bf16x8 pa = *reinterpret_cast<const bf16x8*>(my_p + (qb * 2 + 0) * 64 * 8);
+        const bf16x8 pb = *reinterpret_cast<const bf16x8*>(my_p + (qb * 2 + 1) * 64 * 8);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(Dl + qb * 32 + g * 8 + half * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = g * 4 + e;
+            const float p = (float)(r < 8 ? pa[r] : pb[r - 8]);
+            xacc[qb][r] = p * (xacc[qb][r] - d4[e]);
+          }
+        }
+        op[qb][0] = acc_to_operand(xacc[qb], 0);
+        op[qb][1] = acc_to_operand(xacc[qb], 1);
+      }
+    }
+    // phase 2: acc^T[c, key] += cols(dO or Q)^T . (P or dS), transposed operands requested one pair ahead
+    {
+      constexpr int NSTEP = NQB * NB;
+      bf16x8 fr[2][2];
+      fr[0][0] = frag_cols<DHL>(cols_src, 0, 0, lane);
+      fr[0][1] = frag_cols<DHL>(cols_src, 0, 16, lane);
+#pragma unroll
+      for (int n = 0; n < NSTEP; ++n) {
+        const int qb = n / NB, j = n % NB, m = n + 1;
+        if (m < NSTEP) {
+          fr[m & 1][0] = frag_cols<DHL>(cols_src, (m % NB) * 32, (m / NB) * 32, lane);
+          fr[m & 1][1] = frag_cols<DHL>(cols_src, (m % NB) * 32, (m / NB) * 32 + 16, lane);
+        }
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n & 1][0], op[qb][0], acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n & 1][1], op[qb][1], acc[j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  // which query tiles need the mask tests: as in the single-wavefront kernel, per 32-key block
+  if (kb0 + BK_KEYS > L) {
+    for (int it = 0; it < iters; ++it) step(it, std::true_type{});
+  } else {
+    const int n_front = CAUSAL ? min(nqt, (kb * 32 + 32 + BK_Q - 1) / BK_Q) : 0;
+    const int n_whole = max(n_front, (Lq - qstart) % BK_Q ? nqt - 1 : nqt);
+    int it = 0;
+    for (int h = 0; h < gpart; ++h) {
+      int t = 0;
+      for (; t < n_front; ++t, ++it) step(it, std::true_type{});
+      for (; t < n_whole; ++t, ++it) step(it, std::false_type{});
+      for (; t < nqt; ++t, ++it) step(it, std::true_type{});
+    }
+  }
+  const float out_scale = role == 0 ? 1.0f : scale;     // dV as it is, dK times the softmax scale
+  if (kpos < L && gsplit > 1) {
+    const size_t plane = (size_t)Ttot * Hkv * DH;
+    float* pp = part + ((size_t)gs * 2 + (role == 0 ? 1 : 0)) * plane + (size_t)(lo + kpos) * (Hkv * DH) + hk * DH;
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH)
+          *reinterpret_cast<f32x4*>(pp + j * 32 + g * 8 + half * 4) =
+              f32x4{acc[j][g * 4] * out_scale, acc[j][g * 4 + 1] * out_scale, acc[j][g * 4 + 2] * out_scale,
+                    acc[j][g * 4 + 3] * out_scale};
+  } else if (kpos < L) {
+    bf16_t* pp = (role == 0 ? dv : dk) + (size_t)(lo + kpos) * ldd + hk * DH;
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc[j][g * 4 + e] * out_scale);
+        if (DH % 32 == 0 || j * 32 + g * 8 + half * 4 < DH)
+          *reinterpret_cast<bf16x4*>(pp + j * 32 + g * 8 + half * 4) = w;
+      }
+  }
+}
+
 // dQ of one 128-row query tile of one q head: walks the key tiles, scores kept as
 // S^T[key, q] as in the forward kernel.
 template <int DH, bool CAUSAL>
@@ -823,7 +1030,14 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   const int Tk = a.kv_T();
   dim3 gkv(ktiles * a.Hkv * gsplit), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
 #define BM_L(C)                                                                                  \
-  if (ktiles > 0)                                                                                \
+  if (ktiles > 0 && DH > 64)                                                                     \
+    hipLaunchKernelGGL((fa_bwd_dkdv_pair_kernel<(DH > 64 ? DH : 128), C>), gkv, dim3(512), 0, st, \
+                       (const bf16_t*)a.q,                                                       \
+                       (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
+                       (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
+                       (bf16_t*)dk, (bf16_t*)dv, ldd_kv, a.T, Tk, a.Hkv, a.Hq / a.Hkv, scale, sl2, \
+                       gsplit, part);                                                            \
+  else if (ktiles > 0)                                                                           \
     hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,    \
                        (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
                        (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \

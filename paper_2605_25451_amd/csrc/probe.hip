@@ -8,6 +8,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // 16 independent accumulator blocks per wavefront (the GEMM's register tile), no memory traffic
 __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __restrict__ out) {
@@ -35,10 +36,60 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict
     dst[i] = src[i];
 }
 
+// read-only leg: every thread keeps UNROLL 16-byte loads in flight and folds them into one
+// word, so nothing is written back (one word per workgroup at the end)
+template <int UNROLL>
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4* __restrict__ src, long n16,
+                                                         unsigned* __restrict__ out) {
+  unsigned acc = 0u;
+  const long stride = (long)gridDim.x * 256;
+  long i = (long)blockIdx.x * 256 + threadIdx.x;
+  for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+  }
+  for (; i < n16; i += stride) { const u32x4 v = src[i]; acc ^= v[0] ^ v[1] ^ v[2] ^ v[3]; }
+  if (acc == 0x9e3779b9u) out[blockIdx.x & 255] = acc;        // keeps the loads alive
+}
+
+// write-only leg
+__global__ __launch_bounds__(256) void fill_probe_kernel(u32x4* __restrict__ dst, long n16, unsigned value) {
+  const u32x4 v = {value, value, value, value};
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256)
+    __builtin_nontemporal_store(v, dst + i);
+}
+
 }  // namespace
 }  // namespace bm
 
 using namespace bm;
+
+// Read-only and write-only legs of the HBM yardstick: bm_probe_read streams bytes (multiple of 16)
+// from src with `blocks` workgroups of 256 threads, each thread holding `unroll` (1, 4 or 8)
+// 16-byte loads in flight; bm_probe_fill writes bytes to dst.  out_dev: 256 words (dev).
+extern "C" bm_status bm_probe_read(const void* src, size_t bytes, int32_t blocks, int32_t unroll,
+                                   void* out_dev, void* hip_stream) {
+  BM_ARG_CHECK(src && out_dev && bytes % 16 == 0 && blocks >= 1, "bm_probe_read: bad arguments");
+  BM_ARG_CHECK(unroll == 1 || unroll == 4 || unroll == 8, "bm_probe_read: unroll must be 1, 4 or 8");
+  const long n16 = (long)(bytes / 16);
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (unroll == 1) hipLaunchKernelGGL(read_probe_kernel<1>, dim3(blocks), dim3(256), 0, st, (const u32x4*)src, n16, (unsigned*)out_dev);
+  else if (unroll == 4) hipLaunchKernelGGL(read_probe_kernel<4>, dim3(blocks), dim3(256), 0, st, (const u32x4*)src, n16, (unsigned*)out_dev);
+  else hipLaunchKernelGGL(read_probe_kernel<8>, dim3(blocks), dim3(256), 0, st, (const u32x4*)src, n16, (unsigned*)out_dev);
+  BM_CHECK_LAUNCH("read_probe");
+  return BM_OK;
+}
+
+extern "C" bm_status bm_probe_fill(void* dst, size_t bytes, int32_t blocks, void* hip_stream) {
+  BM_ARG_CHECK(dst && bytes % 16 == 0 && blocks >= 1, "bm_probe_fill: bad arguments");
+  hipLaunchKernelGGL(fill_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, (u32x4*)dst,
+                     (long)(bytes / 16), 0x3f803f80u);
+  BM_CHECK_LAUNCH("fill_probe");
+  return BM_OK;
+}
 
 // Launches `blocks` workgroups of 4 wavefronts, each issuing iters*16 MFMAs of 32x32x16
 // (32768 flop per wavefront-MFMA).  The caller times it; flops = blocks*4*iters*16*32768.
