@@ -501,10 +501,18 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
   } else {
   // input gradient first: the activation backward then also rewrites the activation
   // output that the weight-gradient GEMM of the down projection reads
-  BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
-  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
-    BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a,
-                              c.linear_bias ? (float*)grads->b_up : nullptr, ws.colsum_ws, T, m.F, st)); }
+  GemmEpilogue down_in;
+  if (dt == BM_DTYPE_BF16 && c.act == BM_ACT_SWIGLU && !c.linear_bias &&
+      gemm_mfma_supported(GEMM_NN, dt, T, m.F, d, d, m.F, m.F, down_in)) {
+    // SwiGLU backward rides in the epilogue of this GEMM: dA never goes to memory
+    down_in.swiglu_up = sv.up; down_in.swiglu_dup = ws.dup; down_in.swiglu_a = ws.a;
+    BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, down_in, nullptr, 0, st));
+  } else {
+    BM_RETURN_IF(gemm(GEMM_NN, dt, T, m.F, d, dm, d, w->w_down, m.F, ws.da, m.F, none, nullptr, 0, st));
+    { ProfScope _p(PROF_ELEMENTWISE, (double)T * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
+      BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a,
+                                c.linear_bias ? (float*)grads->b_up : nullptr, ws.colsum_ws, T, m.F, st)); }
+  }
   BM_RETURN_IF(gemm(GEMM_TN, dt, d, m.F, T, dm, d, ws.a, m.F, grads->w_down, m.F, none, ws.gemm_ws,
                     ws.gemm_ws_bytes, st));
   // bias gradients of the down and output projections are column sums of the two

@@ -126,6 +126,13 @@ struct GemmEpilogue {
   const void* bias = nullptr;       // [N] storage dtype
   const void* residual = nullptr;   // [M, ldc] storage dtype
   int out_fp32 = 0;                 // write C as fp32 regardless of dtype (NT/NN)
+  // SwiGLU backward fused into the input-gradient GEMM of the down projection (bf16 MFMA path,
+  // NN layout): the product dA[M,N] is not stored; with the saved pre-activations
+  // up[M, 2N] = [g | u] the epilogue writes d_up[M, 2N] = [dA u silu'(g) | dA silu(g)] and the
+  // activation a[M,N] = silu(g) u (which the weight-gradient GEMM of the down projection reads).
+  const void* swiglu_up = nullptr;  // [M, 2N] storage dtype, row stride 2N
+  void* swiglu_dup = nullptr;       // [M, 2N]
+  void* swiglu_a = nullptr;         // [M, N]
 };
 
 size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype);

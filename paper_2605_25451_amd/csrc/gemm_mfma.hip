@@ -36,6 +36,7 @@ constexpr int KCH = BK / 8;     // 16-byte chunks per k-contiguous row
 struct GemmParams {
   const bf16_t* A; const bf16_t* B; void* C;
   const bf16_t* bias; const bf16_t* residual;
+  const bf16_t* sw_up = nullptr; bf16_t* sw_dup = nullptr; bf16_t* sw_a = nullptr;   // SwiGLU backward epilogue (see GemmEpilogue)
   float* partial;               // TN with splits > 1
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n, splits, k_per_split;
@@ -384,6 +385,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     if (p.bias && gn < p.N) load16(p.bias + gn, bias);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+      // SwiGLU backward epilogue: the saved g and u of this 32-row strip are requested before the
+      // strip is transposed, so their latency is paid once per strip and not once per store
+      Vec16<bf16_t> sw_g[32 / RPI], sw_u[32 / RPI];
+      if (p.sw_up) {
+#pragma unroll
+        for (int t = 0; t < 32 / RPI; ++t) {
+          const int gm = min(m0 + wm * TM + i * 32 + t * RPI + rrow, p.M - 1);
+          const bf16_t* up = p.sw_up + (size_t)gm * (2 * p.N) + min(gn, p.N - 8);
+          sw_g[t] = *reinterpret_cast<const Vec16<bf16_t>*>(up);
+          sw_u[t] = *reinterpret_cast<const Vec16<bf16_t>*>(up + p.N);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -411,6 +424,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
             }
             *reinterpret_cast<f32x4*>(c) = f32x4{c0[0] + out[0], c0[1] + out[1], c0[2] + out[2], c0[3] + out[3]};
             *reinterpret_cast<f32x4*>(c + 4) = f32x4{c1[0] + out[4], c1[1] + out[5], c1[2] + out[6], c1[3] + out[7]};
+            continue;
+          }
+          if (p.sw_up) {
+            // out = dA of 8 columns of one row: d_up and the activation instead of C
+            const size_t up_idx = (size_t)gm * (2 * p.N) + gn;
+            float dg[8], du[8], av[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float g = (float)sw_g[t].v[e], u = (float)sw_u[t].v[e];
+              const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+              const float sl = g * sig;                          // silu(g)
+              av[e] = sl * u;
+              du[e] = out[e] * sl;
+              dg[e] = out[e] * u * sig * (1.0f + g * (1.0f - sig));
+            }
+            store16(p.sw_dup + up_idx, dg);
+            store16(p.sw_dup + up_idx + p.N, du);
+            store16(p.sw_a + (size_t)gm * p.N + gn, av);
             continue;
           }
 #pragma unroll
@@ -560,6 +591,7 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
   p.out_fp32 = epi.out_fp32;
+  p.sw_up = (const bf16_t*)epi.swiglu_up; p.sw_dup = (bf16_t*)epi.swiglu_dup; p.sw_a = (bf16_t*)epi.swiglu_a;
   p.tile_group = nullptr; p.group_rows = nullptr; p.b_group_stride = 0; p.c_group_stride = 0;
   p.grid_groups = 1; p.pair_wgs0 = 0; p.second = {};
   {
