@@ -19,6 +19,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-pragma-unroll-threshold=1000000",       # the GEMM k-step is one unrolled run of 64 MFMAs
     "-Wno-unused-command-line-argument", "-Wno-unused-result", "-Wno-unused-value",
 ]
 

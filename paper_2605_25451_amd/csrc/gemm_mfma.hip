@@ -62,12 +62,12 @@ __device__ inline int kc_offset(int row, int c) {          // in bf16 elements
   return row * BK + ((c ^ ((row >> 1) & (KCH - 1))) << 3);
 }
 // transposed operand: [BK k-rows][R/8 chunks]; chunk c of k-row k sits at
-// c ^ ((k&3)<<2): a transpose read touches 4 consecutive k-rows x 32 bytes per
-// 16 lanes, and this spreads the rows of two neighbouring lane groups over
-// eight different 32-byte bank groups.
+// c ^ ((k&3)<<2) ^ (((k>>3)&1)<<1): a transpose read touches 4 consecutive k-rows x 32 bytes
+// per 16 lanes; the first term puts the 4 k-rows into different 64-byte bank windows, the
+// second moves the lane group that reads 8 k-rows further on into the other half of each.
 template <int R>
 __device__ inline int tr_offset(int k, int c) {             // in bf16 elements
-  const int pos = c ^ ((k & 3) << 2);
+  const int pos = c ^ ((k & 3) << 2) ^ (((k >> 3) & 1) << 1);
   return k * R + (pos << 3);
 }
 
@@ -94,6 +94,40 @@ __device__ inline bf16x8 kc_fragment(const bf16_t* lds, int row0, int ks, int la
   return *reinterpret_cast<const bf16x8*>(lds + kc_offset(row, c));
 }
 
+// 16(row) x 32(k) fragments of the v_mfma_f32_16x16x32_bf16 operands: lane l holds row
+// row0 + l%16 and k = k0 + (l/16)*8 .. +7.
+__device__ inline bf16x8 kc_fragment16(const bf16_t* lds, int row0, int ks32, int lane) {
+  const int row = row0 + (lane & 15);
+  const int c = ks32 * 4 + (lane >> 4);
+  return *reinterpret_cast<const bf16x8*>(lds + kc_offset(row, c));
+}
+
+template <int R>
+__device__ inline bf16x8 tr_fragment16(const bf16_t* lds, int row0, int k0, int lane) {
+  // operand stored [k][row]: the 16 lanes of group gi read a 4(k) x 16(row) block, 8 bytes each, and
+  // the transpose read hands lane s row row0 + s with 4 consecutive k; two reads give 8 k
+  const int gi = lane >> 4, s = lane & 15;
+  const int r = row0 + (s & 3) * 4;
+  const int k = k0 + gi * 8 + (s >> 2);
+  const int c = r >> 3, within = r & 7;
+  const bf16_t* p0 = lds + tr_offset<R>(k, c) + within;
+  const bf16_t* p1 = lds + tr_offset<R>(k + 4, c) + within;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p0);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p1);
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+// acc += a b^T with v_mfma_f32_16x16x32_bf16.  Written as an asm statement that ties the
+// accumulator block to the accumulation half of the register file: with 64 four-register blocks
+// the allocator otherwise keeps some of them in the other half and runs out of registers there
+// (copies between the halves inside the loop, spills).  The accumulator of a block is next
+// touched 63 MFMAs later, far beyond any wait state the instruction asks for.
+__device__ inline void mfma16(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 // ---- global -> registers -> LDS staging -----------------------------------
 // Each thread moves CH = (R*BK/8)/NT chunks of 16 bytes per slice and operand.
 // A chunk's position inside a slice never changes, so its global offset (relative
@@ -102,7 +136,7 @@ __device__ inline bf16x8 kc_fragment(const bf16_t* lds, int row0, int ks, int la
 template <int R, int NT, bool TR, bool KTAIL>
 struct Stage {
   static constexpr int CH = (R * BK / 8) / NT;
-  static constexpr int PARTS = BK / 16;          // one part per k-step of the MFMA loop
+  static constexpr int PARTS = BK / 32;          // one part per k-step (k = 32) of the MFMA loop
   static constexpr int PER = CH / PARTS;
   static_assert(CH % PARTS == 0, "tile does not split evenly over the k-steps");
   u32x4 v[CH];
@@ -207,7 +241,7 @@ template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACCUM_F32, 
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN_ = BN / WN;       // wave tile
-  constexpr int FM = TM / 32, FN = TN_ / 32;       // 32x32 fragments per wave
+  constexpr int FM = TM / 16, FN = TN_ / 16;       // 16x16 blocks per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
   constexpr int A_TILE = BM * BK, B_TILE = BN * BK;      // elements; buffers: A0 A1 B0 B1
@@ -248,13 +282,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     Bmat += (long)g * p.b_group_stride;
   }
 
-  f32x16 acc[FM][FN];
+  f32x4 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Software pipeline, two slices deep: the registers of `sa`/`sb` always hold the
   // slice after the one being multiplied.  During k-step ks of slice j, part ks of
@@ -280,7 +312,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     // difference makes the loop wait for younger loads than the one it stores
     constexpr int PA0 = Stage<BM, NT, A_TR, KTAIL>::PER, PB0 = Stage<BN, NT, B_TR, KTAIL>::PER;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < BK / 32; ++ks) {
 #pragma unroll
       for (int i = 0; i < PA0; ++i) sa.load_one(ks * PA0 + i, a_base + a_step, p.lda, kend - kbeg - BK, tid);
 #pragma unroll
@@ -298,60 +330,55 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     const bf16_t* b_lds = smem + 2 * A_TILE + cur * B_TILE;
     bf16_t* a_nxt = smem + (cur ^ 1) * A_TILE;
     bf16_t* b_nxt = smem + 2 * A_TILE + (cur ^ 1) * B_TILE;
-    // fragments of k-step ks+1 are fetched from LDS while the MFMAs of step ks run
-    bf16x8 af[2][FM], bfr[2][FN];
-    auto fetch_frags = [&](int ks, int buf) {
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int r0 = wm * TM + i * 32;
-        af[buf][i] = A_TR ? tr_fragment<BM>(a_lds, r0, ks * 16, lane) : kc_fragment(a_lds, r0, ks, lane);
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int r0 = wn * TN_ + j * 32;
-        bfr[buf][j] = B_TR ? tr_fragment<BN>(b_lds, r0, ks * 16, lane) : kc_fragment(b_lds, r0, ks, lane);
-      }
+    // Fragments.  A k-step (k = 32) is FM x FN MFMAs, row block i outermost: all FN B fragments
+    // of a step are live (two register sets: the next step's are requested while this one runs),
+    // the A fragments pass through a ring of three (the one for row block g+2 is requested when
+    // row block g starts).
+    constexpr int KS32 = BK / 32, ROWS = KS32 * FM;
+    auto a_frag = [&](int g) {
+      const int ks = g / FM, r0 = wm * TM + (g % FM) * 16;
+      return A_TR ? tr_fragment16<BM>(a_lds, r0, ks * 32, lane) : kc_fragment16(a_lds, r0, ks, lane);
     };
-    fetch_frags(0, 0);
-    // One k-step = FM*FN MFMAs.  Its memory operations -- the FM+FN fragment reads of
-    // the next k-step, the LDS parks of this step's share of slice j+1 and the global
-    // loads that re-arm the same registers with slice j+2 -- are dealt out evenly, one
-    // small group after each MFMA, and pinned there with scheduling barriers so that
-    // they issue in the shadow of the matrix pipeline instead of in bursts.
+    auto b_frag = [&](int ks, int j) {
+      const int r0 = wn * TN_ + j * 16;
+      return B_TR ? tr_fragment16<BN>(b_lds, r0, ks * 32, lane) : kc_fragment16(b_lds, r0, ks, lane);
+    };
+    bf16x8 ar[3], bfr[2][FN];
+    ar[0] = a_frag(0);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) bfr[0][j] = b_frag(0, j);
+    ar[1] = a_frag(1);
+    // The other memory operations of a k-step -- the B fragment reads of the next step, the LDS
+    // parks of this step's share of slice j+1 and the global loads that re-arm the same
+    // registers with slice j+2 -- are dealt out evenly over the MFMAs and pinned there with
+    // scheduling barriers so that they issue in the shadow of the matrix pipeline.
     constexpr int PA = Stage<BM, NT, A_TR, KTAIL>::PER, PB = Stage<BN, NT, B_TR, KTAIL>::PER;
     const bf16_t* a_g2 = a_base + (size_t)((k0 - kbeg) / BK + 2) * a_step;   // slice j+2
     const bf16_t* b_g2 = b_base + (size_t)((k0 - kbeg) / BK + 2) * b_step;
     const int k_left2 = kend - k0 - 2 * BK;
     constexpr int SLOTS = FM * FN;
+    constexpr int NOPS = FN + 2 * (PA + PB);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < KS32; ++ks) {
       const int nb = (ks + 1) & 1;
-      constexpr int NOPS = FM + FN + 2 * (PA + PB);
 #pragma unroll
       for (int t = 0; t < SLOTS; ++t) {
-        const int i = t / FN, j = t % FN;
+        const int i = t / FN, j = t % FN, g = ks * FM + i;
         // operands swapped: the accumulator holds C^T blocks (see the epilogue)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+        mfma16(acc[i][j], bfr[ks & 1][j], ar[g % 3]);
+        if (j == 0 && g + 2 < ROWS) ar[(g + 2) % 3] = a_frag(g + 2);
 #pragma unroll
         for (int o = t * NOPS / SLOTS; o < (t + 1) * NOPS / SLOTS; ++o) {
-          if (o < FM) {
-            if (ks + 1 < BK / 16) {
-              const int r0 = wm * TM + o * 32;
-              af[nb][o] = A_TR ? tr_fragment<BM>(a_lds, r0, (ks + 1) * 16, lane) : kc_fragment(a_lds, r0, ks + 1, lane);
-            }
-          } else if (o < FM + FN) {
-            if (ks + 1 < BK / 16) {
-              const int r0 = wn * TN_ + (o - FM) * 32;
-              bfr[nb][o - FM] = B_TR ? tr_fragment<BN>(b_lds, r0, (ks + 1) * 16, lane) : kc_fragment(b_lds, r0, ks + 1, lane);
-            }
-          } else if (o < FM + FN + PA) {
-            if (NEXT1) sa.store_one(ks * PA + (o - FM - FN), a_nxt, tid);
-          } else if (o < FM + FN + PA + PB) {
-            if (NEXT1) sb.store_one(ks * PB + (o - FM - FN - PA), b_nxt, tid);
-          } else if (o < FM + FN + 2 * PA + PB) {
-            if (NEXT2) sa.load_one(ks * PA + (o - FM - FN - PA - PB), a_g2, p.lda, k_left2, tid);
+          if (o < FN) {
+            if (ks + 1 < KS32) bfr[nb][o] = b_frag(ks + 1, o);
+          } else if (o < FN + PA) {
+            if (NEXT1) sa.store_one(ks * PA + (o - FN), a_nxt, tid);
+          } else if (o < FN + PA + PB) {
+            if (NEXT1) sb.store_one(ks * PB + (o - FN - PA), b_nxt, tid);
+          } else if (o < FN + 2 * PA + PB) {
+            if (NEXT2) sa.load_one(ks * PA + (o - FN - PA - PB), a_g2, p.lda, k_left2, tid);
           } else {
-            if (NEXT2) sb.load_one(ks * PB + (o - FM - FN - 2 * PA - PB), b_g2, p.ldb, k_left2, tid);
+            if (NEXT2) sb.load_one(ks * PB + (o - FN - 2 * PA - PB), b_g2, p.ldb, k_left2, tid);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -369,14 +396,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
 
   {
     // ---- epilogue.  The MFMAs ran with swapped operands, so block (i,j) holds C^T:
-    // lane = row m = l%32, registers = 4 consecutive columns n = 8g + 4*(l/32) + e.
-    // Each wavefront transposes its own 32-row strips through LDS (free after the last
+    // lane = row m = l%16, registers = 4 consecutive columns n = 4*(l/16) + e.
+    // Each wavefront transposes its own 16-row strips through LDS (free after the last
     // barrier) and then writes whole rows: 16 bytes per lane, 256 contiguous bytes per row.
     constexpr int SLD = TN_ + 4;                         // padded fp32 row: conflict-free both ways
-    float* stage = reinterpret_cast<float*>(smem_raw) + wave * (32 * SLD);
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * (16 * SLD);
     constexpr int LPR = TN_ / 8;                          // lanes per output row (8 columns each)
     constexpr int RPI = 64 / LPR;                         // rows per store instruction
-    const int m_in = lane & 31, h4 = (lane >> 5) * 4;
+    static_assert(16 % RPI == 0, "a 16-row strip must be a whole number of store instructions");
+    const int m_in = lane & 15, q4 = (lane >> 4) * 4;
     const int rcol = (lane % LPR) * 8, rrow = lane / LPR;
     const int gn = n0 + wn * TN_ + rcol;
     float bias[8];
@@ -385,13 +413,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     if (p.bias && gn < p.N) load16(p.bias + gn, bias);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      // SwiGLU backward epilogue: the saved g and u of this 32-row strip are requested before the
+      // SwiGLU backward epilogue: the saved g and u of this strip are requested before the
       // strip is transposed, so their latency is paid once per strip and not once per store
-      Vec16<bf16_t> sw_g[32 / RPI], sw_u[32 / RPI];
+      Vec16<bf16_t> sw_g[16 / RPI], sw_u[16 / RPI];
       if (p.sw_up) {
 #pragma unroll
-        for (int t = 0; t < 32 / RPI; ++t) {
-          const int gm = min(m0 + wm * TM + i * 32 + t * RPI + rrow, p.M - 1);
+        for (int t = 0; t < 16 / RPI; ++t) {
+          const int gm = min(m0 + wm * TM + i * 16 + t * RPI + rrow, p.M - 1);
           const bf16_t* up = p.sw_up + (size_t)gm * (2 * p.N) + min(gn, p.N - 8);
           sw_g[t] = *reinterpret_cast<const Vec16<bf16_t>*>(up);
           sw_u[t] = *reinterpret_cast<const Vec16<bf16_t>*>(up + p.N);
@@ -399,15 +427,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
       }
 #pragma unroll
       for (int j = 0; j < FN; ++j)
+        *reinterpret_cast<f32x4*>(stage + m_in * SLD + j * 16 + q4) = acc[i][j];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          f32x4 v = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-          *reinterpret_cast<f32x4*>(stage + m_in * SLD + j * 32 + g * 8 + h4) = v;
-        }
-#pragma unroll
-      for (int t = 0; t < 32 / RPI; ++t) {
+      for (int t = 0; t < 16 / RPI; ++t) {
         const int row = t * RPI + rrow;
-        const int gm = m0 + wm * TM + i * 32 + row;
+        const int gm = m0 + wm * TM + i * 16 + row;
         const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol);
         const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol + 4);
         if (gm < p.M && gn < p.N) {
@@ -531,7 +555,7 @@ Plan make_plan(int layout, int M, int N, int K) {
 template <int BM, int BN, int WM, int WN, bool A_TR, bool B_TR, bool ACC, bool KTAIL>
 bm_status launch_k(const GemmParams& p, hipStream_t st) {
   constexpr size_t lds_pipe = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  constexpr size_t lds_epi = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
+  constexpr size_t lds_epi = (size_t)WM * WN * 16 * (BN / WN + 4) * sizeof(float);
   constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_TR, B_TR, ACC, KTAIL>;
   static bool attr_done = false;
