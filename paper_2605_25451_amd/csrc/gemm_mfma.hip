@@ -140,8 +140,16 @@ struct Stage {
   static constexpr int PER = CH / PARTS;
   static_assert(CH % PARTS == 0, "tile does not split evenly over the k-steps");
   u32x4 v[CH];
-  uint32_t goff[CH];    // element offset from the slice base pointer
+  uint32_t goff[CH];    // byte offset from the slice base pointer
   unsigned live = 0u;   // KTAIL: bit i = chunk i lies inside the k range (else stored as zeros)
+  // LDS byte offset of chunk i = soff[i & 1] + i * SSTRIDE: from one chunk of a thread to the next
+  // the row (k-contiguous layout) or the k-row (transposed layout) advances by a fixed count that
+  // leaves the XOR swizzle alone, except for bit 3 of the k-row, which alternates when that count is 8
+  static constexpr int IROWS = TR ? NT / (R / 8) : NT / KCH;      // rows (k-rows) between chunks i and i+1
+  static constexpr int SSTRIDE = IROWS * (TR ? R : BK) * 2;
+  static constexpr bool ALT = TR && IROWS % 16 == 8;
+  static_assert(TR ? IROWS % 8 == 0 : IROWS % 16 == 0, "the chunk stride would move the swizzle");
+  uint32_t soff[ALT ? 2 : 1];
 
   // k index of chunk i inside a slice
   __device__ static inline int chunk_k(int i, int tid) {
@@ -156,12 +164,18 @@ struct Stage {
       if (TR) {            // memory [k][row]: chunk = 8 consecutive rows
         int row = (id % (R / 8)) * 8;
         if (row >= rows_left) row = 0;
-        goff[i] = (uint32_t)(id / (R / 8)) * (uint32_t)ld + (uint32_t)row;
+        goff[i] = ((uint32_t)(id / (R / 8)) * (uint32_t)ld + (uint32_t)row) * 2u;
       } else {             // memory [row][k]: chunk = 8 consecutive k
         int row = id / KCH;
         if (row >= rows_left) row = rows_left - 1;
-        goff[i] = (uint32_t)row * (uint32_t)ld + (uint32_t)(id % KCH) * 8u;
+        goff[i] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(id % KCH) * 8u) * 2u;
       }
+    }
+#pragma unroll
+    for (int i = 0; i < (ALT ? 2 : 1); ++i) {
+      const int id = tid + i * NT;
+      const int off = TR ? tr_offset<R>(id / (R / 8), id % (R / 8)) : kc_offset(id / KCH, id % KCH);
+      soff[i] = (uint32_t)(off * 2 - i * SSTRIDE);
     }
   }
 
@@ -173,19 +187,20 @@ struct Stage {
       const int kk = chunk_k(i, tid);
       const bool in = kk < k_left;
       live = (live & ~(1u << i)) | ((in ? 1u : 0u) << i);
-      if (!in) o -= TR ? (uint32_t)(kk - (k_left - 1)) * (uint32_t)ld : (uint32_t)(kk - (k_left - 8));
+      if (!in) o -= (TR ? (uint32_t)(kk - (k_left - 1)) * (uint32_t)ld : (uint32_t)(kk - (k_left - 8))) * 2u;
     }
-    v[i] = *reinterpret_cast<const u32x4*>(base + o);
+    // the empty asm keeps the widening of the 32-bit offset next to the load, where the instruction
+    // selector can fold it into the scalar-base + 32-bit-offset address form (hoisted out of the loop
+    // it becomes a 64-bit register pair and a 64-bit add per load)
+    asm volatile("" : "+v"(o));
+    v[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base) + o);
   }
 
   __device__ inline void store_one(int i, bf16_t* lds, int tid) const {
-    const int id = tid + i * NT;
-    int off;
-    if (TR) off = tr_offset<R>(id / (R / 8), id % (R / 8));
-    else off = kc_offset(id / KCH, id % KCH);
+    (void)tid;
     u32x4 val = v[i];
     if (KTAIL && !((live >> i) & 1u)) val = u32x4{0u, 0u, 0u, 0u};
-    *reinterpret_cast<u32x4*>(lds + off) = val;
+    *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(lds) + soff[ALT ? (i & 1) : 0] + i * SSTRIDE) = val;
   }
 
   __device__ inline void load(const bf16_t* __restrict__ base, int ld, int k_left, int tid) {
