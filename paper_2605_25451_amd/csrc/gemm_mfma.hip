@@ -127,6 +127,12 @@ __device__ inline bf16x8 tr_fragment16(const bf16_t* lds, int row0, int k0, int 
 __device__ inline void mfma16(f32x4& acc, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// acc = a b^T: the first product of a tile takes the constant 0 as its addend, so the accumulators
+// are never initialised by separate instructions (which the compiler, not knowing that the asm
+// statement is an MFMA, would place right in front of it without the wait states that needs)
+__device__ inline void mfma16_first(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(acc) : "v"(a), "v"(b));
+}
 
 // ---- global -> registers -> LDS staging -----------------------------------
 // Each thread moves CH = (R*BK/8)/NT chunks of 16 bytes per slice and operand.
@@ -297,11 +303,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     Bmat += (long)g * p.b_group_stride;
   }
 
-  f32x4 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[FM][FN];        // first written by the first k-step of the first slice
 
   // Software pipeline, two slices deep: the registers of `sa`/`sb` always hold the
   // slice after the one being multiplied.  During k-step ks of slice j, part ks of
@@ -339,17 +341,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   // one slice; NEXT1: the registers hold a slice to park, NEXT2: one more to fetch.
   // The flags are compile-time so that the steady-state loop body is branch-free
   // (the wait-count bookkeeping of the loads then stays exact across iterations).
-  auto slice = [&](auto next1_t, auto next2_t, int k0, int cur) {
+  // Fragments.  A k-step (k = 32) is FM x FN MFMAs, row block i outermost: all FN B fragments
+  // of a step are live (two register sets: the next step's are requested while this one runs),
+  // the A fragments pass through a ring of four (the one for row block g+2 is requested when
+  // row block g starts).  The last row block of a slice is held back: its operands are in
+  // registers, so its MFMAs run AFTER the barrier that ends the slice and cover the LDS latency
+  // of the next slice's first fragments.
+  constexpr int KS32 = BK / 32, ROWS = KS32 * FM;
+  static_assert(ROWS % 4 == 0, "the A ring continues across slices");
+  bf16x8 ar[4], bfr[2][FN];
+  auto pending_row = [&](auto&& between) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      mfma16(acc[FM - 1][j], bfr[(KS32 - 1) & 1][j], ar[(ROWS - 1) % 4]);
+      between(j);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto slice = [&](auto next1_t, auto next2_t, auto pend_t, int k0, int cur) {
     constexpr bool NEXT1 = decltype(next1_t)::value, NEXT2 = decltype(next2_t)::value;
+    constexpr bool PEND = decltype(pend_t)::value;
     const bf16_t* a_lds = smem + cur * A_TILE;
     const bf16_t* b_lds = smem + 2 * A_TILE + cur * B_TILE;
     bf16_t* a_nxt = smem + (cur ^ 1) * A_TILE;
     bf16_t* b_nxt = smem + 2 * A_TILE + (cur ^ 1) * B_TILE;
-    // Fragments.  A k-step (k = 32) is FM x FN MFMAs, row block i outermost: all FN B fragments
-    // of a step are live (two register sets: the next step's are requested while this one runs),
-    // the A fragments pass through a ring of three (the one for row block g+2 is requested when
-    // row block g starts).
-    constexpr int KS32 = BK / 32, ROWS = KS32 * FM;
     auto a_frag = [&](int g) {
       const int ks = g / FM, r0 = wm * TM + (g % FM) * 16;
       return A_TR ? tr_fragment16<BM>(a_lds, r0, ks * 32, lane) : kc_fragment16(a_lds, r0, ks, lane);
@@ -358,11 +373,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
       const int r0 = wn * TN_ + j * 16;
       return B_TR ? tr_fragment16<BN>(b_lds, r0, ks * 32, lane) : kc_fragment16(b_lds, r0, ks, lane);
     };
-    bf16x8 ar[3], bfr[2][FN];
+    // the first MFMA of the slice waits for two fragments only: keep this request order
     ar[0] = a_frag(0);
+    bfr[0][0] = b_frag(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    auto head_rest = [&](int n) {          // the other FN fragments of the head, one per call
+      if (n + 1 < FN) bfr[0][n + 1] = b_frag(0, n + 1);
+      else ar[1] = a_frag(1);
+    };
+    if (PEND) {
+      pending_row(head_rest);
+    } else {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) bfr[0][j] = b_frag(0, j);
-    ar[1] = a_frag(1);
+      for (int n = 0; n < FN; ++n) head_rest(n);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // The other memory operations of a k-step -- the B fragment reads of the next step, the LDS
     // parks of this step's share of slice j+1 and the global loads that re-arm the same
     // registers with slice j+2 -- are dealt out evenly over the MFMAs and pinned there with
@@ -371,21 +396,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     const bf16_t* a_g2 = a_base + (size_t)((k0 - kbeg) / BK + 2) * a_step;   // slice j+2
     const bf16_t* b_g2 = b_base + (size_t)((k0 - kbeg) / BK + 2) * b_step;
     const int k_left2 = kend - k0 - 2 * BK;
-    constexpr int SLOTS = FM * FN;
-    constexpr int NOPS = FN + 2 * (PA + PB);
 #pragma unroll
     for (int ks = 0; ks < KS32; ++ks) {
       const int nb = (ks + 1) & 1;
+      const bool last = ks + 1 == KS32;
+      // the last k-step has no fragments of a next step to fetch and one row block fewer to deal over
+      const int SLOTS = last ? (FM - 1) * FN : FM * FN;
+      const int FIRST = last ? FN : 0;                      // first op index of this step
+      const int NOPS = FN + 2 * (PA + PB) - FIRST;
 #pragma unroll
       for (int t = 0; t < SLOTS; ++t) {
         const int i = t / FN, j = t % FN, g = ks * FM + i;
         // operands swapped: the accumulator holds C^T blocks (see the epilogue)
-        mfma16(acc[i][j], bfr[ks & 1][j], ar[g % 3]);
-        if (j == 0 && g + 2 < ROWS) ar[(g + 2) % 3] = a_frag(g + 2);
+        if (!PEND && ks == 0) mfma16_first(acc[i][j], bfr[ks & 1][j], ar[g % 4]);   // first slice of the tile
+        else mfma16(acc[i][j], bfr[ks & 1][j], ar[g % 4]);
+        if (j == 0 && g + 2 < ROWS) ar[(g + 2) % 4] = a_frag(g + 2);
 #pragma unroll
-        for (int o = t * NOPS / SLOTS; o < (t + 1) * NOPS / SLOTS; ++o) {
+        for (int oo = t * NOPS / SLOTS; oo < (t + 1) * NOPS / SLOTS; ++oo) {
+          const int o = oo + FIRST;
           if (o < FN) {
-            if (ks + 1 < KS32) bfr[nb][o] = b_frag(ks + 1, o);
+            bfr[nb][o] = b_frag(ks + 1, o);
           } else if (o < FN + PA) {
             if (NEXT1) sa.store_one(ks * PA + (o - FN), a_nxt, tid);
           } else if (o < FN + PA + PB) {
@@ -404,10 +434,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   };
   using yes = std::integral_constant<bool, true>;
   using no = std::integral_constant<bool, false>;
-  int cur = 0, k0 = kbeg;
-  for (; k0 + 2 * BK < kend; k0 += BK, cur ^= 1) slice(yes{}, yes{}, k0, cur);
-  if (k0 + BK < kend) { slice(yes{}, no{}, k0, cur); k0 += BK; cur ^= 1; }
-  slice(no{}, no{}, k0, cur);
+  {
+    // the first slice has no row block pending; the flags of the steady-state slices are
+    // compile-time constants, so the loop body is branch-free
+    int cur = 0, k0 = kbeg;
+    if (k0 + 2 * BK < kend) {
+      slice(yes{}, yes{}, no{}, k0, cur); k0 += BK; cur ^= 1;
+      for (; k0 + 2 * BK < kend; k0 += BK, cur ^= 1) slice(yes{}, yes{}, yes{}, k0, cur);
+      slice(yes{}, no{}, yes{}, k0, cur); k0 += BK; cur ^= 1;
+      slice(no{}, no{}, yes{}, k0, cur);
+    } else if (k0 + BK < kend) {
+      slice(yes{}, no{}, no{}, k0, cur); k0 += BK; cur ^= 1;
+      slice(no{}, no{}, yes{}, k0, cur);
+    } else {
+      slice(no{}, no{}, no{}, k0, cur);
+    }
+    pending_row([](int) {});
+    // the compiler does not know that the asm statements above are MFMAs and leaves no wait states
+    // between the last of them and the epilogue's reads of the accumulators
+    asm volatile("s_nop 15\n\ts_nop 15");
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
   {
     // ---- epilogue.  The MFMAs ran with swapped operands, so block (i,j) holds C^T:
