@@ -238,6 +238,14 @@ def measured_peaks():
     bm.probe_mfma(blocks, 200, out)
     e0.record(); bm.probe_mfma(blocks, iters, out); e1.record(); torch.cuda.synchronize()
     mfma = blocks * 4 * iters * 16 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    # the same loop by instruction shape and operand data: the clock under matrix load depends on the data
+    by_data = {}
+    for shape16, sname in ((0, "32x32x16"), (1, "16x16x32")):
+        for rnd, dname in ((0, "zeros"), (1, "random")):
+            it = iters * 4 if shape16 == 0 else iters * 2
+            bm.probe_mfma_ex(blocks, 200, shape16, rnd, out)
+            e0.record(); bm.probe_mfma_ex(blocks, it, shape16, rnd, out); e1.record(); torch.cuda.synchronize()
+            by_data[f"{sname}_{dname}"] = blocks * 4 * it * (2.0 ** 19 if shape16 == 0 else 2.0 ** 20) / (e0.elapsed_time(e1) * 1e-3) / 1e12
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
     src.zero_()
@@ -259,7 +267,7 @@ def measured_peaks():
     reads = {f"{wpc}wg_per_cu_x{u}": timed(lambda: bm.probe_read(src, n, 256 * wpc, u, word))
              for wpc, u in ((8, 1), (8, 4), (8, 8), (16, 4), (4, 8))}
     fills = {f"{wpc}wg_per_cu": timed(lambda: bm.probe_fill(dst, n, 256 * wpc)) for wpc in (4, 8, 16)}
-    return {"mfma_bf16_tflops": mfma, "hbm_copy_gbs": hbm, "hbm_read_gbs": max(reads.values()),
+    return {"mfma_bf16_tflops": mfma, "mfma_bf16_tflops_by_shape_and_operands": by_data, "hbm_copy_gbs": hbm, "hbm_read_gbs": max(reads.values()),
             "hbm_write_gbs": max(fills.values()), "hbm_read_sweep_gbs": reads, "hbm_write_sweep_gbs": fills}
 
 

@@ -231,6 +231,13 @@ bm_status bm_profile_end(double* ms /* host */, double* work /* host */, int64_t
  * bm_probe_copy streams bytes (multiple of 16) from src to dst (dev), 2*bytes of HBM traffic. */
 bm_status bm_probe_mfma(int32_t blocks, int32_t iters, float* out_dev, void* hip_stream);
 bm_status bm_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+/* bm_probe_mfma with a choice of instruction shape (shape16 = 0: 32x32x16, 16 MFMAs per iteration;
+ * 1: 16x16x32, 64 per iteration: iters * 2^19 or iters * 2^20 flop per wavefront) and of operand
+ * data (random_operands = 0: zeros; 1: pseudo-random values of unit scale).  The clock the chip
+ * holds under matrix load depends on the operand data, so the rate on random operands is the
+ * ceiling that applies to real activations.  Other values of the two switches: BM_ERR_INVALID_ARG. */
+bm_status bm_probe_mfma_ex(int32_t blocks, int32_t iters, int32_t shape16, int32_t random_operands,
+                           float* out_dev, void* hip_stream);
 /* The two legs of the copy on their own: bm_probe_read streams bytes (multiple of 16) from
  * src_dev and writes nothing (out_dev: 256 words of dev memory that keep the loads alive), with
  * `blocks` workgroups of 256 threads each holding `unroll` (1, 4 or 8) 16-byte loads in flight;

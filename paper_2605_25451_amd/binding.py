@@ -148,6 +148,8 @@ def lib() -> C.CDLL:
         l.bm_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.bm_probe_mfma.argtypes = [i32, i32, vp, vp]
         l.bm_probe_copy.argtypes = [vp, vp, sz, vp]
+        l.bm_probe_mfma_ex.argtypes = [i32, i32, i32, i32, vp, vp]
+        l.bm_probe_mfma_ex.restype = C.c_int
         l.bm_probe_read.argtypes = [vp, sz, i32, i32, vp, vp]
         l.bm_probe_fill.argtypes = [vp, sz, i32, vp]
         l.bm_probe_read.restype = C.c_int
@@ -449,6 +451,10 @@ def row_scatter(dtype, src, rows_dev, dst, n, width, stream=None):
 
 def probe_mfma(blocks, iters, out, stream=None):
     _check(lib().bm_probe_mfma(blocks, iters, _ptr(out), _stream() if stream is None else stream))
+
+
+def probe_mfma_ex(blocks, iters, shape16, random_operands, out, stream=None):
+    _check(lib().bm_probe_mfma_ex(blocks, iters, shape16, random_operands, _ptr(out), _stream() if stream is None else stream))
 
 
 def probe_copy(src, dst, nbytes, stream=None):

@@ -30,6 +30,65 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __res
   if (s == -1.f) out[0] = s;      // keeps the loop alive without writing
 }
 
+// The same loop for either MFMA shape and either kind of operand data.  The clock the chip holds
+// under matrix load depends on how many operand bits toggle: operands that are all zero keep it at
+// its maximum, pseudo-random values of unit scale (what activations look like) lower it, and the
+// 16x16x32 shape (a quarter of the accumulator registers written per flop) lowers it less than
+// the 32x32x16 shape does.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ inline unsigned probe_hash(unsigned x) {
+  x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+  return x;
+}
+template <int N>
+__device__ inline void probe_operands(bf16x8 (&a)[N], bf16x8 (&b)[N], int random_operands) {
+#pragma unroll
+  for (int f = 0; f < N; ++f)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float va = 0.f, vb = 0.f;
+      if (random_operands) {
+        // sum of four uniform bytes, centred and scaled to unit variance: roughly normal
+        const unsigned h1 = probe_hash(threadIdx.x * 64 + f * 8 + e + blockIdx.x * 7919u), h2 = probe_hash(h1 + 12345u);
+        va = (((h1 & 255) + ((h1 >> 8) & 255) + ((h1 >> 16) & 255) + (h1 >> 24)) / 256.f - 2.f) * 1.73f;
+        vb = (((h2 & 255) + ((h2 >> 8) & 255) + ((h2 >> 16) & 255) + (h2 >> 24)) / 256.f - 2.f) * 1.73f;
+      }
+      a[f][e] = (bf16_t)va; b[f][e] = (bf16_t)vb;
+    }
+}
+template <int SHAPE16>
+__global__ __launch_bounds__(256) void mfma_probe_ex_kernel(int iters, int random_operands, float* __restrict__ out) {
+  float s = 0.f;
+  if (SHAPE16 == 0) {
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    bf16x8 a[4], b[4];
+    probe_operands(a, b, random_operands);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i][0];
+  } else {
+    f32x4 acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 a[8], b[8];
+    probe_operands(a, b, random_operands);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 64; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 7], b[i >> 3], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 64; ++i) s += acc[i][0];
+  }
+  if (s == -1.2345f) out[0] = s;      // keeps the loop alive without writing
+}
+
 __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src,
                                                          uint4* __restrict__ dst, long n16) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256)
@@ -97,6 +156,20 @@ extern "C" bm_status bm_probe_mfma(int32_t blocks, int32_t iters, float* out_dev
   BM_ARG_CHECK(blocks >= 1 && iters >= 1 && out_dev, "bm_probe_mfma: bad arguments");
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, iters, out_dev);
   BM_CHECK_LAUNCH("mfma_probe");
+  return BM_OK;
+}
+
+// bm_probe_mfma with a choice of MFMA shape (shape16 = 0: 32x32x16, 16 per iteration; 1: 16x16x32,
+// 64 per iteration) and of operand data (random_operands = 0: zeros, 1: pseudo-random values of unit
+// scale).  flops = blocks * 4 * iters * 2^19 (shape16 = 0) or 2^20 (shape16 = 1).
+extern "C" bm_status bm_probe_mfma_ex(int32_t blocks, int32_t iters, int32_t shape16, int32_t random_operands,
+                                      float* out_dev, void* hip_stream) {
+  BM_ARG_CHECK(blocks >= 1 && iters >= 1 && out_dev, "bm_probe_mfma_ex: bad arguments");
+  BM_ARG_CHECK((shape16 == 0 || shape16 == 1) && (random_operands == 0 || random_operands == 1),
+               "bm_probe_mfma_ex: shape16 and random_operands are 0 or 1");
+  if (shape16) hipLaunchKernelGGL(mfma_probe_ex_kernel<1>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, iters, random_operands, out_dev);
+  else hipLaunchKernelGGL(mfma_probe_ex_kernel<0>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, iters, random_operands, out_dev);
+  BM_CHECK_LAUNCH("mfma_probe_ex");
   return BM_OK;
 }
 
