@@ -29,29 +29,31 @@ PAPER_CONTEXT = ("the paper reports 1.08x-1.9x end-to-end training speedups of i
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch (fetched + written, mean over the class's launches in one step) from
-# the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, scaled by what
-# the same counters read for a plain 1 GiB copy (fetch x2.000, write x1.000).  The split-k
-# reduction that follows a weight-gradient GEMM is part of that class's launch.  Workloads
-# or classes without a summarised counter run report null.
-MIB = 1048576.0
-TRAFFIC_SOURCE = {
-    "config2_vit_large_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config2.md",
-    "config3_decoder_7b_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config3.md",
-    "config4_decoder_8b_gqa_bf16": "offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/block_fwd_bwd_config4.md",
+# HBM bytes per launch of a kernel class come from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised under profiles/: each summary ends with a JSON block "traffic_bytes_per_launch"
+# (fetched + written, counters scaled by what they read for a plain 1 GiB copy; the split-k
+# reduction that follows a weight-gradient GEMM is part of that class's launch).  They are an
+# offline measurement of the same command, not counters read in this run; workloads or classes
+# without a summarised counter run report null.
+PROFILE_OF = {
+    "config2_vit_large_bf16": "block_fwd_bwd_config2.md",
+    "config3_decoder_7b_bf16": "block_fwd_bwd_config3.md",
+    "config4_decoder_8b_gqa_bf16": "block_fwd_bwd_config4.md",
 }
-MEASURED_TRAFFIC_BYTES = {
-    "config2_vit_large_bf16": {
-        "gemm_tn": 392.4 * MIB,      # 3 launches (232.4 + 64.0) and 4 split-k reductions (60.0 + 12.0) per step
-        "gemm_nt": 236.4 * MIB,      # 164.4 fetched + 72.0 written
-        "gemm_nn": 200.4 * MIB,      # 144.4 fetched + 56.0 written
-    },
-    "config3_decoder_7b_bf16": {     # no k split at these sizes: the class is the GEMM kernel alone
-        "gemm_tn": 1666.3 * MIB,     # 1473.3 fetched + 193.0 written
-        "gemm_nt": 1360.3 * MIB,     # 1194.3 fetched + 166.0 written
-        "gemm_nn": 1259.4 * MIB,     # 1168.4 fetched + 91.0 written
-    },
-}
+
+
+def measured_traffic(case_name):
+    """(bytes per launch by class, source) from the committed profile summary, or ({}, None)."""
+    name = PROFILE_OF.get(case_name)
+    if name is None:
+        return {}, None
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        text = open(path).read()
+        block = text.split("```json traffic_bytes_per_launch", 1)[1].split("```", 1)[0]
+        return json.loads(block), f"offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/{name}"
+    except (OSError, IndexError, ValueError):
+        return {}, None
 
 
 def moe_case(seed=5, total=8192):
@@ -566,7 +568,8 @@ def bench_block(workload, steps, warmup, peaks=True, baseline=True, copy_cal=Fal
         breakdown[cls] = entry
     dom = max(breakdown, key=lambda c: breakdown[c]["ms_per_step"])
     d_ms, d_work, d_n = prof[dom]
-    traffic = MEASURED_TRAFFIC_BYTES.get(case.name, {}).get(dom)
+    traffic_by_class, traffic_source = measured_traffic(case.name)
+    traffic = traffic_by_class.get(dom)
     if dom.startswith("gemm") or dom.startswith("attn"):
         achieved = d_work / (d_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -578,7 +581,7 @@ def bench_block(workload, steps, warmup, peaks=True, baseline=True, copy_cal=Fal
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "avg_launch_us": d_ms / d_n * 1e3, "traffic": traffic}
     if traffic is not None:
-        roofline["traffic_source"] = TRAFFIC_SOURCE.get(case.name)
+        roofline["traffic_source"] = traffic_source
     gemm_ms = sum(prof[c][0] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     gemm_work = sum(prof[c][1] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     attn_ms = prof["attn_fwd"][0] + prof["attn_bwd"][0]
