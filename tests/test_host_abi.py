@@ -155,3 +155,13 @@ def test_static_workspace_entry_refuses_oversized_packs_without_a_gpu():
                                      p, p, p, ld, stream=0)
     assert e.value.status == -3
     assert "built-in workspace" in str(e.value)
+
+
+def test_mfma_yardstick_refuses_unknown_switches_without_a_gpu():
+    """bm_probe_mfma_ex checks its arguments before it launches anything."""
+    import ctypes as C
+    l = bm.lib()
+    dummy = C.c_void_p(256)                      # never dereferenced: the call is refused first
+    for blocks, iters, shape16, rnd in ((0, 1, 0, 0), (1, 0, 0, 0), (1, 1, 2, 0), (1, 1, 0, 3)):
+        assert l.bm_probe_mfma_ex(blocks, iters, shape16, rnd, dummy, None) == bm.BM_ERR_INVALID_ARG
+    assert l.bm_probe_mfma_ex(1, 1, 0, 0, None, None) == bm.BM_ERR_INVALID_ARG
