@@ -28,6 +28,10 @@ GEMM_SHAPES = [
     # and for the weight-gradient layout also a contraction of only a few rows
     (16, 1152, 1152), (1, 64, 64), (33, 200, 136), (16, 512, 2048), (640, 384, 16), (8, 64, 64),
     (64, 64, 8), (24, 3072, 4608),
+    # enough 256x256 tiles to fill the chip with a contraction of one, two, three and five k slices:
+    # every entry path of the large-tile kernel's software pipeline (its first slice, the slices
+    # that still fetch, the last two) plus a ragged last slice
+    (4096, 4096, 64), (4096, 4096, 128), (4096, 4096, 192), (4096, 4096, 328),
 ]
 
 
