@@ -405,10 +405,17 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
   }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_up : nullptr;
-    BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.UP, m.d, ws.h, m.d, w->w_up, m.d, sv.up, m.UP, e,
-                      nullptr, 0, st));
+    if (dt == BM_DTYPE_BF16 && c.act == BM_ACT_SWIGLU && !c.linear_bias && m.UP % 256 == 0 &&
+        gemm_mfma_supported(GEMM_NT, dt, T, m.UP, m.d, m.d, m.d, m.UP, e)) {
+      // the activation rides in the epilogue of the up projection: the pre-activations are not read again
+      e.swiglu_fwd_a = ws.a;
+      BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.UP, m.d, ws.h, m.d, w->w_up, m.d, sv.up, m.UP, e, nullptr, 0, st));
+    } else {
+      BM_RETURN_IF(gemm(GEMM_NT, dt, T, m.UP, m.d, ws.h, m.d, w->w_up, m.d, sv.up, m.UP, e,
+                        nullptr, 0, st));
+      { ProfScope _p(PROF_ELEMENTWISE, (double)T * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st)); }
+    }
   }
-  { ProfScope _p(PROF_ELEMENTWISE, (double)T * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, T, m.F, st)); }
   {
     GemmEpilogue e; e.bias = c.linear_bias ? w->b_down : nullptr;
     if (m.ada) {

@@ -133,6 +133,11 @@ struct GemmEpilogue {
   const void* swiglu_up = nullptr;  // [M, 2N] storage dtype, row stride 2N
   void* swiglu_dup = nullptr;       // [M, 2N]
   void* swiglu_a = nullptr;         // [M, N]
+  // SwiGLU forward fused into the up projection (bf16 MFMA path, NT layout, no bias, N a multiple of
+  // 256): C[M, N] = [g | u] is written as usual and the epilogue also writes the activation
+  // a[M, N/2] = silu(g) u, taken from the ROUNDED g and u (what a separate pass over C would read).
+  // A tile gathers its weight rows from both halves, so that g and u of a column meet in one wavefront.
+  void* swiglu_fwd_a = nullptr;     // [M, N/2]
 };
 
 size_t gemm_scratch_bytes(int layout, int M, int N, int K, int dtype);

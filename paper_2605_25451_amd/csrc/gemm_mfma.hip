@@ -37,6 +37,7 @@ struct GemmParams {
   const bf16_t* A; const bf16_t* B; void* C;
   const bf16_t* bias; const bf16_t* residual;
   const bf16_t* sw_up = nullptr; bf16_t* sw_dup = nullptr; bf16_t* sw_a = nullptr;   // SwiGLU backward epilogue (see GemmEpilogue)
+  bf16_t* swf_a = nullptr;      // SwiGLU forward epilogue (see GemmEpilogue); N = 2F
   float* partial;               // TN with splits > 1
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n, splits, k_per_split;
@@ -163,10 +164,20 @@ struct Stage {
     return TR ? id / (R / 8) : (id % KCH) * 8;
   }
   // rows_left: how many rows of the R dimension are valid from this tile's first row on
-  __device__ inline void init(int ld, int rows_left, int tid) {
+  // half > 0 (k-contiguous operand only): the tile's rows are gathered from two row ranges F rows
+  // apart -- within every run of 2*half tile rows, the first half come from row0.. and the second
+  // half from F + row0.. (the gate and the up half of a SwiGLU weight); offsets are then relative
+  // to the matrix's first row
+  __device__ inline void init(int ld, int rows_left, int tid, int half = 0, int F = 0, int row0 = 0) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int id = tid + i * NT;
+      if (!TR && half > 0) {
+        const int r = id / KCH;
+        const int row = (r / half & 1) * F + row0 + (r / (2 * half)) * half + r % half;
+        goff[i] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(id % KCH) * 8u) * 2u;
+        continue;
+      }
       if (TR) {            // memory [k][row]: chunk = 8 consecutive rows
         int row = (id % (R / 8)) * 8;
         if (row >= rows_left) row = 0;
@@ -313,10 +324,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
   Stage<BM, NT, A_TR, KTAIL> sa;
   Stage<BN, NT, B_TR, KTAIL> sb;
   sa.init(p.lda, p.M - m0, tid);
-  sb.init(p.ldb, p.N - n0, tid);
+  const bool swf = !B_TR && p.swf_a != nullptr;          // SwiGLU forward: N = 2F, a tile covers BN/2 columns of a
+  if (swf) sb.init(p.ldb, BN, tid, TN_ / 2, p.N / 2, tn * (BN / 2));
+  else sb.init(p.ldb, p.N - n0, tid);
   // slice base pointers (wave-uniform): first row of the tile at k = kbeg
   const bf16_t* a_base = A_TR ? p.A + (size_t)kbeg * p.lda + m0 : p.A + (size_t)m0 * p.lda + kbeg;
-  const bf16_t* b_base = B_TR ? Bmat + (size_t)kbeg * p.ldb + n0 : Bmat + (size_t)n0 * p.ldb + kbeg;
+  const bf16_t* b_base = B_TR ? Bmat + (size_t)kbeg * p.ldb + n0 : Bmat + (swf ? (size_t)0 : (size_t)n0 * p.ldb) + kbeg;
   const size_t a_step = A_TR ? (size_t)BK * p.lda : (size_t)BK;
   const size_t b_step = B_TR ? (size_t)BK * p.ldb : (size_t)BK;
   sa.load(a_base, p.lda, kend - kbeg, tid);
@@ -490,6 +503,39 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
 #pragma unroll
       for (int j = 0; j < FN; ++j)
         *reinterpret_cast<f32x4*>(stage + m_in * SLD + j * 16 + q4) = acc[i][j];
+      if (!A_TR && !B_TR && !ACCUM_F32 && p.swf_a) {
+        // SwiGLU forward: the strip holds g in its first TN_/2 columns and u in the others, of the
+        // same TN_/2 columns of a; a lane takes 8 of them
+        constexpr int HW = TN_ / 2, LPR2 = HW / 8, RPI2 = 64 / LPR2;
+        const int F = p.N / 2;
+        const int rcol2 = (lane % LPR2) * 8, rrow2 = lane / LPR2;
+        const int acol = tn * (BN / 2) + wn * HW + rcol2;
+#pragma unroll
+        for (int t = 0; t < (16 + RPI2 - 1) / RPI2; ++t) {
+          const int row = t * RPI2 + rrow2;
+          const int gm = m0 + wm * TM + i * 16 + row;
+          if (row < 16 && gm < p.M) {
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol2);
+            const f32x4 g1 = *reinterpret_cast<const f32x4*>(stage + row * SLD + rcol2 + 4);
+            const f32x4 u0 = *reinterpret_cast<const f32x4*>(stage + row * SLD + HW + rcol2);
+            const f32x4 u1 = *reinterpret_cast<const f32x4*>(stage + row * SLD + HW + rcol2 + 4);
+            union { u32x4 v; bf16_t h[8]; } pg, pu, pa;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              pg.h[e] = Elt<bf16_t>::from_f(e < 4 ? g0[e] : g1[e - 4]);
+              pu.h[e] = Elt<bf16_t>::from_f(e < 4 ? u0[e] : u1[e - 4]);
+              const float g = (float)pg.h[e], u = (float)pu.h[e];
+              const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+              pa.h[e] = Elt<bf16_t>::from_f(g * sig * u);
+            }
+            bf16_t* c = (bf16_t*)p.C + (size_t)gm * p.ldc + acol;
+            __builtin_nontemporal_store(pg.v, reinterpret_cast<u32x4*>(c));
+            __builtin_nontemporal_store(pu.v, reinterpret_cast<u32x4*>(c + F));
+            *reinterpret_cast<u32x4*>(p.swf_a + (size_t)gm * F + acol) = pa.v;
+          }
+        }
+        continue;
+      }
 #pragma unroll
       for (int t = 0; t < 16 / RPI; ++t) {
         const int row = t * RPI + rrow;
@@ -678,6 +724,11 @@ bm_status gemm_mfma(int layout, int M, int N, int K, const void* A, int lda, con
   p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
   p.out_fp32 = epi.out_fp32;
   p.sw_up = (const bf16_t*)epi.swiglu_up; p.sw_dup = (bf16_t*)epi.swiglu_dup; p.sw_a = (bf16_t*)epi.swiglu_a;
+  p.swf_a = (bf16_t*)epi.swiglu_fwd_a;
+  if (p.swf_a && (layout != GEMM_NT || N % 256 || epi.bias || epi.residual || epi.out_fp32)) {
+    set_error("gemm: the SwiGLU forward epilogue needs the NT layout, N a multiple of 256 and no bias");
+    return BM_ERR_INVALID_ARG;
+  }
   p.tile_group = nullptr; p.group_rows = nullptr; p.b_group_stride = 0; p.c_group_stride = 0;
   p.grid_groups = 1; p.pair_wgs0 = 0; p.second = {};
   {
