@@ -50,12 +50,15 @@ struct HeadDim {
 
 // ---- swizzled [rows][DHL] bf16 tile -----------------------------------------
 template <int DHL>
+__device__ inline int tile_swizzle(int row) {      // chunk c of a row sits in slot c ^ tile_swizzle(row)
+  if (DHL == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  if (DHL == 96) return (row >> 2) & 3;
+  const int v = row >> 1;
+  return ((v & 1) << 2) | ((v >> 1) & 3);
+}
+template <int DHL>
 __device__ inline int tile_off(int row, int c) {   // element offset of 16-byte chunk c of a row
-  int f;
-  if (DHL == 128) f = ((row & 3) << 2) | ((row >> 2) & 3);
-  else if (DHL == 96) f = (row >> 2) & 3;
-  else { const int v = row >> 1; f = ((v & 1) << 2) | ((v >> 1) & 3); }
-  return row * DHL + ((c ^ f) << 3);
+  return row * DHL + ((c ^ tile_swizzle<DHL>(row)) << 3);
 }
 
 // 8 consecutive dh values (chunk c) of a global row as an MFMA operand; zeros past dh
@@ -142,6 +145,85 @@ struct TileStage {
   }
 };
 
+// The same tile brought in by 16-byte loads that write LDS directly (no registers, no LDS store
+// instructions): lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1 KiB run of slots, so the
+// swizzle is applied on the global side -- the lane that owns slot s of a row fetches chunk
+// s ^ tile_swizzle(row).  Padding slots (head sizes that are no multiple of 32) are never written
+// by a load: zero() clears them once.  The loads are asynchronous: wait for vmcnt(0), then a
+// workgroup barrier, before any wavefront reads the tile.
+template <int ROWS, int DH, int NT>
+struct TileAsync {
+  static constexpr int DHL = HeadDim<DH>::DHL;
+  static constexpr int CPR = DHL / 8;
+  static constexpr int SLOTS = ROWS * CPR;
+  static constexpr int CH = (SLOTS + NT - 1) / NT;    // loads per thread (the last round may be short)
+  // UNI: every load of a thread has the same chunk, and rows a fixed distance apart
+  static constexpr bool UNI = NT % CPR == 0 && (NT / CPR) % 16 == 0 && SLOTS % NT == 0;
+  static constexpr int RSTEP = NT / CPR, NV = UNI ? 1 : CH;
+  static_assert(SLOTS % 64 == 0 && NT % 64 == 0, "a tile is a whole number of 1 KiB runs");
+  int r0[NV];           // tile row of a load
+  uint32_t coff[NV];    // byte offset of its chunk inside a row
+  uint32_t goff[NV];    // byte offset of the load from the tile's first row (full tiles)
+  uint32_t live;        // bit i clear: load i would fill a padding slot and is not issued
+  __device__ inline void init(int ld, int tid) {
+    live = 0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int id = tid + i * NT;
+      r0[i] = id / CPR;
+      const int c = (id % CPR) ^ tile_swizzle<DHL>(r0[i]);
+      if (id < SLOTS && (DHL == DH || c < HeadDim<DH>::VCH)) live |= 1u << i;
+      coff[i] = (uint32_t)c * 16u;
+      goff[i] = (uint32_t)r0[i] * (uint32_t)ld * 2u + coff[i];
+    }
+  }
+  // One 16-byte load per lane straight into LDS.  Written as inline assembly so that the compiler does
+  // not see an LDS write in flight: it would otherwise make every LDS read that follows wait for
+  // vmcnt(0) and the tile would no longer stream in behind the arithmetic.  The caller orders the
+  // reads of a tile after wait_async_tiles() and a barrier.
+  static __device__ inline void load16(const void* base, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+  }
+  // base: first row of the tile (wave-uniform); rows_left: valid rows from there (>= 1), rows beyond
+  // them are clamped to the last valid one (their results are masked or unused); wave: wave-uniform
+  __device__ inline void issue(const bf16_t* __restrict__ base, int ld, int rows_left, bf16_t* t,
+                               int wave) const {
+    const uint32_t dst = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)(t + wave * 512);
+    if (rows_left >= ROWS) {
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const int v = UNI ? 0 : i;
+        if ((live >> v) & 1u)
+          load16(base, goff[v] + (UNI ? (uint32_t)(i * RSTEP) * (uint32_t)ld * 2u : 0u), dst + i * NT * 16);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const int v = UNI ? 0 : i;
+        if ((live >> v) & 1u)
+          load16(base, (uint32_t)min(r0[v] + (UNI ? i * RSTEP : 0), rows_left - 1) * (uint32_t)ld * 2u + coff[v],
+                 dst + i * NT * 16);
+      }
+    }
+  }
+  static __device__ inline void zero_padding(bf16_t* t, int tid) {
+    if (DHL == DH) return;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int id = tid + i * NT;
+      const int r = id / CPR, c = (id % CPR) ^ tile_swizzle<DHL>(r);
+      if (id < SLOTS && c >= HeadDim<DH>::VCH) *reinterpret_cast<u32x4*>(t + id * 8) = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+};
+// The tile loads are invisible to the compiler's wait-count bookkeeping, so the wait for them is
+// written out as well.  A vmcnt wait that the compiler adds for one of ITS loads would also wait for
+// tile loads in flight: settle_compiler_loads() (a wait the bookkeeping does read) goes once in front
+// of a loop that streams tiles, after the kernel's ordinary loads, so that none is added inside.
+__device__ inline void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ inline void settle_compiler_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
+
 // which (sequence, tile) a linear tile id is; tiles of `rows` rows, later tiles of a
 // sequence first (under a causal mask they are the long ones)
 __device__ inline bool find_tile(const int32_t* __restrict__ cu, int S, int rows, int id, int* seq,
@@ -178,8 +260,10 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     int ldk, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk, int S,
     bf16_t* __restrict__ o, int ldo, float* __restrict__ lse, int Ttot, int Hq, int group,
     float scale_log2) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
+  // K and V tiles are double-buffered: tile kt+1 streams into LDS while tile kt is consumed
+  constexpr int TILE = FK * HeadDim<DH>::DHL;
+  __shared__ __attribute__((aligned(1024))) bf16_t Kbuf[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vbuf[2 * TILE];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
@@ -222,24 +306,37 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   const int nkt = (kend + FK - 1) / FK;
   const bf16_t* kbase = k + (size_t)lok * ldk + hk * DH;
   const bf16_t* vbase = v + (size_t)lok * ldk + hk * DH;
-  TileStage<FK, DH, 256> sk, sv;
-  sk.load(kbase, ldk, 0, Lk, tid);
-  sv.load(vbase, ldk, 0, Lk, tid);
+  using Tile = TileAsync<FK, DH, 256>;
+  Tile tile;
+  tile.init(ldk, tid);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    Tile::zero_padding(Kbuf + b * TILE, tid);
+    Tile::zero_padding(Vbuf + b * TILE, tid);
+  }
+  tile.issue(kbase, ldk, Lk, Kbuf, wave_u);
+  tile.issue(vbase, ldk, Lk, Vbuf, wave_u);
+  settle_compiler_loads();                 // the Q fragments (and, with them, tile 0)
 
   // The step comes in two copies, without and with the per-element mask test, each in a loop of
   // its own: the leading key tiles lie wholly inside the sequence (and before the diagonal under a
   // causal mask) and need no test; written as a run-time condition inside the unrolled code, the
   // test becomes compare/select pairs that every step pays for.  Every wavefront runs nkt steps
   // in total (the split may differ between wavefronts; the barrier count per step does not).
-  auto step = [&](int kt, auto masked) {
+  auto step = [&](int kt, auto masked, auto parity) {
     constexpr bool MASKED = decltype(masked)::value;
-    __syncthreads();                       // previous step's readers are done
-    sk.store(Ks, tid);
-    sv.store(Vs, tid);
+    constexpr int PAR = decltype(parity)::value;
+    const bf16_t* Ks = Kbuf + PAR * TILE;
+    const bf16_t* Vs = Vbuf + PAR * TILE;
+    // one barrier per step: tile kt has landed for every wavefront, and every wavefront is done
+    // with tile kt-1, whose buffer the loads of tile kt+1 overwrite
+    wait_async_tiles();
     __syncthreads();
     if (kt + 1 < nkt) {
-      sk.load(kbase, ldk, (kt + 1) * FK, Lk, tid);
-      sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
+      const size_t next = (size_t)(kt + 1) * FK * ldk;
+      tile.issue(kbase + next, ldk, Lk - (kt + 1) * FK, Kbuf + (1 - PAR) * TILE, wave_u);
+      tile.issue(vbase + next, ldk, Lk - (kt + 1) * FK, Vbuf + (1 - PAR) * TILE, wave_u);
     }
     const int key0 = kt * FK;
     // S^T = K Q^T for both 32-key blocks first: the MFMAs of block 1 run while the
@@ -322,9 +419,13 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
   int n_plain = Lk / FK;
   if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
   n_plain = min(n_plain, nkt);
-  int kt = 0;
-  for (; kt < n_plain; ++kt) step(kt, std::false_type{});
-  for (; kt < nkt; ++kt) step(kt, std::true_type{});
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+  for (int kt = 0; kt < nkt; ++kt) {
+    const bool plain = kt < n_plain;
+    if (kt & 1) { if (plain) step(kt, std::false_type{}, P1{}); else step(kt, std::true_type{}, P1{}); }
+    else { if (plain) step(kt, std::false_type{}, P0{}); else step(kt, std::true_type{}, P0{}); }
+  }
   lsum = sum_with_other_half(lsum);
   if (qpos < L) {
     const float inv = 1.0f / lsum;
