@@ -269,8 +269,24 @@ def measured_peaks():
     reads = {f"{wpc}wg_per_cu_x{u}": timed(lambda: bm.probe_read(src, n, 256 * wpc, u, word))
              for wpc, u in ((8, 1), (8, 4), (8, 8), (16, 4), (4, 8))}
     fills = {f"{wpc}wg_per_cu": timed(lambda: bm.probe_fill(dst, n, 256 * wpc)) for wpc in (4, 8, 16)}
+    # LDS by instruction kind (bytes per ns and CU; two workgroups of four wavefronts per CU), and what a
+    # GEMM slice's mix -- two bytes of fragment reads per byte filled -- takes with either kind of fill
+    lds_iters, per_wave = 4000, {1: 16384, 2: 16384, 4: 8192, 8: 8192, 5: 24576, 9: 24576}
+    names = {1: "read_b128", 2: "read_tr_b64", 4: "store_b128", 8: "direct_load_b128", 5: "reads_and_stores", 9: "reads_and_direct_loads"}
+    lds = {}
+    for what in (1, 2, 4, 8, 5, 9):
+        bm.probe_lds(what, 100, src, n, word)
+        e0.record(); bm.probe_lds(what, lds_iters, src, n, word); e1.record(); torch.cuda.synchronize()
+        lds[names[what]] = 2 * 4 * lds_iters * per_wave[what] / (e0.elapsed_time(e1) * 1e6)
+    # ns per group of one 32x32x16 MFMA and 0 / 4 / 8 independent vector instructions, one wavefront per SIMD
+    issue = {}
+    for nv in (0, 4, 8):
+        bm.probe_issue(nv, 100, out)
+        e0.record(); bm.probe_issue(nv, 20000, out); e1.record(); torch.cuda.synchronize()
+        issue[f"mfma_plus_{nv}_valu"] = e0.elapsed_time(e1) * 1e6 / (20000 * 4)
     return {"mfma_bf16_tflops": mfma, "mfma_bf16_tflops_by_shape_and_operands": by_data, "hbm_copy_gbs": hbm, "hbm_read_gbs": max(reads.values()),
-            "hbm_write_gbs": max(fills.values()), "hbm_read_sweep_gbs": reads, "hbm_write_sweep_gbs": fills}
+            "hbm_write_gbs": max(fills.values()), "hbm_read_sweep_gbs": reads, "hbm_write_sweep_gbs": fills,
+            "lds_bytes_per_ns_per_cu": lds, "issue_ns_per_group": issue}
 
 
 def make_workload(name):

@@ -245,6 +245,20 @@ bm_status bm_probe_mfma_ex(int32_t blocks, int32_t iters, int32_t shape16, int32
 bm_status bm_probe_read(const void* src_dev, size_t bytes, int32_t blocks, int32_t unroll,
                         void* out_dev, void* hip_stream);
 bm_status bm_probe_fill(void* dst_dev, size_t bytes, int32_t blocks, void* hip_stream);
+/* LDS yardstick (measurement contract, like the probes above).  512 workgroups of 4 wavefronts,
+ * two per CU; per wavefront and iteration, `what` -- a sum of 1: 16 KiB of row-fragment reads
+ * (ds_read_b128), 2: 16 KiB of transposed-fragment reads (ds_read_b64_tr_b16), 4: 8 KiB of LDS
+ * stores (ds_write_b128), 8: 8 KiB of 16-byte loads that write LDS directly -- moves through the
+ * LDS.  Supported: 1, 2, 4, 8, 5 and 9 (reads next to either kind of fill, the ratio of a GEMM
+ * slice).  src_dev (dev, at least 512 KiB) is read by the direct loads only and may be NULL
+ * otherwise; out_dev: one word (dev), never written.  The caller times the launch.
+ * bm_probe_issue: 256 workgroups of 4 wavefronts, iters x 4 groups of one 32x32x16 MFMA followed
+ * by n_valu (0, 4 or 8) independent vector instructions: what a group takes beyond the MFMA's
+ * 32 clocks is vector issue time that found no room beside it.
+ * Both return BM_ERR_INVALID_ARG for any other `what` / n_valu, before anything is launched. */
+bm_status bm_probe_lds(int32_t what, int32_t iters, const void* src_dev, size_t src_bytes, void* out_dev,
+                       void* hip_stream);
+bm_status bm_probe_issue(int32_t n_valu, int32_t iters, float* out_dev, void* hip_stream);
 
 /* ---- nested schedule (host only; Sec. 3.1 and the BuildSchedule figure) ------------ */
 

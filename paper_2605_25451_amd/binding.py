@@ -152,6 +152,10 @@ def lib() -> C.CDLL:
         l.bm_probe_mfma_ex.restype = C.c_int
         l.bm_probe_read.argtypes = [vp, sz, i32, i32, vp, vp]
         l.bm_probe_fill.argtypes = [vp, sz, i32, vp]
+        l.bm_probe_lds.argtypes = [i32, i32, vp, sz, vp, vp]
+        l.bm_probe_lds.restype = C.c_int
+        l.bm_probe_issue.argtypes = [i32, i32, vp, vp]
+        l.bm_probe_issue.restype = C.c_int
         l.bm_probe_read.restype = C.c_int
         l.bm_probe_fill.restype = C.c_int
         l.bm_probe_mfma.restype = C.c_int
@@ -470,6 +474,14 @@ def probe_read(src, nbytes, blocks, unroll, out, stream=None):
 
 def probe_fill(dst, nbytes, blocks, stream=None):
     _check(lib().bm_probe_fill(_ptr(dst), nbytes, blocks, _stream() if stream is None else stream))
+
+
+def probe_lds(what, iters, src, src_bytes, out, stream=None):
+    _check(lib().bm_probe_lds(what, iters, _ptr(src), src_bytes, _ptr(out), _stream() if stream is None else stream))
+
+
+def probe_issue(n_valu, iters, out, stream=None):
+    _check(lib().bm_probe_issue(n_valu, iters, _ptr(out), _stream() if stream is None else stream))
 
 
 def profile_begin():

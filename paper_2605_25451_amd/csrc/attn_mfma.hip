@@ -926,11 +926,17 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
     int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
-  // At head size 128 the dO operand of this tile's queries lives in LDS instead of registers:
-  // with it in registers the kernel spills inside the MFMA loop at two wavefronts per SIMD.
-  constexpr bool DO_LDS = DH > 72;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[FK * HeadDim<DH>::DHL];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[FK * HeadDim<DH>::DHL];
+#ifndef BM_DQ_DO_LDS
+#define BM_DQ_DO_LDS (DH > 72)
+#endif
+  // dO operand of this tile's queries: registers, or (head size 128) LDS
+  constexpr bool DO_LDS = BM_DQ_DO_LDS;
+  // K and V tiles are double-buffered and streamed into LDS as in the forward kernel; with dO in
+  // LDS as well, 32-key tiles keep two workgroups on a CU
+  constexpr int FKD = DO_LDS ? 32 : FK;
+  constexpr int TILE = FKD * HeadDim<DH>::DHL;
+  __shared__ __attribute__((aligned(1024))) bf16_t Kbuf[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vbuf[2 * TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Dos[DO_LDS ? FQ * HeadDim<DH>::DHL : 8];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
@@ -979,29 +985,40 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     for (int r = 0; r < 16; ++r) dqacc[j][r] = 0.f;
 
   const int kend = CAUSAL ? min(Lk, q0 + FQ) : Lk;
-  const int nkt = (kend + FK - 1) / FK;
+  const int nkt = (kend + FKD - 1) / FKD;
   const bf16_t* kbase = k + (size_t)lok * ldk + hk * DH;
   const bf16_t* vbase = v + (size_t)lok * ldk + hk * DH;
-  TileStage<FK, DH, 256> sk, sv;
-  sk.load(kbase, ldk, 0, Lk, tid);
-  sv.load(vbase, ldk, 0, Lk, tid);
+  using Tile = TileAsync<FKD, DH, 256>;
+  Tile tile;
+  tile.init(ldk, tid);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    Tile::zero_padding(Kbuf + b * TILE, tid);
+    Tile::zero_padding(Vbuf + b * TILE, tid);
+  }
+  tile.issue(kbase, ldk, Lk, Kbuf, wave_u);
+  tile.issue(vbase, ldk, Lk, Vbuf, wave_u);
+  settle_compiler_loads();                 // the Q and dO fragments, lse, delta (and, with them, tile 0)
   // two copies of the step, without and with the mask test, as in the forward kernel
   constexpr bool FOLD_DELTA = DH <= 64;      // dP accumulators start at -delta (see the dK/dV kernel)
-  auto step = [&](int kt, auto masked) {
+  auto step = [&](int kt, auto masked, auto parity) {
     constexpr bool MASKED = decltype(masked)::value;
-    __syncthreads();
-    sk.store(Ks, tid);
-    sv.store(Vs, tid);
-    __syncthreads();
+    constexpr int PAR = decltype(parity)::value;
+    const bf16_t* Ks = Kbuf + PAR * TILE;
+    const bf16_t* Vs = Vbuf + PAR * TILE;
+    wait_async_tiles();
+    __syncthreads();      // tile kt is there for everyone, and everyone is done with tile kt-1
     if (kt + 1 < nkt) {
-      sk.load(kbase, ldk, (kt + 1) * FK, Lk, tid);
-      sv.load(vbase, ldk, (kt + 1) * FK, Lk, tid);
+      const size_t next = (size_t)(kt + 1) * FKD * ldk;
+      tile.issue(kbase + next, ldk, Lk - (kt + 1) * FKD, Kbuf + (1 - PAR) * TILE, wave_u);
+      tile.issue(vbase + next, ldk, Lk - (kt + 1) * FKD, Vbuf + (1 - PAR) * TILE, wave_u);
     }
-    const int key0 = kt * FK;
+    const int key0 = kt * FKD;
     // S^T = K Q^T and dP^T = V dO^T of BP 32-key blocks are issued before any softmax arithmetic,
     // so that one block's MFMAs run under the other's vector work; at head size 128 that is one
     // block at a time (two sets of accumulators do not fit next to two resident wavefronts).
-    constexpr int NBLK = FK / 32, BP = DH > 72 ? 1 : NBLK, KS = HeadDim<DH>::KS;
+    constexpr int NBLK = FKD / 32, BP = DH > 72 ? 1 : NBLK, KS = HeadDim<DH>::KS;
 #pragma unroll
     for (int b0 = 0; b0 < NBLK; b0 += BP) {
       f32x16 sacc[BP], dpacc[BP];
@@ -1063,12 +1080,16 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
       }
     }
   };
-  int n_plain = Lk / FK;
-  if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FK);
+  int n_plain = Lk / FKD;
+  if (CAUSAL) n_plain = min(n_plain, (q0 + wave * 32 + 1) / FKD);
   n_plain = min(n_plain, nkt);
-  int kt = 0;
-  for (; kt < n_plain; ++kt) step(kt, std::false_type{});
-  for (; kt < nkt; ++kt) step(kt, std::true_type{});
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+  for (int kt = 0; kt < nkt; ++kt) {
+    const bool plain = kt < n_plain;
+    if (kt & 1) { if (plain) step(kt, std::false_type{}, P1{}); else step(kt, std::true_type{}, P1{}); }
+    else { if (plain) step(kt, std::false_type{}, P0{}); else step(kt, std::true_type{}, P0{}); }
+  }
   if (qpos < L) {
     bf16_t* pq = dq + (size_t)(lo + qpos) * ldd + hq * DH;
 #pragma unroll

@@ -137,3 +137,28 @@ def test_attention_matches_definition(dtype, Hq, Hkv, dh, lens, causal):
     for name, sl in (("dq", slice(0, Hq * dh)), ("dk", slice(Hq * dh, (Hq + Hkv) * dh)),
                      ("dv", slice((Hq + Hkv) * dh, W))):
         assert rel_err(got[:, sl], ref_d[:, sl]) <= tol, name
+
+
+def test_lds_and_issue_yardsticks_run_and_leave_their_buffers_alone():
+    """The measuring kernels behind bench.py's `measured_peaks` launch, finish, and write nothing:
+    the source buffer of the direct loads and the output word keep their contents."""
+    import torch
+    from paper_2605_25451_amd import binding as bm
+    src = torch.full((1 << 20,), 7, dtype=torch.uint8, device="cuda")
+    word = torch.full((4,), 5, dtype=torch.int32, device="cuda")
+    out = torch.full((4,), 3.0, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rates = {}
+    for what, nbytes in ((1, 16384), (2, 16384), (4, 8192), (8, 8192), (5, 24576), (9, 24576)):
+        print(f"probe_lds what={what}", flush=True)
+        bm.probe_lds(what, 10, src, src.numel(), word)
+        e0.record(); bm.probe_lds(what, 500, src, src.numel(), word); e1.record(); torch.cuda.synchronize()
+        rates[what] = 2 * 4 * 500 * nbytes / (e0.elapsed_time(e1) * 1e6)
+    for nv in (0, 4, 8):
+        print(f"probe_issue n_valu={nv}", flush=True)
+        bm.probe_issue(nv, 100, out)
+    torch.cuda.synchronize()
+    assert int(src.min()) == 7 and int(src.max()) == 7
+    assert word.cpu().tolist() == [5, 5, 5, 5] and out.cpu().tolist() == [3.0, 3.0, 3.0, 3.0]
+    # bytes per ns and CU: anything between a crawl and what 256 bytes per clock could give
+    assert all(5.0 < r < 1000.0 for r in rates.values()), rates

@@ -165,3 +165,20 @@ def test_mfma_yardstick_refuses_unknown_switches_without_a_gpu():
     for blocks, iters, shape16, rnd in ((0, 1, 0, 0), (1, 0, 0, 0), (1, 1, 2, 0), (1, 1, 0, 3)):
         assert l.bm_probe_mfma_ex(blocks, iters, shape16, rnd, dummy, None) == bm.BM_ERR_INVALID_ARG
     assert l.bm_probe_mfma_ex(1, 1, 0, 0, None, None) == bm.BM_ERR_INVALID_ARG
+
+
+def test_lds_and_issue_yardsticks_refuse_unknown_switches_without_a_gpu():
+    """bm_probe_lds / bm_probe_issue check their arguments before they launch anything."""
+    import ctypes as C
+    l = bm.lib()
+    dummy = C.c_void_p(16)
+    for what in (0, 3, 6, 7, 10, 16, -1):
+        assert l.bm_probe_lds(what, 1, dummy, 1 << 20, dummy, None) == bm.BM_ERR_INVALID_ARG
+    assert l.bm_probe_lds(1, 0, dummy, 1 << 20, dummy, None) == bm.BM_ERR_INVALID_ARG
+    assert l.bm_probe_lds(8, 1, None, 0, dummy, None) == bm.BM_ERR_INVALID_ARG          # direct loads need a source
+    assert l.bm_probe_lds(9, 1, dummy, 1024, dummy, None) == bm.BM_ERR_INVALID_ARG      # ... of 512 KiB
+    assert l.bm_probe_lds(1, 1, None, 0, None, None) == bm.BM_ERR_INVALID_ARG
+    for nv in (1, 2, 3, 5, 16, -4):
+        assert l.bm_probe_issue(nv, 1, dummy, None) == bm.BM_ERR_INVALID_ARG
+    assert l.bm_probe_issue(4, 0, dummy, None) == bm.BM_ERR_INVALID_ARG
+    assert l.bm_probe_issue(4, 1, None, None) == bm.BM_ERR_INVALID_ARG
