@@ -161,20 +161,23 @@ struct TileAsync {
   static constexpr bool UNI = NT % CPR == 0 && (NT / CPR) % 16 == 0 && SLOTS % NT == 0;
   static constexpr int RSTEP = NT / CPR, NV = UNI ? 1 : CH;
   static_assert(SLOTS % 64 == 0 && NT % 64 == 0, "a tile is a whole number of 1 KiB runs");
-  int r0[NV];           // tile row of a load
-  uint32_t coff[NV];    // byte offset of its chunk inside a row
-  uint32_t goff[NV];    // byte offset of the load from the tile's first row (full tiles)
-  uint32_t live;        // bit i clear: load i would fill a padding slot and is not issued
+  static constexpr bool ALL_LIVE = DHL == DH && SLOTS % NT == 0;   // no padding slot, no short round
+  uint32_t goff[NV];    // byte offset of a load from the tile's first row (full tiles)
+  int tid_;             // the thread's index among the NT that bring the tile in
+  // (row, chunk) of load i; false: it would fill a padding slot or lies past the tile
+  __device__ inline bool place(int i, int* row, int* chunk, int tid) const {
+    const int id = tid + i * NT;
+    *row = id / CPR;
+    *chunk = (id % CPR) ^ tile_swizzle<DHL>(*row);
+    return ALL_LIVE || (id < SLOTS && *chunk < HeadDim<DH>::VCH);
+  }
   __device__ inline void init(int ld, int tid) {
-    live = 0;
+    tid_ = tid;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int id = tid + i * NT;
-      r0[i] = id / CPR;
-      const int c = (id % CPR) ^ tile_swizzle<DHL>(r0[i]);
-      if (id < SLOTS && (DHL == DH || c < HeadDim<DH>::VCH)) live |= 1u << i;
-      coff[i] = (uint32_t)c * 16u;
-      goff[i] = (uint32_t)r0[i] * (uint32_t)ld * 2u + coff[i];
+      int row, c;
+      place(i, &row, &c, tid);
+      goff[i] = (uint32_t)row * (uint32_t)ld * 2u + (uint32_t)c * 16u;
     }
   }
   // One 16-byte load per lane straight into LDS.  Written as inline assembly so that the compiler does
@@ -187,23 +190,35 @@ struct TileAsync {
   }
   // base: first row of the tile (wave-uniform); rows_left: valid rows from there (>= 1), rows beyond
   // them are clamped to the last valid one (their results are masked or unused); wave: wave-uniform
-  __device__ inline void issue(const bf16_t* __restrict__ base, int ld, int rows_left, bf16_t* t,
+  __device__ inline void issue(const bf16_t* __restrict__ base_in, int ld, int rows_left, bf16_t* t,
                                int wave) const {
+    // the base goes into the asm statement as a scalar register pair: say so, wherever the caller's
+    // arithmetic left it
+    const uint64_t b64 = reinterpret_cast<uint64_t>(base_in);
+    const bf16_t* base = reinterpret_cast<const bf16_t*>(
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b64 >> 32)) << 32) |
+        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b64));
+    rows_left = __builtin_amdgcn_readfirstlane(rows_left);
     const uint32_t dst = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)(t + wave * 512);
     if (rows_left >= ROWS) {
 #pragma unroll
       for (int i = 0; i < CH; ++i) {
-        const int v = UNI ? 0 : i;
-        if ((live >> v) & 1u)
-          load16(base, goff[v] + (UNI ? (uint32_t)(i * RSTEP) * (uint32_t)ld * 2u : 0u), dst + i * NT * 16);
+        int row, c;
+        // (UNI: the distance between a thread's loads goes into the scalar base, not into a register each)
+        if (place(i, &row, &c, tid_))
+          load16(base + (UNI ? (size_t)(i * RSTEP) * ld : (size_t)0), goff[UNI ? 0 : i], dst + i * NT * 16);
       }
     } else {
+      // a cut tile (the last one of a sequence): offsets from scratch, rows clamped.  The thread index
+      // passes through an empty asm so that none of this is computed ahead of the loop and kept in
+      // registers for the one step that needs it.
+      int t_op = tid_;
+      asm volatile("" : "+v"(t_op));
 #pragma unroll
       for (int i = 0; i < CH; ++i) {
-        const int v = UNI ? 0 : i;
-        if ((live >> v) & 1u)
-          load16(base, (uint32_t)min(r0[v] + (UNI ? i * RSTEP : 0), rows_left - 1) * (uint32_t)ld * 2u + coff[v],
-                 dst + i * NT * 16);
+        int row, c;
+        if (place(i, &row, &c, t_op))
+          load16(base, (uint32_t)min(row, rows_left - 1) * (uint32_t)ld * 2u + (uint32_t)c * 16u, dst + i * NT * 16);
       }
     }
   }
@@ -730,11 +745,14 @@ __global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
     float scale, float scale_log2, int gsplit,
     float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
   constexpr int DHL = HeadDim<DH>::DHL, KS = HeadDim<DH>::KS, NB = HeadDim<DH>::NB, NQB = BK_Q / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * DHL];
-  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * DHL];
+  // Q and dO tiles are double-buffered and streamed into LDS (see TileAsync): with one workgroup
+  // per CU nothing else runs while a tile is parked between two barriers
+  constexpr int TILE = BK_Q * DHL;
+  __shared__ __attribute__((aligned(1024))) bf16_t Qbuf[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Dbuf[2 * TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Ps[4 * NQB * 2 * 64 * 8];   // [key block][q block][half k-step][lane] x 16 B
-  __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
-  __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
+  __shared__ __attribute__((aligned(16))) float Lbuf[2 * BK_Q];
+  __shared__ __attribute__((aligned(16))) float Dlbuf[2 * BK_Q];
   int seq, kt, nkt, tile_id, hk, hk_gs;
   tile_and_head(Hkv * gsplit, &tile_id, &hk_gs);
   hk = hk_gs / gsplit;
@@ -767,32 +785,45 @@ __global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
   const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
   const int nqt = Lq > qstart ? (Lq - qstart + BK_Q - 1) / BK_Q : 0;   // no query: dk = dv = 0
   const int iters = nqt * gpart;
-  // role 0's threads stage the Q tile, role 1's the dO tile
-  TileStage<BK_Q, DH, 256> stg;
+  // role 0's wavefronts bring in the Q tile, role 1's the dO tile; lse and delta of the tile's
+  // queries pass through registers of the first wavefront
+  using Tile = TileAsync<BK_Q, DH, 256>;
+  Tile tile;
+  tile.init(role == 0 ? ld : ldo, tid_r);
+  const int wave_r = __builtin_amdgcn_readfirstlane(wave & 3);
+  const int role_u = __builtin_amdgcn_readfirstlane(role);
   float st_l = 0.f, st_d = 0.f;
-  auto fetch = [&](int it) {
+  auto fetch = [&](int it, int par) {
     const int hq = hk * group + gs * gpart + it / nqt;
     const int q0 = qstart + (it % nqt) * BK_Q;
-    if (role == 0) stg.load(q + (size_t)loq * ld + hq * DH, ld, q0, Lq, tid_r);
-    else stg.load(d_o + (size_t)loq * ldo + hq * DH, ldo, q0, Lq, tid_r);
+    if (role_u == 0) tile.issue(q + ((size_t)loq + q0) * ld + hq * DH, ld, Lq - q0, Qbuf + par * TILE, wave_r);
+    else tile.issue(d_o + ((size_t)loq + q0) * ldo + hq * DH, ldo, Lq - q0, Dbuf + par * TILE, wave_r);
     if (tid < BK_Q) {
       const int qi = min(q0 + tid, Lq - 1);
-      st_l = lse[(size_t)hq * Tq + loq + qi] * LOG2E;
+      st_l = lse[(size_t)hq * Tq + loq + qi];     // used (and waited for) when the next step opens
       st_d = delta[(size_t)hq * Tq + loq + qi];
     }
   };
-  if (iters > 0) fetch(0);
-  const bf16_t* rows_src = role == 0 ? Qs : Ds;         // phase 1 operand: Q (S) or dO (dP)
-  const bf16_t* cols_src = role == 0 ? Ds : Qs;         // phase 2 operand: dO^T (dV) or Q^T (dK)
+#pragma unroll
+  for (int b = 0; b < 2; ++b) Tile::zero_padding((role == 0 ? Qbuf : Dbuf) + b * TILE, tid_r);
+  if (iters > 0) fetch(0, 0);
+  settle_compiler_loads();                              // K / V fragments, lse, delta (and, with them, tile 0)
   bf16_t* my_p = Ps + (size_t)kb * (NQB * 2 * 64 * 8) + lane * 8;
 
-  auto step = [&](int it, auto masked) {
+  auto step = [&](int it, auto masked, auto parity) {
     constexpr bool MASKED = decltype(masked)::value;
-    __syncthreads();                                    // previous step's readers are done
-    stg.store(role == 0 ? Qs : Ds, tid_r);
-    if (tid < BK_Q) { Ls[tid] = st_l; Dl[tid] = st_d; }
+    constexpr int PAR = decltype(parity)::value;
+    const bf16_t* Qs = Qbuf + PAR * TILE;
+    const bf16_t* Ds = Dbuf + PAR * TILE;
+    const float* Ls = Lbuf + PAR * BK_Q;
+    const float* Dl = Dlbuf + PAR * BK_Q;
+    const bf16_t* rows_src = role == 0 ? Qs : Ds;       // phase 1 operand: Q (S) or dO (dP)
+    const bf16_t* cols_src = role == 0 ? Ds : Qs;       // phase 2 operand: dO^T (dV) or Q^T (dK)
+    if (tid < BK_Q) { Lbuf[PAR * BK_Q + tid] = st_l * LOG2E; Dlbuf[PAR * BK_Q + tid] = st_d; }
+    // tile `it` is there for everyone, and everyone is done with tile it-1 and its P
+    wait_async_tiles();
     __syncthreads();
-    if (it + 1 < iters) fetch(it + 1);
+    if (it + 1 < iters) fetch(it + 1, 1 - PAR);
     const int q0 = qstart + (it % nqt) * BK_Q;
     // phase 1: X[q, key] = rows(Q or dO) . (K or V)^T for both 32-query blocks
     f32x16 xacc[NQB];
@@ -878,18 +909,19 @@ __global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
     }
   };
   // which query tiles need the mask tests: as in the single-wavefront kernel, per 32-key block
-  if (kb0 + BK_KEYS > L) {
-    for (int it = 0; it < iters; ++it) step(it, std::true_type{});
-  } else {
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+  auto step_of = [&](int it, bool masked) {
+    if (it & 1) { if (masked) step(it, std::true_type{}, P1{}); else step(it, std::false_type{}, P1{}); }
+    else { if (masked) step(it, std::true_type{}, P0{}); else step(it, std::false_type{}, P0{}); }
+  };
+  {
+    // (one call site per copy of the step: with two the compiler stops inlining them)
+    const bool all_masked = kb0 + BK_KEYS > L;
     const int n_front = CAUSAL ? min(nqt, (kb * 32 + 32 + BK_Q - 1) / BK_Q) : 0;
     const int n_whole = max(n_front, (Lq - qstart) % BK_Q ? nqt - 1 : nqt);
-    int it = 0;
-    for (int h = 0; h < gpart; ++h) {
-      int t = 0;
-      for (; t < n_front; ++t, ++it) step(it, std::true_type{});
-      for (; t < n_whole; ++t, ++it) step(it, std::false_type{});
-      for (; t < nqt; ++t, ++it) step(it, std::true_type{});
-    }
+    for (int it = 0, t = 0; it < iters; ++it, t = (t + 1 == nqt ? 0 : t + 1))
+      step_of(it, all_masked || t < n_front || t >= n_whole);
   }
   const float out_scale = role == 0 ? 1.0f : scale;     // dV as it is, dK times the softmax scale
   if (kpos < L && gsplit > 1) {
