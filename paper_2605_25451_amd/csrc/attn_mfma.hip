@@ -521,10 +521,12 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     float scale, float scale_log2, int gsplit,
     float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
   // cu, Ttot, ldk: the packing of the keys/values (and of dk, dv); cuq, Tq, ld: of the queries
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[BK_Q * HeadDim<DH>::DHL];
-  __shared__ __attribute__((aligned(16))) bf16_t Ds[BK_Q * HeadDim<DH>::DHL];
-  __shared__ __attribute__((aligned(16))) float Ls[BK_Q];
-  __shared__ __attribute__((aligned(16))) float Dl[BK_Q];
+  // Q and dO tiles are double-buffered and streamed into LDS (see TileAsync)
+  constexpr int TILE = BK_Q * HeadDim<DH>::DHL;
+  __shared__ __attribute__((aligned(1024))) bf16_t Qbuf[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t Dbuf[2 * TILE];
+  __shared__ __attribute__((aligned(16))) float Lbuf[2 * BK_Q];
+  __shared__ __attribute__((aligned(16))) float Dlbuf[2 * BK_Q];
   int seq, kt, nkt, tile_id, hk;
   // with gsplit > 1 a workgroup takes group/gsplit of the q heads that share this kv head
   // and leaves an fp32 partial; the (kv head, q-head part) pair plays the head's role
@@ -561,30 +563,43 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   const int qstart = CAUSAL ? (kb0 / BK_Q) * BK_Q : 0;
   const int nqt = Lq > qstart ? (Lq - qstart + BK_Q - 1) / BK_Q : 0;   // no query: dk = dv = 0
   const int iters = nqt * gpart;
-  TileStage<BK_Q, DH, 256> sq, sd;
+  using Tile = TileAsync<BK_Q, DH, 256>;
+  Tile tq, td;
+  tq.init(ld, tid);
+  td.init(ldo, tid);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   float st_l = 0.f, st_d = 0.f;
-  auto fetch = [&](int it) {
+  auto fetch = [&](int it, int par) {
     const int hq = hk * group + gs * gpart + it / nqt;
     const int q0 = qstart + (it % nqt) * BK_Q;
-    sq.load(q + (size_t)loq * ld + hq * DH, ld, q0, Lq, tid);
-    sd.load(d_o + (size_t)loq * ldo + hq * DH, ldo, q0, Lq, tid);
+    tq.issue(q + ((size_t)loq + q0) * ld + hq * DH, ld, Lq - q0, Qbuf + par * TILE, wave_u);
+    td.issue(d_o + ((size_t)loq + q0) * ldo + hq * DH, ldo, Lq - q0, Dbuf + par * TILE, wave_u);
     if (tid < BK_Q) {
       const int qi = min(q0 + tid, Lq - 1);
-      st_l = lse[(size_t)hq * Tq + loq + qi] * LOG2E;
+      st_l = lse[(size_t)hq * Tq + loq + qi];      // used (and waited for) when the next step opens
       st_d = delta[(size_t)hq * Tq + loq + qi];
     }
   };
-  if (iters > 0) fetch(0);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    Tile::zero_padding(Qbuf + b * TILE, tid);
+    Tile::zero_padding(Dbuf + b * TILE, tid);
+  }
+  if (iters > 0) fetch(0, 0);
+  settle_compiler_loads();                              // K and V fragments, lse, delta (and, with them, tile 0)
   // one step; MASKED is a compile-time copy with the per-element tests (see the forward kernel)
   constexpr bool FOLD_DELTA = DH <= 64;
-  auto step = [&](int it, auto masked) {
+  auto step = [&](int it, auto masked, auto parity) {
     constexpr bool MASKED = decltype(masked)::value;
-    __syncthreads();
-    sq.store(Qs, tid);
-    sd.store(Ds, tid);
-    if (tid < BK_Q) { Ls[tid] = st_l; Dl[tid] = st_d; }
-    __syncthreads();
-    if (it + 1 < iters) fetch(it + 1);
+    constexpr int PAR = decltype(parity)::value;
+    const bf16_t* Qs = Qbuf + PAR * TILE;
+    const bf16_t* Ds = Dbuf + PAR * TILE;
+    const float* Ls = Lbuf + PAR * BK_Q;
+    const float* Dl = Dlbuf + PAR * BK_Q;
+    if (tid < BK_Q) { Lbuf[PAR * BK_Q + tid] = st_l * LOG2E; Dlbuf[PAR * BK_Q + tid] = st_d; }
+    wait_async_tiles();
+    __syncthreads();      // tile `it` is there for everyone, and everyone is done with tile it-1
+    if (it + 1 < iters) fetch(it + 1, 1 - PAR);
     const int q0 = qstart + (it % nqt) * BK_Q;
     // S = Q K^T and dP = dO V^T for both 32-query blocks first, then per block the
     // softmax arithmetic (under the other block's MFMAs) followed by its dV / dK MFMAs.
@@ -678,17 +693,17 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   // else, per q head, the first ones under a causal mask (queries before this wavefront's last
   // key) and the last one when it is cut by the sequence end.  Every wavefront runs `iters`
   // steps; only the split between the copies differs.
-  if (kb0 + BK_KEYS > L) {
-    for (int it = 0; it < iters; ++it) step(it, std::true_type{});
-  } else {
+  {
+    // (one call site per copy of the step: with two the compiler stops inlining them)
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    const bool all_masked = kb0 + BK_KEYS > L;
     const int n_front = CAUSAL ? min(nqt, (wave * 32 + 32 + BK_Q - 1) / BK_Q) : 0;
     const int n_whole = max(n_front, (Lq - qstart) % BK_Q ? nqt - 1 : nqt);
-    int it = 0;
-    for (int h = 0; h < gpart; ++h) {
-      int t = 0;
-      for (; t < n_front; ++t, ++it) step(it, std::true_type{});
-      for (; t < n_whole; ++t, ++it) step(it, std::false_type{});
-      for (; t < nqt; ++t, ++it) step(it, std::true_type{});
+    for (int it = 0, t = 0; it < iters; ++it, t = (t + 1 == nqt ? 0 : t + 1)) {
+      const bool masked = all_masked || t < n_front || t >= n_whole;
+      if (it & 1) { if (masked) step(it, std::true_type{}, P1{}); else step(it, std::false_type{}, P1{}); }
+      else { if (masked) step(it, std::true_type{}, P0{}); else step(it, std::false_type{}, P0{}); }
     }
   }
   if (kpos < L && gsplit > 1) {
