@@ -115,37 +115,8 @@ __device__ inline bf16x8 acc_to_operand(const f32x16& a, int t) {
   return r;
 }
 
-// ---- global <-> LDS staging of a [ROWS][DH] tile by NT threads ----------------
-template <int ROWS, int DH, int NT>
-struct TileStage {
-  static constexpr int DHL = HeadDim<DH>::DHL;
-  static constexpr int CPR = DHL / 8;
-  static constexpr int CH = ROWS * CPR / NT;
-  static_assert((ROWS * CPR) % NT == 0, "tile does not split evenly over the threads");
-  u32x4 v[CH];
-  // rows beyond nrows are clamped to the last valid row (their results are masked or unused)
-  __device__ inline void load(const bf16_t* __restrict__ g, int ld, int row0, int nrows, int tid) {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int id = tid + i * NT;
-      int row = row0 + id / CPR;
-      if (row >= nrows) row = nrows - 1;
-      if (DHL == DH || id % CPR < HeadDim<DH>::VCH)
-        v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + (id % CPR) * 8);
-      else
-        v[i] = u32x4{0u, 0u, 0u, 0u};                 // padding chunks of the LDS row
-    }
-  }
-  __device__ inline void store(bf16_t* t, int tid) const {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int id = tid + i * NT;
-      *reinterpret_cast<u32x4*>(t + tile_off<DHL>(id / CPR, id % CPR)) = v[i];
-    }
-  }
-};
-
-// The same tile brought in by 16-byte loads that write LDS directly (no registers, no LDS store
+// ---- global -> LDS: a [ROWS][DH] tile brought in by NT threads -------------------
+// 16-byte loads that write LDS directly (no registers, no LDS store
 // instructions): lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1 KiB run of slots, so the
 // swizzle is applied on the global side -- the lane that owns slot s of a row fetches chunk
 // s ^ tile_swizzle(row).  Padding slots (head sizes that are no multiple of 32) are never written
@@ -973,18 +944,15 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
     int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
-#ifndef BM_DQ_DO_LDS
-#define BM_DQ_DO_LDS (DH > 72)
-#endif
-  // dO operand of this tile's queries: registers, or (head size 128) LDS
-  constexpr bool DO_LDS = BM_DQ_DO_LDS;
-  // K and V tiles are double-buffered and streamed into LDS as in the forward kernel; with dO in
-  // LDS as well, 32-key tiles keep two workgroups on a CU
-  constexpr int FKD = DO_LDS ? 32 : FK;
+  // K and V tiles are double-buffered and streamed into LDS as in the forward kernel; Q and dO of
+  // this wavefront's 32 queries stay in registers.  At head size 128 a step is one 32-key block:
+  // with two blocks' fragments and masks in flight next to Q, dO and the dQ accumulator the
+  // kernel spills at two wavefronts per SIMD.  (dO read from LDS instead, a quarter more fragment
+  // reads per key block, measured 1 % slower.)
+  constexpr int FKD = DH > 72 ? 32 : FK;
   constexpr int TILE = FKD * HeadDim<DH>::DHL;
   __shared__ __attribute__((aligned(1024))) bf16_t Kbuf[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vbuf[2 * TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Dos[DO_LDS ? FQ * HeadDim<DH>::DHL : 8];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
   if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
@@ -1007,21 +975,15 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     return;
   }
 
-  bf16x8 qf[HeadDim<DH>::KS], dof[DO_LDS ? 1 : HeadDim<DH>::KS];
+  bf16x8 qf[HeadDim<DH>::KS], dof[HeadDim<DH>::KS];
   {
     const bf16_t* qp = q + (size_t)(lo + qrow) * ld + hq * DH;
     const bf16_t* dp = d_o + (size_t)(lo + qrow) * ldo + hq * DH;
 #pragma unroll
     for (int ks = 0; ks < HeadDim<DH>::KS; ++ks) {
       qf[ks] = load_chunk<DH>(qp, ks * 2 + half);
-      if (!DO_LDS) dof[ks] = load_chunk<DH>(dp, ks * 2 + half);
+      dof[ks] = load_chunk<DH>(dp, ks * 2 + half);
     }
-  }
-  if (DO_LDS) {
-    // (visible to every wavefront after the barriers that open the first step)
-    TileStage<FQ, DH, 256> sdo;
-    sdo.load(d_o + (size_t)lo * ldo + hq * DH, ldo, q0, L, tid);
-    sdo.store(Dos, tid);
   }
   const float my_lse = lse[(size_t)hq * Ttot + lo + qrow] * LOG2E;
   const float my_delta = delta[(size_t)hq * Ttot + lo + qrow];
@@ -1076,11 +1038,10 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
       {
         // operand fragments are requested AHEAD MFMA pairs before their use (see the dK/dV kernel)
         constexpr int NSTEP = BP * KS, AHEAD = 2;
-        bf16x8 fk[AHEAD + 1], fv[AHEAD + 1], fo[AHEAD + 1];
+        bf16x8 fk[AHEAD + 1], fv[AHEAD + 1];
         auto request = [&](int n) {
           fk[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Ks, (b0 + n / KS) * 32, n % KS, lane);
           fv[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Vs, (b0 + n / KS) * 32, n % KS, lane);
-          if (DO_LDS) fo[n % (AHEAD + 1)] = frag_rows<HeadDim<DH>::DHL>(Dos, wave * 32, n % KS, lane);
         };
 #pragma unroll
         for (int n = 0; n < AHEAD && n < NSTEP; ++n) request(n);
@@ -1089,7 +1050,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
           const int bi = n / KS, ks = n % KS;
           if (n + AHEAD < NSTEP) request(n + AHEAD);
           sacc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[n % (AHEAD + 1)], qf[ks], sacc[bi], 0, 0, 0);
-          dpacc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[n % (AHEAD + 1)], DO_LDS ? fo[n % (AHEAD + 1)] : dof[DO_LDS ? 0 : ks],
+          dpacc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[n % (AHEAD + 1)], dof[ks],
                                                               dpacc[bi], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
