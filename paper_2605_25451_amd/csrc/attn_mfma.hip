@@ -210,15 +210,78 @@ struct TileAsync {
 __device__ inline void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ inline void settle_compiler_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
 
+// The order in which the tiles of the sequences are handed out: workgroups are dispatched in id
+// order, so the sequences whose tiles run longest go first and the short ones fill the tail of the
+// launch.  Built on the host from the host copy of the offsets (the same copy that sizes the grid)
+// and passed by value in the kernel arguments: nothing to allocate or copy, and a workgroup finds
+// its tile from one batch of scalar loads instead of a dependent load per sequence.  Any order
+// gives the same results, only the schedule changes.  n == 0: no table (more than 64 sequences),
+// the kernel walks the offsets in pack order.
+struct SeqOrder {
+  int n;                // positions in use, a multiple of 16
+  uint32_t w[64];       // position i: sequence index in bits 0..7, its number of tiles above
+};
+
+// cu_tiles: offsets of the side that is cut into tiles of `rows` rows; cu_cost: offsets of the side
+// a tile loops over (its running time).  sorted = false keeps the pack order: under a causal mask
+// a pack has tiles of every length whatever the order, and the long sequences' tiles all running at
+// once measured slower (their operands no longer fit the L2 of an XCD together).
+SeqOrder make_seq_order(const int32_t* cu_tiles, const int32_t* cu_cost, int S, int rows, bool sorted) {
+  SeqOrder o;
+  o.n = 0;
+  for (int i = 0; i < 64; ++i) o.w[i] = 0;          // unused positions: sequence 0, no tile
+  if (S < 1 || S > 64) return o;
+  for (int s = 0; s < S; ++s)
+    if ((cu_tiles[s + 1] - cu_tiles[s] + rows - 1) / rows >= (1 << 24)) return o;
+  unsigned char idx[64];
+  for (int i = 0; i < S; ++i) idx[i] = (unsigned char)i;
+  // stable insertion sort by descending length
+  for (int i = 1; sorted && i < S; ++i) {
+    const unsigned char x = idx[i];
+    const int lx = cu_cost[x + 1] - cu_cost[x];
+    int j = i;
+    while (j > 0 && cu_cost[idx[j - 1] + 1] - cu_cost[idx[j - 1]] < lx) { idx[j] = idx[j - 1]; --j; }
+    idx[j] = x;
+  }
+  o.n = (S + 15) / 16 * 16;
+  for (int i = 0; i < S; ++i) {
+    const int nt = (cu_tiles[idx[i] + 1] - cu_tiles[idx[i]] + rows - 1) / rows;
+    o.w[i] = ((uint32_t)nt << 8) | idx[i];
+  }
+  return o;
+}
+
 // which (sequence, tile) a linear tile id is; tiles of `rows` rows, later tiles of a
-// sequence first (under a causal mask they are the long ones)
-__device__ inline bool find_tile(const int32_t* __restrict__ cu, int S, int rows, int id, int* seq,
-                                 int* tile, int* ntiles) {
-  for (int s = 0; s < S; ++s) {
-    const int L = cu[s + 1] - cu[s];
-    const int nt = (L + rows - 1) / rows;
-    if (id < nt) { *seq = s; *tile = nt - 1 - id; *ntiles = nt; return true; }
-    id -= nt;
+// sequence first (under a causal mask they are the long ones).  Wave-uniform throughout.
+__device__ inline bool find_tile(const int32_t* __restrict__ cu, const SeqOrder& ord, int S, int rows, int id,
+                                 int* seq, int* tile, int* ntiles) {
+  if (ord.n == 0) {
+    for (int s = 0; s < S; ++s) {
+      const int L = cu[s + 1] - cu[s];
+      const int nt = (L + rows - 1) / rows;
+      if (id < nt) { *seq = s; *tile = nt - 1 - id; *ntiles = nt; return true; }
+      id -= nt;
+    }
+    return false;
+  }
+  for (int s0 = 0; s0 < ord.n; s0 += 16) {
+    uint32_t e[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) e[j] = ord.w[s0 + j];
+    int found = -1, fid = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {               // branch-free choice among the sixteen
+      const int n = (int)(e[j] >> 8);
+      const bool here = found < 0 && id < n;
+      found = here ? (int)e[j] : found;
+      fid = here ? id : fid;
+      id -= found < 0 ? n : 0;
+    }
+    if (found >= 0) {
+      const int nt = found >> 8;
+      *seq = found & 255; *tile = nt - 1 - fid; *ntiles = nt;
+      return true;
+    }
   }
   return false;
 }
@@ -245,14 +308,14 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     int ldk, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk, int S,
     bf16_t* __restrict__ o, int ldo, float* __restrict__ lse, int Ttot, int Hq, int group,
-    float scale_log2) {
+    float scale_log2, SeqOrder ord) {
   // K and V tiles are double-buffered: tile kt+1 streams into LDS while tile kt is consumed
   constexpr int TILE = FK * HeadDim<DH>::DHL;
   __shared__ __attribute__((aligned(1024))) bf16_t Kbuf[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t Vbuf[2 * TILE];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
-  if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
+  if (!find_tile(cu, ord, S, FQ, tile_id, &seq, &qt, &nqt)) return;
   const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   // keys and values may be packed on their own (a chunk of a context-parallel partition)
@@ -441,10 +504,12 @@ bm_status fwd_launch(const AttnArgs& a, void* o, float* lse, hipStream_t st) {
   dim3 grid(count_tiles(a.cu_host, a.S, FQ) * a.Hq), block(256);
   if (grid.x == 0) return BM_OK;
   const float sl2 = LOG2E / sqrtf((float)a.dh);
+  // a query tile runs as long as its sequence has keys
+  const SeqOrder ord = make_seq_order(a.cu_host, a.kv_cu_host(), a.S, FQ, !a.causal);
 #define BM_L(C)                                                                                  \
   hipLaunchKernelGGL((fa_fwd_kernel<DH, C>), grid, block, 0, st, (const bf16_t*)a.q,             \
                      (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(), a.cu_dev,      \
-                     a.kv_cu_dev(), a.S, (bf16_t*)o, a.Hq * a.dh, lse, a.T, a.Hq, a.Hq / a.Hkv, sl2)
+                     a.kv_cu_dev(), a.S, (bf16_t*)o, a.Hq * a.dh, lse, a.T, a.Hq, a.Hq / a.Hkv, sl2, ord)
   if (a.causal) BM_L(true); else BM_L(false);
 #undef BM_L
   BM_CHECK_LAUNCH("fa_fwd");
@@ -490,7 +555,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
     const float* __restrict__ delta, const int32_t* __restrict__ cuq, const int32_t* __restrict__ cu,
     int S, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int ldd, int Tq, int Ttot, int Hkv, int group,
     float scale, float scale_log2, int gsplit,
-    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
+    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */, SeqOrder ord) {
   // cu, Ttot, ldk: the packing of the keys/values (and of dk, dv); cuq, Tq, ld: of the queries
   // Q and dO tiles are double-buffered and streamed into LDS (see TileAsync)
   constexpr int TILE = BK_Q * HeadDim<DH>::DHL;
@@ -506,7 +571,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 2 : 1) void fa_bwd_dkdv_kernel(
   hk = hk_gs / gsplit;
   const int gs = hk_gs % gsplit;
   const int gpart = group / gsplit;
-  if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
+  if (!find_tile(cu, ord, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
   kt = nkt - 1 - kt;                                   // early key tiles see the most queries
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int loq = cuq[seq], Lq = cuq[seq + 1] - loq;
@@ -729,7 +794,7 @@ __global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
     const float* __restrict__ delta, const int32_t* __restrict__ cuq, const int32_t* __restrict__ cu,
     int S, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int ldd, int Tq, int Ttot, int Hkv, int group,
     float scale, float scale_log2, int gsplit,
-    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */) {
+    float* __restrict__ part /* [gsplit][2][Ttot][Hkv*DH] fp32 when gsplit > 1 */, SeqOrder ord) {
   constexpr int DHL = HeadDim<DH>::DHL, KS = HeadDim<DH>::KS, NB = HeadDim<DH>::NB, NQB = BK_Q / 32;
   // Q and dO tiles are double-buffered and streamed into LDS (see TileAsync): with one workgroup
   // per CU nothing else runs while a tile is parked between two barriers
@@ -744,7 +809,7 @@ __global__ __launch_bounds__(512, 2) void fa_bwd_dkdv_pair_kernel(
   hk = hk_gs / gsplit;
   const int gs = hk_gs % gsplit;
   const int gpart = group / gsplit;
-  if (!find_tile(cu, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
+  if (!find_tile(cu, ord, S, BK_KEYS, tile_id, &seq, &kt, &nkt)) return;
   kt = nkt - 1 - kt;                                   // early key tiles see the most queries
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int loq = cuq[seq], Lq = cuq[seq + 1] - loq;
@@ -943,7 +1008,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int ld,
     int ldk, const bf16_t* __restrict__ d_o, int ldo, const float* __restrict__ lse,
     const float* __restrict__ delta, const int32_t* __restrict__ cu, const int32_t* __restrict__ cuk,
-    int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2) {
+    int S, bf16_t* __restrict__ dq, int ldd, int Ttot, int Hq, int group, float scale, float scale_log2,
+    SeqOrder ord) {
   // K and V tiles are double-buffered and streamed into LDS as in the forward kernel; Q and dO of
   // this wavefront's 32 queries stay in registers.  At head size 128 a step is one 32-key block:
   // with two blocks' fragments and masks in flight next to Q, dO and the dQ accumulator the
@@ -955,7 +1021,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(
   __shared__ __attribute__((aligned(1024))) bf16_t Vbuf[2 * TILE];
   int seq, qt, nqt, tile_id, hq;
   tile_and_head(Hq, &tile_id, &hq);
-  if (!find_tile(cu, S, FQ, tile_id, &seq, &qt, &nqt)) return;
+  if (!find_tile(cu, ord, S, FQ, tile_id, &seq, &qt, &nqt)) return;
   const int hk = hq / group;
   const int lo = cu[seq], L = cu[seq + 1] - lo;
   const int lok = cuk[seq], Lk = cuk[seq + 1] - lok;
@@ -1159,6 +1225,9 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
   float* part = delta + align_up((size_t)a.Hq * a.T, 64);      // after the delta plane
   const int Tk = a.kv_T();
   dim3 gkv(ktiles * a.Hkv * gsplit), gq(count_tiles(a.cu_host, a.S, FQ) * a.Hq);
+  // a key tile runs as long as its sequence has queries, a query tile as long as it has keys
+  const SeqOrder ord_kv = make_seq_order(a.kv_cu_host(), a.cu_host, a.S, BK_KEYS, !a.causal);
+  const SeqOrder ord_q = make_seq_order(a.cu_host, a.kv_cu_host(), a.S, FQ, !a.causal);
 #define BM_L(C)                                                                                  \
   if (ktiles > 0 && DH > 64)                                                                     \
     hipLaunchKernelGGL((fa_bwd_dkdv_pair_kernel<(DH > 64 ? DH : 128), C>), gkv, dim3(512), 0, st, \
@@ -1166,18 +1235,18 @@ bm_status bwd_launch(const AttnArgs& a, const void* o, const void* d_o, const fl
                        (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
                        (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
                        (bf16_t*)dk, (bf16_t*)dv, ldd_kv, a.T, Tk, a.Hkv, a.Hq / a.Hkv, scale, sl2, \
-                       gsplit, part);                                                            \
+                       gsplit, part, ord_kv);                                                    \
   else if (ktiles > 0)                                                                           \
     hipLaunchKernelGGL((fa_bwd_dkdv_kernel<DH, C>), gkv, dim3(256), 0, st, (const bf16_t*)a.q,    \
                        (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
                        (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
                        (bf16_t*)dk, (bf16_t*)dv, ldd_kv, a.T, Tk, a.Hkv, a.Hq / a.Hkv, scale, sl2, \
-                       gsplit, part);                                                            \
+                       gsplit, part, ord_kv);                                                    \
   if (gq.x > 0)                                                                                  \
     hipLaunchKernelGGL((fa_bwd_dq_kernel<DH, C>), gq, dim3(256), 0, st, (const bf16_t*)a.q,      \
                        (const bf16_t*)a.k, (const bf16_t*)a.v, a.ld_qkv, a.kv_ld(),              \
                        (const bf16_t*)d_o, ldo, lse, delta, a.cu_dev, a.kv_cu_dev(), a.S,        \
-                       (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2)
+                       (bf16_t*)dq, ldd, a.T, a.Hq, a.Hq / a.Hkv, scale, sl2, ord_q)
   if (a.causal) { BM_L(true); } else { BM_L(false); }
 #undef BM_L
   if (gsplit > 1 && ktiles > 0) {
