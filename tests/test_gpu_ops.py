@@ -82,6 +82,15 @@ ATTN_CASES = [
     (synth.DTYPE_BF16, 2, 2, 72, [256, 256, 100], 0),
     (synth.DTYPE_BF16, 4, 2, 72, [130, 77, 1], 1),
     (synth.DTYPE_BF16, 2, 1, 128, [2049], 1),
+    # many sequences: the tile walk takes its order from a 64-entry table read 16 positions at a
+    # time (longest sequences first without a mask, pack order under a causal one) and walks the
+    # offsets themselves past 64 sequences
+    (synth.DTYPE_BF16, 2, 2, 64, [40 + 13 * (i % 7) for i in range(16)], 0),
+    (synth.DTYPE_BF16, 2, 1, 64, [150 - 8 * i for i in range(17)], 1),
+    (synth.DTYPE_BF16, 2, 2, 64, [1 + (37 * i) % 131 for i in range(64)], 0),
+    (synth.DTYPE_BF16, 2, 2, 128, [1 + (53 * i) % 140 for i in range(33)], 1),
+    (synth.DTYPE_BF16, 2, 2, 64, [1 + (29 * i) % 97 for i in range(70)], 0),
+    (synth.DTYPE_BF16, 2, 1, 72, [130 if i == 40 else 9 + i % 5 for i in range(65)], 1),
 ]
 
 
