@@ -145,7 +145,10 @@ bm_status norm_forward(const NormArgs& a, const void* x, void* h, float* stats, 
 // gradient written here (the bias gradients of the two neighbouring linear
 // layers, whose output gradients these are).  With h_out the normalised row is
 // written again for the weight-gradient GEMM that follows.
-constexpr int NORM_BWD_MAX_BLOCKS = 768;
+// (grid cap: every workgroup ends with a fixed-order combine of its wavefronts and leaves NP
+// partial rows, so narrow rows want few workgroups; wide rows, whose wavefronts hold many registers,
+// want more of them in flight)
+constexpr int NORM_BWD_MAX_BLOCKS = 768, NORM_BWD_MAX_BLOCKS_WIDE = 1024;
 
 template <int KIND, bool SUMS> struct NormBwdParts {
   static constexpr int NP = (KIND == BM_NORM_LAYERNORM ? 2 : KIND == BM_NORM_RMSNORM ? 1 : 0) + (SUMS ? 2 : 0);
@@ -536,10 +539,14 @@ bm_status segment_gate(int dtype, const void* a, const void* b, const float* gat
   return seg_launch<0>(dtype, p, S, scratch, st);
 }
 
-static int norm_bwd_blocks(int T) { int b = cdiv(T, 4); return b < NORM_BWD_MAX_BLOCKS ? b : NORM_BWD_MAX_BLOCKS; }
+static int norm_bwd_blocks(int T, int d) {
+  const int cap = d >= 2048 ? NORM_BWD_MAX_BLOCKS_WIDE : NORM_BWD_MAX_BLOCKS;
+  const int b = cdiv(T, 4);
+  return b < cap ? b : cap;
+}
 
 size_t norm_backward_scratch_bytes(int T, int d) {
-  return align_up((size_t)norm_bwd_blocks(T) * 4 * d * sizeof(float), 256) + segment_scratch_bytes();
+  return align_up((size_t)norm_bwd_blocks(T, d) * 4 * d * sizeof(float), 256) + segment_scratch_bytes();
 }
 
 template <typename T, int KIND, bool SUMS>
@@ -548,7 +555,7 @@ static bm_status norm_bwd_dispatch(const NormArgs& a, const void* x, const float
                                    float* partial, hipStream_t st) {
   constexpr int VEC = Elt<T>::VEC;
   int nv = cdiv(a.d, WAVE * VEC);
-  dim3 grid(norm_bwd_blocks(a.T));
+  dim3 grid(norm_bwd_blocks(a.T, a.d));
   size_t lds = (size_t)a.d * sizeof(float);
 #define BM_LAUNCH_NV(NVV, SP)                                                                    \
   hipLaunchKernelGGL((norm_bwd_kernel<T, KIND, NVV, SUMS, SP>), grid, dim3(NormBwdWaves<NVV>::N * 64), lds, st, (const T*)x,   \
@@ -591,7 +598,7 @@ bm_status norm_backward(const NormArgs& a, const void* x, const float* stats, co
 #undef BM_KIND
 #undef BM_KIND2
   BM_RETURN_IF(rc);
-  const int nb = norm_bwd_blocks(a.T);
+  const int nb = norm_bwd_blocks(a.T, a.d);
   if (a.kind == BM_NORM_ADALN) {
     SegArgs p{};
     p.a = dh; p.b = x; p.stats = stats; p.cu = cu_dev; p.out = dmod; p.ld_out = a.ld_mod;
