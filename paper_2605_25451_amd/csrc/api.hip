@@ -90,7 +90,8 @@ bm_status gemm_tn_pair(int dtype, int K, int M0, int N0, const void* A0, int lda
 }
 
 bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
-                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st) {
+                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st,
+                       const GemmEpilogue* epi) {
   if (M <= 0 || N <= 0) return BM_OK;
   const int rows = layout == GEMM_TN ? K : M;
   if (rows % MOE_PAD) { set_error("grouped gemm: %d rows are not a multiple of %d", rows, MOE_PAD); return BM_ERR_INVALID_ARG; }
@@ -102,7 +103,8 @@ bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A
   const double rows_used = g.routed_rows > 0 ? (double)g.routed_rows : (double)rows;
   ProfScope prof(PROF_GEMM_NT + layout, layout == GEMM_TN ? 2.0 * M * N * rows_used : 2.0 * rows_used * N * K, st);
   if (gemm_mfma_grouped_supported(layout, dtype, M, N, K, lda, ldb, ldc))
-    return gemm_mfma_grouped(layout, M, N, K, A, lda, B, ldb, C, ldc, g, st);
+    return gemm_mfma_grouped(layout, M, N, K, A, lda, B, ldb, C, ldc, g, st, epi);
+  if (epi) { set_error("grouped gemm: an epilogue needs the MFMA path"); return BM_ERR_UNSUPPORTED; }
   return gemm_generic_grouped(layout, dtype, M, N, K, A, lda, B, ldb, C, ldc, g, st);
 }
 

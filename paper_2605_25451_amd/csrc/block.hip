@@ -396,8 +396,15 @@ extern "C" bm_status bm_block_forward(const bm_block_desc* desc, const bm_block_
       BM_RETURN_IF(moe_gather(dt, ws.h, sv.moe, 0, ws.xp, m.d, T, st));
     }
     g.b_stride = (long)m.UP * m.d;
-    BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.UP, m.d, ws.xp, m.d, w->w_up, m.d, sv.up, m.UP, g, st));
-    { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, m.cap, m.F, st)); }
+    if (c.act == BM_ACT_SWIGLU && m.UP % 256 == 0 &&
+        gemm_mfma_grouped_supported(GEMM_NT, dt, m.cap, m.UP, m.d, m.d, m.d, m.UP)) {
+      // the activation rides in the epilogue of the experts' up projections
+      GemmEpilogue e; e.swiglu_fwd_a = ws.a;
+      BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.UP, m.d, ws.xp, m.d, w->w_up, m.d, sv.up, m.UP, g, st, &e));
+    } else {
+      BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.UP, m.d, ws.xp, m.d, w->w_up, m.d, sv.up, m.UP, g, st));
+      { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (m.UP + m.F) * (double)m.es, st); BM_RETURN_IF(act_forward(dt, c.act, sv.up, ws.a, m.cap, m.F, st)); }
+    }
     g.b_stride = (long)m.d * m.F;
     BM_RETURN_IF(gemm_grouped(GEMM_NT, dt, m.cap, m.d, m.F, ws.a, m.F, w->w_down, m.F, sv.moe_y, m.d, g, st));
     { ProfScope _p(PROF_ELEMENTWISE, 0.0, st); BM_RETURN_IF(moe_combine(dt, sv.moe_y, sv.moe, 1, sv.x1, y, T, m.k, m.d, st)); }
@@ -482,9 +489,16 @@ extern "C" bm_status bm_block_backward(const bm_block_desc* desc, const bm_block
       BM_RETURN_IF(moe_router_backward(dt, dm, sv.moe_y, sv.moe, ws.dlogits, T, m.E, m.k, d, st));
     }
     g.b_stride = (long)d * m.F;
-    BM_RETURN_IF(gemm_grouped(GEMM_NN, dt, m.cap, m.F, d, ws.dyp, d, w->w_down, m.F, ws.da, m.F, g, st));
-    { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
-      BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a, nullptr, ws.colsum_ws, m.cap, m.F, st)); }
+    if (c.act == BM_ACT_SWIGLU && m.F % 256 == 0 &&
+        gemm_mfma_grouped_supported(GEMM_NN, dt, m.cap, m.F, d, d, m.F, m.F)) {
+      // SwiGLU backward in the epilogue of the experts' input-gradient GEMM: dA never goes to memory
+      GemmEpilogue e; e.swiglu_up = sv.up; e.swiglu_dup = ws.dup; e.swiglu_a = ws.a;
+      BM_RETURN_IF(gemm_grouped(GEMM_NN, dt, m.cap, m.F, d, ws.dyp, d, w->w_down, m.F, ws.da, m.F, g, st, &e));
+    } else {
+      BM_RETURN_IF(gemm_grouped(GEMM_NN, dt, m.cap, m.F, d, ws.dyp, d, w->w_down, m.F, ws.da, m.F, g, st));
+      { ProfScope _p(PROF_ELEMENTWISE, (double)m.cap * (2.0 * m.UP + 2.0 * m.F) * (double)m.es, st);
+        BM_RETURN_IF(act_backward(dt, c.act, sv.up, ws.da, ws.dup, ws.a, nullptr, ws.colsum_ws, m.cap, m.F, st)); }
+    }
     g.c_stride = (long)d * m.F;
     BM_RETURN_IF(gemm_grouped(GEMM_TN, dt, d, m.F, m.cap, ws.dyp, d, ws.a, m.F, grads->w_down, m.F, g, st));
     g.b_stride = (long)m.UP * d;

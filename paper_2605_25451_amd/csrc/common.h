@@ -172,11 +172,15 @@ size_t gemm_mfma_tn_pair_scratch_bytes(int K, int M0, int N0, int M1, int N1);
 bool gemm_mfma_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0,
                        int M1, int N1, const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1,
                        void* scratch, size_t scratch_bytes, hipStream_t st, bm_status* rc);
+// epi (MFMA path only, the caller checks gemm_mfma_grouped_supported): the SwiGLU epilogues of
+// GemmEpilogue, forward on NT (N a multiple of 256) and backward on NN (N a multiple of 256)
 bm_status gemm_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
-                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st);
+                       const void* B, int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st,
+                       const GemmEpilogue* epi = nullptr);
 bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int lda, int ldb, int ldc);
 bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int lda, const void* B,
-                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st);
+                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st,
+                            const GemmEpilogue* epi = nullptr);
 bm_status gemm_generic_grouped(int layout, int dtype, int M, int N, int K, const void* A, int lda,
                                const void* B, int ldb, void* C, int ldc, const GemmGroups& g,
                                hipStream_t st);

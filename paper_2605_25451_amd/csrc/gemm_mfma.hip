@@ -855,7 +855,8 @@ bool gemm_mfma_grouped_supported(int layout, int dtype, int M, int N, int K, int
 
 // 128x128 tiles: a row tile is one MOE_PAD block, so it never straddles two groups.
 bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int lda, const void* B,
-                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st) {
+                            int ldb, void* C, int ldc, const GemmGroups& g, hipStream_t st,
+                            const GemmEpilogue* epi) {
   static_assert(MOE_PAD == 128, "the grouped path uses 128-row tiles");
   GemmParams p;
   p.A = (const bf16_t*)A; p.B = (const bf16_t*)B; p.C = C;
@@ -867,6 +868,18 @@ bm_status gemm_mfma_grouped(int layout, int M, int N, int K, const void* A, int 
   p.group_rows = layout == GEMM_TN ? g.group_rows : nullptr;
   p.b_group_stride = g.b_stride; p.c_group_stride = g.c_stride;
   p.grid_groups = layout == GEMM_TN ? g.n_groups : 1;
+  if (epi) {
+    // the SwiGLU epilogues ride on the 128x256 tiles (a tile gathers its weight rows per expert
+    // exactly as the dense kernel does per matrix)
+    const bool fwd = epi->swiglu_fwd_a != nullptr, bwd = epi->swiglu_up != nullptr;
+    if (epi->bias || epi->residual || epi->out_fp32 || fwd == bwd || N % 256 || (fwd && layout != GEMM_NT) ||
+        (bwd && (layout != GEMM_NN || !epi->swiglu_dup || !epi->swiglu_a))) {
+      set_error("grouped gemm: only the SwiGLU epilogues (forward on NT, backward on NN, N a multiple of 256)");
+      return BM_ERR_INVALID_ARG;
+    }
+    p.sw_up = (const bf16_t*)epi->swiglu_up; p.sw_dup = (bf16_t*)epi->swiglu_dup; p.sw_a = (bf16_t*)epi->swiglu_a;
+    p.swf_a = (bf16_t*)epi->swiglu_fwd_a;
+  }
   if ((layout == GEMM_TN ? p.group_rows == nullptr || g.n_groups < 1 : p.tile_group == nullptr)) {
     set_error("grouped gemm: group tables are NULL");
     return BM_ERR_INVALID_ARG;
