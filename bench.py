@@ -598,6 +598,11 @@ def bench_block(workload, steps, warmup, peaks=True, baseline=True, copy_cal=Fal
                     "avg_launch_us": d_ms / d_n * 1e3, "traffic": traffic}
     if traffic is not None:
         roofline["traffic_source"] = traffic_source
+        if dom.startswith("gemm"):
+            # the counter sits below the eight per-XCD L2s: an operand panel is fetched once by every
+            # L2 whose tiles use it, and fetches that the memory-side cache serves are counted too
+            roofline["traffic_note"] = ("FETCH_SIZE counts fetches below the per-XCD L2 caches "
+                                        "(operand panels re-fetched per XCD, memory-side cache hits included)")
     gemm_ms = sum(prof[c][0] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     gemm_work = sum(prof[c][1] for c in ("gemm_nt", "gemm_nn", "gemm_tn"))
     attn_ms = prof["attn_fwd"][0] + prof["attn_bwd"][0]
